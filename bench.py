@@ -1,0 +1,229 @@
+"""Throughput of the fused gossip + Adam (+ accumulate) step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+
+A "step" is one iteration t of the decentralized accumulated Adam algorithm over the whole
+workload: one call of dadam_gossip_step (all rows, all elements) followed by the exchange of the
+ping-pong parameter buffers.  Inputs (parameters, a small pool of pre-generated gradient sets,
+zero moments) are resident in HBM before the timed region starts.  Prints ONE JSON line.
+
+The default workload is BASELINE configuration 2 (16 replicas, static exponential graph,
+GPT-2-small tensor shapes, float32, s = 4); --config selects 1..5.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_BYTES_PER_S = 8.0e12   # MI355X HBM3E, published peak
+
+
+def phase_of(t: int, s: int) -> str:
+    if s == 1:
+        return "alg1"
+    if t % s == 0:
+        return "fold"
+    if (t - 1) % s == 0:
+        return "loopstart"
+    return "plain"
+
+
+def algorithmic_bytes_per_replica_param(wl, phase: str) -> float:
+    """Every distinct input read once, every output written once (per updated element)."""
+    px = 2 if wl.param_dtype == "bf16" else 4
+    pg = 2 if wl.grad_dtype == "bf16" else 4
+    src = px * wl.n_cols / wl.n_rows      # each source buffer is one datum however many rows read it
+    common = src + px + pg + 4 + 4        # x read, x written, g, m_hat, v_hat read
+    if phase == "alg1":
+        return common + 8                 # moments written back, no accumulator
+    if phase == "plain":
+        return common + 4 + 4             # b read, b written
+    if phase == "loopstart":
+        return common + 4                 # b written only
+    if phase == "fold":
+        return common + 4 + 4 + 8         # b read, b written (zero), moments written
+    raise ValueError(phase)
+
+
+def cpu_baseline(wl, x0_sample, grad_samples, csrs, iters: int):
+    """The CPU oracle as it stands, timed on this host on a bounded sample of the workload."""
+    import numpy as np
+    from oracle import dadam_oracle as O
+    hp = O.Hyper(float(np.float32(wl.lr)), float(np.float32(wl.beta1)), float(np.float32(wl.beta2)),
+                 float(np.float32(wl.eps)), wl.s)
+    n = x0_sample[0].shape[0]
+    z = lambda: [np.zeros(n) for _ in range(wl.n_rows)]
+    st = O.State([x.copy() for x in x0_sample], z(), z(), z())
+    ocsr = [O.Csr(np.asarray(rp), np.asarray(col), np.asarray(w, dtype=np.float64)) for rp, col, w in csrs]
+    t0 = time.perf_counter()
+    for t in range(1, iters + 1):
+        xn = O.dadam_step(st, grad_samples[(t - 1) % len(grad_samples)], ocsr[wl.slot_of_step(t)], t, hp, "O32m", wl.param_dtype)
+        for i in range(wl.n_rows):
+            st.x_src[i] = xn[i]
+    dt = time.perf_counter() - t0
+    return wl.n_rows * n * iters / dt, dt
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--mode", choices=["auto", "tile", "direct"], default="auto")
+    ap.add_argument("--inplace", action="store_true", help="update parameters in place instead of ping-pong")
+    ap.add_argument("--pool", type=int, default=2, help="number of pre-generated gradient sets cycled through")
+    ap.add_argument("--scale-div", type=int, default=1, help="divide tensor dimensions (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 20)
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; all replicas of the simulated run (or one node's share) live in "
+              "one HBM and there is no multi-GPU path to time. Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2410_11998_amd import binding as B
+    from paper_2410_11998_amd import workloads as WL
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = WL.workload(args.config, scale_div=args.scale_div)
+    K = args.steps if args.steps is not None else wl.steps
+    W = args.warmup
+    layout = wl.layout()
+    d, R, C = layout.d, wl.n_rows, wl.n_cols
+    TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+    ADT = {"f32": B.DADAM_F32, "bf16": B.DADAM_BF16}
+    pdt, gdt = TDT[wl.param_dtype], TDT[wl.grad_dtype]
+    inplace = args.inplace or R != C
+
+    # ---- resident inputs ----------------------------------------------------------------
+    x0 = WL.normal_torch(WL.seed_for(wl.cfg, 0), (d,), wl.param_std, dev, pdt)     # one draw shared by all replicas
+    x_src = [x0.clone() for _ in range(R)]
+    for c in range(R, C):                                                          # neighbours' receive buffers
+        x_src.append(WL.normal_torch(WL.seed_for(wl.cfg, 1) + c, (d,), wl.param_std, dev, pdt))
+    del x0
+    x_dst = x_src[:R] if inplace else [torch.zeros(d, dtype=pdt, device=dev) for _ in range(R)]
+    m_hat = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(R)]
+    v_hat = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(R)]
+    acc = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(R)] if wl.s > 1 else None
+    pool = []
+    gen = torch.Generator(device=dev)
+    for p in range(max(1, args.pool)):
+        gen.manual_seed(WL.seed_for(wl.cfg, 2 + p))
+        gs = []
+        for i in range(R):
+            g = torch.empty(d, dtype=torch.float32, device=dev).normal_(0.0, wl.grad_std, generator=gen)
+            gs.append(g if gdt == torch.float32 else g.to(gdt))
+        pool.append(gs)
+
+    csrs = [wl.csr(k) for k in range(wl.n_slots())]
+    h = B.dadam_init(R, C, d, layout.offsets, layout.numels, ADT[wl.param_dtype], ADT[wl.grad_dtype], wl.lr, wl.beta1,
+                     wl.beta2, wl.eps, wl.s, -1.0, device=0)
+    for k, (rp, col, w) in enumerate(csrs):
+        B.dadam_set_topology(h, k, rp, col, w)
+    B.dadam_bind(h, x_src, x_dst, m_hat, v_hat, acc)
+    flags = B.DADAM_FUSE_ACCUM | {"auto": 0, "tile": B.DADAM_FORCE_TILE, "direct": B.DADAM_FORCE_DIRECT}[args.mode]
+    tile_mode = (args.mode == "tile") or (args.mode == "auto" and B.dadam_slot_uses_tile_mode(h, 0))
+
+    # sample for the CPU baseline, taken before anything is updated
+    ns = min(args.cpu_sample, d)
+    if not args.no_cpu_baseline:
+        x0_sample = [x[:ns].to(torch.float64).cpu().numpy() for x in x_src]
+        g_samples = [[g[:ns].to(torch.float64).cpu().numpy() for g in gs] for gs in pool]
+
+    stream = B.current_stream()
+
+    def one_step(t: int):
+        B.dadam_gossip_step(h, wl.slot_of_step(t), pool[t % len(pool)], t, flags, stream)
+        if not inplace:
+            B.dadam_swap_x(h)
+
+    t = 0
+    for _ in range(W):
+        t += 1
+        one_step(t)
+    torch.cuda.synchronize()
+
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    phases = []
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for k in range(K):
+        t += 1
+        phases.append(phase_of(t, wl.s))
+        ev0[k].record()
+        one_step(t)
+        ev1[k].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_begin
+
+    kernel_ms = [ev0[k].elapsed_time(ev1[k]) for k in range(K)]
+    avg_kernel_s = sum(kernel_ms) / K / 1e3
+    replica_params = R * d
+    value = replica_params * K / elapsed
+    bytes_per_launch = replica_params * sum(algorithmic_bytes_per_replica_param(wl, p) for p in phases) / K
+    achieved = bytes_per_launch / avg_kernel_s
+    by_phase = {}
+    for p, ms in zip(phases, kernel_ms):
+        by_phase.setdefault(p, []).append(ms)
+
+    out = {
+        "metric": "replica-params updated/sec for fused gossip+Adam step",
+        "value": value,
+        "unit": "replica-params/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": elapsed / K * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if wl.param_dtype == "f32" else "bf16 params+grads, f32 moments and arithmetic",
+        "data": "synthetic",
+        "config": {
+            "workload": wl.name, "n_rows": R, "n_sources": C, "d": d, "tensors": len(layout.names), "topology": wl.topology,
+            "accum_s": wl.s, "kernel": ("k_tile" if tile_mode else "k_direct"), "x_buffers": "in-place" if inplace else "ping-pong",
+            "grad_pool": len(pool),
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK_BYTES_PER_S / 1e9, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_BYTES_PER_S, "traffic": None,
+            "algorithmic_bytes_per_launch": bytes_per_launch, "avg_launch_ms": avg_kernel_s * 1e3,
+            "ms_by_phase": {p: sum(v) / len(v) for p, v in by_phase.items()},
+        },
+    }
+
+    torch.cuda.synchronize()
+    B.dadam_destroy(h)
+    if not args.no_cpu_baseline:
+        del x_src, x_dst, m_hat, v_hat, acc, pool
+        torch.cuda.empty_cache()
+        iters = wl.s + 1
+        v, dt = cpu_baseline(wl, x0_sample, g_samples, csrs, iters)
+        out["cpu_baseline"] = {
+            "value": v, "unit": "replica-params/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {ns} coordinates of all {R} rows, {iters} iterations of the same workload "
+                      f"({dt:.1f} s of single-threaded NumPy float64)",
+        }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,207 @@
+/*
+ * dadam - the per-iteration decentralized Adam step on one MI355X (gfx950).
+ *
+ * One call of dadam_gossip_step performs, for every updated replica ("row") i and every
+ * element e of the packed parameter vector, iteration t of the paper's Algorithm 3
+ * (appendix "Decentralized accumulated Adam"; Algorithm 1 of section 4 is its case s = 1):
+ *
+ *     t_hat = ceil(t / s)                                                   line 4
+ *     m     = beta1 * m_hat_i[e] + (1 - beta1) * g_i[e]                      line 6
+ *     v     = beta2 * v_hat_i[e] + (1 - beta2) * g_i[e]^2                    line 7
+ *     x_dst_i[e] = sum_k w[k] * x_src[col[k]][e]                             line 8, mixing term
+ *                  - lr * (m / (1 - beta1^t_hat)) / (sqrt(v / (1 - beta2^t_hat)) + eps)       (eq. (2), section 2)
+ *     b_i[e] += g_i[e] / s                                                   line 9
+ *     if t mod s == 0:  m_hat_i[e] = beta1 * m_hat_i[e] + (1 - beta1) * b_i[e]               lines 10-13
+ *                       v_hat_i[e] = beta_vhat * v_hat_i[e] + (1 - beta_vhat) * b_i[e]^2
+ *                       b_i[e] = 0
+ *
+ * k runs over row i of a CSR neighbour list (row_ptr, col, w); the replica itself is an ordinary
+ * entry of its row.  Every row reads the previous iterate x^(t-1) (the sources), never a value
+ * written by the same call.  m and v are temporaries and are not stored.
+ *
+ * General rules of this interface
+ *   - All entry points are extern "C", take plain pointers and sizes, return an int status
+ *     (0 = DADAM_OK, negative = error) and never throw or abort.  The text of the last error of a
+ *     handle is available from dadam_last_error().
+ *   - "host" / "device" says where a pointer must point.  Large buffers (parameters, gradients,
+ *     moments, accumulator) are DEVICE memory owned by the caller; the library never allocates,
+ *     frees or copies them and never synchronises a stream.  The library owns only small metadata
+ *     (segment table, CSR slots) on host and device.
+ *   - Launching entry points enqueue work on the given HIP stream (a hipStream_t passed as
+ *     void*; NULL = the default stream) and return at once.  The caller keeps every buffer alive
+ *     and unmodified until that work has finished.
+ *   - All validation happens on the host before anything is launched; a failed call launches
+ *     nothing.
+ *   - At most DADAM_MAX_ROWS rows and DADAM_MAX_ROWS source buffers per handle.
+ */
+#ifndef DADAM_H_
+#define DADAM_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DADAM_ABI_VERSION 1u
+#define DADAM_MAX_ROWS 64u
+#define DADAM_MAX_SLOTS 16u
+#define DADAM_DEVICE_NONE (-1) /* host-only handle: validation and planning work, launches fail */
+
+/* element types of parameters and gradients; m_hat, v_hat and b are always float32 */
+#define DADAM_F32 0u
+#define DADAM_BF16 1u
+
+/* status codes */
+#define DADAM_OK 0
+#define DADAM_EINVAL (-1) /* null pointer, zero size, bad enum, value out of range            */
+#define DADAM_EALIGN (-2) /* a device buffer is not 16-byte aligned                            */
+#define DADAM_ETOPO (-3)  /* malformed neighbour list                                          */
+#define DADAM_EALIAS (-4) /* buffers overlap in a way that would let a row read a new value     */
+#define DADAM_ESTATE (-5) /* call order: no buffers bound, slot not set, host-only handle, ...  */
+#define DADAM_EHIP (-6)   /* a HIP runtime call failed                                         */
+
+/* flags of dadam_gossip_step */
+#define DADAM_FUSE_ACCUM 1u   /* also do lines 9-13 (accumulate and fold) in the same pass         */
+#define DADAM_FORCE_DIRECT 2u /* every row streams its sources from global memory                  */
+#define DADAM_FORCE_TILE 4u   /* stage each source tile once in LDS and update all rows from it    */
+
+/* flags reported by dadam_set_topology through *warn */
+#define DADAM_WARN_NOT_COLUMN_STOCHASTIC 1u /* square W whose columns do not sum to 1             */
+
+typedef struct dadam_handle dadam_handle; /* opaque, owned by the library */
+
+/* One tensor of the packed layout: elements [offset_elems, offset_elems + numel) of every
+ * per-replica buffer.  Tensors must be listed in increasing offset order and must not overlap;
+ * elements between tensors (padding) are never read or written.  weight_decay and flags are
+ * reserved for per-tensor hyper-parameters and must be 0. */
+typedef struct {
+  uint64_t offset_elems;
+  uint64_t numel;
+  float weight_decay;
+  uint32_t flags;
+} dadam_tensor_desc;
+
+typedef struct {
+  uint32_t abi_version; /* DADAM_ABI_VERSION */
+  uint32_t n_rows;      /* R: replicas updated by a step                                          */
+  uint32_t n_cols;      /* number of source buffers holding x^(t-1) (R for a full simulation;     */
+                        /* own parameters + neighbours' receive buffers for one node's share)     */
+  uint64_t d;           /* elements per buffer (packed length, padding included)                  */
+  uint32_t n_tensors;
+  const dadam_tensor_desc* tensors; /* host, copied */
+  uint32_t param_dtype;             /* DADAM_F32 | DADAM_BF16: type of x_src and x_dst            */
+  uint32_t grad_dtype;              /* DADAM_F32 | DADAM_BF16: type of the gradients              */
+  float lr, beta1, beta2, eps;      /* Algorithm 1 / 3 hyper-parameters                           */
+  uint32_t accum_s;                 /* s >= 1, iterations per accumulation loop; 1 = Algorithm 1  */
+  float beta_vhat; /* decay of v_hat in the fold (line 12).  The listing prints beta_1 there; that is
+                      taken as a misprint and the default, selected by a negative value or NaN, is
+                      beta2.  Any value in [0, 1) selects it explicitly. */
+  int32_t device;  /* HIP device ordinal, or DADAM_DEVICE_NONE */
+} dadam_config;
+
+/* Arrays (host) of DEVICE pointers, caller-owned; the arrays themselves are copied.
+ * Every buffer holds cfg.d elements and is 16-byte aligned.
+ * x_dst[i] may be the very same buffer as one x_src[c] (update in place); any other overlap
+ * between two different buffers is rejected with DADAM_EALIAS.  In-place update is legal when the
+ * step runs in tile mode, or when source c is read by row i only. */
+typedef struct {
+  const void* const* x_src; /* [n_cols] x^(t-1) */
+  void* const* x_dst;       /* [n_rows] x^(t)   */
+  float* const* m_hat;      /* [n_rows] */
+  float* const* v_hat;      /* [n_rows] */
+  float* const* acc;        /* [n_rows] the accumulator b; may be NULL when accum_s == 1 */
+} dadam_buffers;
+
+/* What the planner decided, for tests and tuning. */
+typedef struct {
+  uint32_t n_segments;      /* maximal runs of contiguous tensors                               */
+  uint32_t tile_elems;      /* elements of one tile in tile mode                                */
+  uint32_t direct_elems;    /* elements of one work item in direct mode                         */
+  uint64_t n_tiles_tile;    /* work items (workgroups) of a full step in tile mode              */
+  uint64_t n_tiles_direct;  /* tiles per row in direct mode (work items = this * n_rows)        */
+  uint32_t lds_bytes_tile;  /* LDS per workgroup in tile mode                                   */
+  uint32_t tile_mode_possible; /* 1 if the source tile fits in LDS                              */
+} dadam_plan_info;
+
+/* Create a handle.  Validates the configuration, builds the segment table from the tensor list
+ * and (unless device == DADAM_DEVICE_NONE) uploads it.  *out is set only on success.
+ * Errors: DADAM_EINVAL (null, n_rows/n_cols 0 or above DADAM_MAX_ROWS, d == 0, s == 0, dtype,
+ * tensors unordered / overlapping / beyond d / non-zero reserved fields, hyper-parameters out of
+ * range: lr finite, 0 <= beta < 1, eps >= 0), DADAM_EHIP. */
+int dadam_init(const dadam_config* cfg, dadam_handle** out);
+
+/* Register rows of the mixing matrix W (section 2, eq. (2); Assumption 3 lists the properties the
+ * analysis wants) in slot `slot` (< DADAM_MAX_SLOTS); time-varying topologies use one slot per
+ * distinct matrix.  row_ptr[n_rows + 1], col_idx[nnz], w[nnz] are HOST arrays and are copied.
+ * Checked: row_ptr[0] == 0, non-decreasing, every row non-empty; 0 <= col < n_cols; no column
+ * twice in a row; w finite and > 0; |sum of a row - 1| <= 1e-5.  Else DADAM_ETOPO.
+ * If n_rows == n_cols and some column sum is off by more than 1e-5, the call still succeeds and
+ * sets DADAM_WARN_NOT_COLUMN_STOCHASTIC in *warn (warn may be NULL).
+ * A slot may be overwritten only while no launched work still uses it. */
+int dadam_set_topology(dadam_handle* h, uint32_t slot, const int32_t* row_ptr,
+                       const int32_t* col_idx, const float* w, uint32_t* warn);
+
+/* Bind the device buffers.  May be called again at any time (e.g. to exchange x_src and x_dst);
+ * work already launched keeps the pointers it was launched with.
+ * Errors: DADAM_EINVAL (null), DADAM_EALIGN, DADAM_EALIAS. */
+int dadam_bind(dadam_handle* h, const dadam_buffers* bufs);
+
+/* Exchange the roles of x_src and x_dst (needs n_rows == n_cols): what a ping-pong caller does
+ * between two iterations. */
+int dadam_swap_x(dadam_handle* h);
+
+/* Iteration t (1-based) of Algorithm 3 as written at the top of this file, using the neighbour
+ * list in `slot` and grads[n_rows] (HOST array of DEVICE pointers, each cfg.d elements of
+ * grad_dtype, 16-byte aligned, not overlapping any output).  With DADAM_FUSE_ACCUM lines 4-13 are
+ * done in one pass; without it only lines 4-8 (x_dst) and the caller follows with
+ * dadam_accumulate(grads, t) - never both for one t.  On the first iteration of a loop
+ * ((t-1) mod s == 0) the accumulator is taken to be zero and is not read.
+ * Errors: DADAM_ESTATE (nothing bound, slot empty, host-only handle), DADAM_EINVAL (t == 0, null,
+ * both FORCE flags), DADAM_EALIGN, DADAM_EALIAS (in-place rows that the chosen mode cannot do, or
+ * DADAM_FORCE_TILE when the source tile does not fit in LDS -> DADAM_EINVAL), DADAM_EHIP. */
+int dadam_gossip_step(dadam_handle* h, uint32_t slot, const void* const* grads, uint64_t t,
+                      uint32_t flags, void* hip_stream);
+
+/* The same restricted to tensors [tensor_begin, tensor_end) of the layout (a "bucket" in the
+ * sense of section 2.1, where parameters are updated and communicated bucket by bucket). */
+int dadam_gossip_step_range(dadam_handle* h, uint32_t slot, const void* const* grads, uint64_t t,
+                            uint32_t flags, uint32_t tensor_begin, uint32_t tensor_end,
+                            void* hip_stream);
+
+/* Lines 9-13 of Algorithm 3 alone: b += g / s and, when t mod s == 0, the fold into m_hat and
+ * v_hat followed by b = 0. */
+int dadam_accumulate(dadam_handle* h, const void* const* grads, uint64_t t, void* hip_stream);
+
+/* x_dst = W x_src: eq. (2) with a zero search direction (pure gossip averaging).  flags: 0 or one
+ * of DADAM_FORCE_DIRECT / DADAM_FORCE_TILE. */
+int dadam_mix(dadam_handle* h, uint32_t slot, uint32_t flags, void* hip_stream);
+
+/* Change the step size used by later calls (learning-rate schedules). */
+int dadam_set_lr(dadam_handle* h, float lr);
+
+/* Planner facts for this handle. */
+int dadam_get_plan_info(const dadam_handle* h, dadam_plan_info* out);
+
+/* 1 if a step with this slot would run in tile mode when no FORCE flag is given, 0 for direct
+ * mode, negative status on error. */
+int dadam_slot_uses_tile_mode(const dadam_handle* h, uint32_t slot);
+
+/* Offsets of a packed layout: tensor k starts at the next multiple of align_elems elements after
+ * tensor k-1 ends.  numel[n] in, offsets[n] out (both host); returns the packed length through
+ * *d_out. */
+int dadam_pack_offsets(const uint64_t* numel, uint32_t n, uint32_t align_elems, uint64_t* offsets,
+                       uint64_t* d_out);
+
+/* Text of the last error recorded on this handle ("" if none).  With h == NULL: the text of the
+ * last dadam_init failure of the calling thread.  The pointer stays valid until the next call on
+ * the same handle (thread). */
+const char* dadam_last_error(const dadam_handle* h);
+
+/* Free the handle and its metadata.  The caller makes sure launched work has finished. */
+void dadam_destroy(dadam_handle* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DADAM_H_ */

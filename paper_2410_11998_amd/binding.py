@@ -1,0 +1,209 @@
+"""ctypes binding of libdadam.so - argument marshalling only.
+
+Every function below has the name and the arguments of the C entry point it wraps (see
+include/dadam.h); nothing of the method is computed in Python.  Device memory comes from
+PyTorch tensors (their ``data_ptr()``), streams from ``torch.cuda.current_stream()``.
+
+The library must have been built (``python -m paper_2410_11998_amd.build`` or
+``__graft_entry__.build()``); importing this module without it raises, there is no
+fallback path.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdadam.so")
+
+DADAM_ABI_VERSION = 1
+DADAM_MAX_ROWS = 64
+DADAM_MAX_SLOTS = 16
+DADAM_DEVICE_NONE = -1
+DADAM_F32, DADAM_BF16 = 0, 1
+DADAM_OK, DADAM_EINVAL, DADAM_EALIGN, DADAM_ETOPO, DADAM_EALIAS, DADAM_ESTATE, DADAM_EHIP = 0, -1, -2, -3, -4, -5, -6
+DADAM_FUSE_ACCUM, DADAM_FORCE_DIRECT, DADAM_FORCE_TILE = 1, 2, 4
+DADAM_WARN_NOT_COLUMN_STOCHASTIC = 1
+
+EXPORTS = [
+    "dadam_init", "dadam_set_topology", "dadam_bind", "dadam_swap_x", "dadam_gossip_step",
+    "dadam_gossip_step_range", "dadam_accumulate", "dadam_mix", "dadam_set_lr", "dadam_get_plan_info",
+    "dadam_slot_uses_tile_mode", "dadam_pack_offsets", "dadam_last_error", "dadam_destroy",
+]
+
+
+class dadam_tensor_desc(C.Structure):
+    _fields_ = [("offset_elems", C.c_uint64), ("numel", C.c_uint64), ("weight_decay", C.c_float), ("flags", C.c_uint32)]
+
+
+class dadam_config(C.Structure):
+    _fields_ = [
+        ("abi_version", C.c_uint32), ("n_rows", C.c_uint32), ("n_cols", C.c_uint32), ("d", C.c_uint64),
+        ("n_tensors", C.c_uint32), ("tensors", C.POINTER(dadam_tensor_desc)),
+        ("param_dtype", C.c_uint32), ("grad_dtype", C.c_uint32),
+        ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+        ("accum_s", C.c_uint32), ("beta_vhat", C.c_float), ("device", C.c_int32),
+    ]
+
+
+class dadam_buffers(C.Structure):
+    _fields_ = [("x_src", C.POINTER(C.c_void_p)), ("x_dst", C.POINTER(C.c_void_p)), ("m_hat", C.POINTER(C.c_void_p)),
+                ("v_hat", C.POINTER(C.c_void_p)), ("acc", C.POINTER(C.c_void_p))]
+
+
+class dadam_plan_info(C.Structure):
+    _fields_ = [("n_segments", C.c_uint32), ("tile_elems", C.c_uint32), ("direct_elems", C.c_uint32),
+                ("n_tiles_tile", C.c_uint64), ("n_tiles_direct", C.c_uint64), ("lds_bytes_tile", C.c_uint32),
+                ("tile_mode_possible", C.c_uint32)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2410_11998_amd.build); "
+                          "there is no fallback implementation")
+    lib = C.CDLL(LIB_PATH)
+    H = C.c_void_p
+    lib.dadam_init.argtypes = [C.POINTER(dadam_config), C.POINTER(H)]
+    lib.dadam_set_topology.argtypes = [H, C.c_uint32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_uint32)]
+    lib.dadam_bind.argtypes = [H, C.POINTER(dadam_buffers)]
+    lib.dadam_swap_x.argtypes = [H]
+    lib.dadam_gossip_step.argtypes = [H, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64, C.c_uint32, C.c_void_p]
+    lib.dadam_gossip_step_range.argtypes = [H, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
+    lib.dadam_accumulate.argtypes = [H, C.POINTER(C.c_void_p), C.c_uint64, C.c_void_p]
+    lib.dadam_mix.argtypes = [H, C.c_uint32, C.c_uint32, C.c_void_p]
+    lib.dadam_set_lr.argtypes = [H, C.c_float]
+    lib.dadam_get_plan_info.argtypes = [H, C.POINTER(dadam_plan_info)]
+    lib.dadam_slot_uses_tile_mode.argtypes = [H, C.c_uint32]
+    lib.dadam_pack_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+    lib.dadam_last_error.argtypes = [H]
+    lib.dadam_last_error.restype = C.c_char_p
+    lib.dadam_destroy.argtypes = [H]
+    lib.dadam_destroy.restype = None
+    for name in EXPORTS:
+        if name not in ("dadam_last_error", "dadam_destroy"):
+            getattr(lib, name).restype = C.c_int
+    return lib
+
+
+lib = _load()
+
+
+class DadamError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"dadam error {code}: {msg}")
+        self.code = code
+
+
+def _ptr_array(ptrs: Sequence[int]):
+    arr = (C.c_void_p * len(ptrs))(*[C.c_void_p(int(p)) for p in ptrs])
+    return arr
+
+
+def _ptrs_of(tensors) -> Sequence[int]:
+    return [t if isinstance(t, int) else t.data_ptr() for t in tensors]
+
+
+def _check(h, rc: int) -> int:
+    if rc < 0:
+        raise DadamError(rc, (lib.dadam_last_error(h) or b"").decode())
+    return rc
+
+
+def dadam_last_error(h) -> str:
+    return (lib.dadam_last_error(h) or b"").decode()
+
+
+def dadam_pack_offsets(numel: Sequence[int], align_elems: int):
+    n = len(numel)
+    a = (C.c_uint64 * n)(*[int(x) for x in numel])
+    o = (C.c_uint64 * n)()
+    d = C.c_uint64(0)
+    rc = lib.dadam_pack_offsets(a, n, align_elems, o, C.byref(d))
+    if rc < 0:
+        raise DadamError(rc, "dadam_pack_offsets")
+    return np.asarray(list(o), dtype=np.uint64), int(d.value)
+
+
+def dadam_init(n_rows: int, n_cols: int, d: int, offsets: Sequence[int], numels: Sequence[int],
+               param_dtype: int = DADAM_F32, grad_dtype: int = DADAM_F32, lr: float = 1e-3, beta1: float = 0.9,
+               beta2: float = 0.999, eps: float = 1e-8, accum_s: int = 1, beta_vhat: float = -1.0,
+               device: int = 0, abi_version: int = DADAM_ABI_VERSION, weight_decay=None, tensor_flags=None):
+    n = len(offsets)
+    descs = (dadam_tensor_desc * max(n, 1))()
+    for k in range(n):
+        descs[k].offset_elems = int(offsets[k])
+        descs[k].numel = int(numels[k])
+        descs[k].weight_decay = float(weight_decay[k]) if weight_decay is not None else 0.0
+        descs[k].flags = int(tensor_flags[k]) if tensor_flags is not None else 0
+    cfg = dadam_config(abi_version, n_rows, n_cols, d, n, descs, param_dtype, grad_dtype, lr, beta1, beta2, eps,
+                       accum_s, beta_vhat, device)
+    h = C.c_void_p()
+    rc = lib.dadam_init(C.byref(cfg), C.byref(h))
+    if rc < 0:
+        raise DadamError(rc, (lib.dadam_last_error(None) or b"").decode())
+    return h
+
+
+def dadam_set_topology(h, slot: int, row_ptr, col_idx, w) -> int:
+    rp = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx, dtype=np.int32)
+    ww = np.ascontiguousarray(w, dtype=np.float32)
+    warn = C.c_uint32(0)
+    _check(h, lib.dadam_set_topology(h, slot, rp.ctypes.data_as(C.POINTER(C.c_int32)), ci.ctypes.data_as(C.POINTER(C.c_int32)),
+                                     ww.ctypes.data_as(C.POINTER(C.c_float)), C.byref(warn)))
+    return int(warn.value)
+
+
+def dadam_bind(h, x_src, x_dst, m_hat, v_hat, acc=None) -> None:
+    keep = [_ptr_array(_ptrs_of(x_src)), _ptr_array(_ptrs_of(x_dst)), _ptr_array(_ptrs_of(m_hat)), _ptr_array(_ptrs_of(v_hat)),
+            _ptr_array(_ptrs_of(acc)) if acc is not None else None]
+    b = dadam_buffers(keep[0], keep[1], keep[2], keep[3], keep[4] if keep[4] is not None else C.POINTER(C.c_void_p)())
+    _check(h, lib.dadam_bind(h, C.byref(b)))
+
+
+def dadam_swap_x(h) -> None:
+    _check(h, lib.dadam_swap_x(h))
+
+
+def dadam_gossip_step(h, slot: int, grads, t: int, flags: int = DADAM_FUSE_ACCUM, stream: int = 0) -> None:
+    _check(h, lib.dadam_gossip_step(h, slot, _ptr_array(_ptrs_of(grads)), t, flags, C.c_void_p(stream)))
+
+
+def dadam_gossip_step_range(h, slot: int, grads, t: int, flags: int, tensor_begin: int, tensor_end: int, stream: int = 0) -> None:
+    _check(h, lib.dadam_gossip_step_range(h, slot, _ptr_array(_ptrs_of(grads)), t, flags, tensor_begin, tensor_end, C.c_void_p(stream)))
+
+
+def dadam_accumulate(h, grads, t: int, stream: int = 0) -> None:
+    _check(h, lib.dadam_accumulate(h, _ptr_array(_ptrs_of(grads)), t, C.c_void_p(stream)))
+
+
+def dadam_mix(h, slot: int, flags: int = 0, stream: int = 0) -> None:
+    _check(h, lib.dadam_mix(h, slot, flags, C.c_void_p(stream)))
+
+
+def dadam_set_lr(h, lr: float) -> None:
+    _check(h, lib.dadam_set_lr(h, lr))
+
+
+def dadam_get_plan_info(h) -> dadam_plan_info:
+    info = dadam_plan_info()
+    _check(h, lib.dadam_get_plan_info(h, C.byref(info)))
+    return info
+
+
+def dadam_slot_uses_tile_mode(h, slot: int) -> bool:
+    return _check(h, lib.dadam_slot_uses_tile_mode(h, slot)) == 1
+
+
+def dadam_destroy(h) -> None:
+    lib.dadam_destroy(h)
+
+
+def current_stream() -> int:
+    """The HIP stream PyTorch is launching on, as an integer handle."""
+    import torch
+    return int(torch.cuda.current_stream().cuda_stream)

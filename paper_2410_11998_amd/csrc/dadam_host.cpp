@@ -1,0 +1,647 @@
+// Host side of libdadam: the C ABI of include/dadam.h - argument validation, the segment/tile
+// planner, neighbour-list slots, per-iteration scalars and launch set-up.  No arithmetic of the
+// method happens here except the scalar bias corrections of Algorithm 3 line 8, which are the same
+// for every element of an iteration.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "dadam_internal.h"
+
+using namespace dadam;
+
+namespace {
+
+thread_local std::string g_init_error;
+
+struct Slot {
+  bool set = false;
+  std::vector<int32_t> row_ptr, col;
+  std::vector<float> w;
+  int32_t* d_row_ptr = nullptr;
+  int32_t* d_col = nullptr;
+  float* d_w = nullptr;
+  bool reuse = false;                 // some source is read by two or more rows
+  std::vector<int32_t> sole_reader;   // per source: the only row reading it, -1 none, -2 several
+};
+
+struct DeviceGuard {
+  int prev = -1;
+  bool switched = false;
+  hipError_t err = hipSuccess;
+  explicit DeviceGuard(int dev) {
+    err = hipGetDevice(&prev);
+    if (err == hipSuccess && prev != dev) {
+      err = hipSetDevice(dev);
+      switched = (err == hipSuccess);
+    }
+  }
+  ~DeviceGuard() {
+    if (switched) (void)hipSetDevice(prev);
+  }
+};
+
+}  // namespace
+
+struct dadam_handle {
+  dadam_config cfg{};
+  std::vector<dadam_tensor_desc> tensors;
+  std::vector<uint32_t> tensor_seg;  // segment of each non-empty tensor, UINT32_MAX for empty ones
+  std::vector<Segment> segs;
+  Segment* d_segs = nullptr;
+  TileShape shape{4, 1};
+  int vec = 4;
+  uint32_t tile_elems = 0, direct_elems = 0, lds_bytes = 0;
+  bool tile_possible = false;
+  uint64_t n_work_t = 0, n_work_d = 0;
+  Slot slots[DADAM_MAX_SLOTS];
+  bool bound = false;
+  const void* x_src[kMaxRows] = {};
+  void* x_dst[kMaxRows] = {};
+  float* m_hat[kMaxRows] = {};
+  float* v_hat[kMaxRows] = {};
+  float* acc[kMaxRows] = {};
+  int32_t inplace_col[kMaxRows];  // source that x_dst[i] coincides with, or -1
+  float lr = 0.f;
+  double betav = 0.0;
+  mutable std::string err;
+};
+
+namespace {
+
+int fail(const dadam_handle* h, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  if (h) h->err = buf; else g_init_error = buf;
+  return code;
+}
+
+size_t dtype_bytes(uint32_t dt) { return dt == DADAM_BF16 ? 2 : 4; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Interval {
+  uintptr_t lo, hi;
+  int kind;  // 0 x_src, 1 x_dst, 2 state
+  int index;
+};
+
+bool overlaps(const Interval& a, const Interval& b) { return a.lo < b.hi && b.lo < a.hi; }
+
+int env_int(const char* name, int fallback) {
+  const char* v = getenv(name);
+  if (!v || !*v) return fallback;
+  return atoi(v);
+}
+
+// Build maximal runs of contiguous tensors and number the tiles of both tile grids.
+int plan(dadam_handle* h) {
+  h->segs.clear();
+  h->tensor_seg.assign(h->tensors.size(), UINT32_MAX);
+  for (size_t k = 0; k < h->tensors.size(); ++k) {
+    const dadam_tensor_desc& t = h->tensors[k];
+    if (t.numel == 0) continue;
+    if (!h->segs.empty() && h->segs.back().hi == t.offset_elems) {
+      h->segs.back().hi = t.offset_elems + t.numel;
+    } else {
+      Segment s{};
+      s.lo = t.offset_elems;
+      s.hi = t.offset_elems + t.numel;
+      h->segs.push_back(s);
+    }
+    h->tensor_seg[k] = (uint32_t)(h->segs.size() - 1);
+  }
+  uint64_t wt = 0, wd = 0;
+  for (Segment& s : h->segs) {
+    s.first_tile_t = s.lo / h->tile_elems;
+    s.first_tile_d = s.lo / h->direct_elems;
+    if (wt > 0x7fffffffull || wd > 0x7fffffffull) break;
+    s.work0_t = (uint32_t)wt;
+    s.work0_d = (uint32_t)wd;
+    wt += (s.hi - 1) / h->tile_elems - s.first_tile_t + 1;
+    wd += (s.hi - 1) / h->direct_elems - s.first_tile_d + 1;
+  }
+  h->n_work_t = wt;
+  h->n_work_d = wd;
+  if (wt > 0x7fffffffull || wd * h->cfg.n_rows > 0x7fffffffull)
+    return fail(nullptr, DADAM_EINVAL, "layout too large: more than 2^31-1 work items");
+  return DADAM_OK;
+}
+
+// Work-item range [w0, w1) of the tiles that intersect elements [lo, hi), which start in segment
+// s0 and end in segment s1.
+void work_range(const dadam_handle* h, bool tile_mode, uint32_t s0, uint32_t s1, uint64_t lo,
+                uint64_t hi, uint32_t* w0, uint32_t* w1) {
+  const uint64_t T = tile_mode ? h->tile_elems : h->direct_elems;
+  const Segment& a = h->segs[s0];
+  const Segment& b = h->segs[s1];
+  *w0 = (tile_mode ? a.work0_t : a.work0_d) + (uint32_t)(lo / T - (tile_mode ? a.first_tile_t : a.first_tile_d));
+  *w1 = (tile_mode ? b.work0_t : b.work0_d) + (uint32_t)((hi - 1) / T - (tile_mode ? b.first_tile_t : b.first_tile_d)) + 1;
+}
+
+int check_launchable(const dadam_handle* h) {
+  if (h->cfg.device == DADAM_DEVICE_NONE)
+    return fail(h, DADAM_ESTATE, "host-only handle (device = DADAM_DEVICE_NONE) cannot launch");
+  if (!h->bound) return fail(h, DADAM_ESTATE, "no buffers bound: call dadam_bind first");
+  return DADAM_OK;
+}
+
+int check_grads(const dadam_handle* h, const void* const* grads) {
+  if (!grads) return fail(h, DADAM_EINVAL, "grads is null");
+  const uint32_t R = h->cfg.n_rows;
+  const size_t gb = h->cfg.d * dtype_bytes(h->cfg.grad_dtype);
+  const size_t xb = h->cfg.d * dtype_bytes(h->cfg.param_dtype);
+  const size_t sb = h->cfg.d * 4;
+  for (uint32_t i = 0; i < R; ++i) {
+    if (!grads[i]) return fail(h, DADAM_EINVAL, "grads[%u] is null", i);
+    if (!aligned16(grads[i])) return fail(h, DADAM_EALIGN, "grads[%u] is not 16-byte aligned", i);
+  }
+  for (uint32_t i = 0; i < R; ++i) {
+    Interval g{(uintptr_t)grads[i], (uintptr_t)grads[i] + gb, 3, (int)i};
+    for (uint32_t j = 0; j < R; ++j) {
+      Interval outs[4] = {{(uintptr_t)h->x_dst[j], (uintptr_t)h->x_dst[j] + xb, 1, (int)j},
+                          {(uintptr_t)h->m_hat[j], (uintptr_t)h->m_hat[j] + sb, 2, (int)j},
+                          {(uintptr_t)h->v_hat[j], (uintptr_t)h->v_hat[j] + sb, 2, (int)j},
+                          {(uintptr_t)h->acc[j], (uintptr_t)h->acc[j] + (h->acc[j] ? sb : 0), 2, (int)j}};
+      for (const Interval& o : outs)
+        if (o.lo && overlaps(g, o))
+          return fail(h, DADAM_EALIAS, "grads[%u] overlaps an output buffer of row %u", i, j);
+    }
+  }
+  return DADAM_OK;
+}
+
+void fill_args(const dadam_handle* h, const Slot* slot, const void* const* grads, StepArgs* a) {
+  memset(a, 0, sizeof(*a));
+  const uint32_t R = h->cfg.n_rows, C = h->cfg.n_cols;
+  for (uint32_t c = 0; c < C; ++c) a->x_src[c] = h->x_src[c];
+  for (uint32_t i = 0; i < R; ++i) {
+    a->x_dst[i] = h->x_dst[i];
+    a->m_hat[i] = h->m_hat[i];
+    a->v_hat[i] = h->v_hat[i];
+    a->acc[i] = h->acc[i];
+    a->grad[i] = grads ? grads[i] : nullptr;
+  }
+  if (slot) {
+    a->row_ptr = slot->d_row_ptr;
+    a->col = slot->d_col;
+    a->w = slot->d_w;
+  }
+  a->seg = h->d_segs;
+  a->n_seg = (uint32_t)h->segs.size();
+  a->n_rows = R;
+  a->n_cols = C;
+}
+
+// Scalars of iteration t (Algorithm 3 lines 4 and 8), computed in double and rounded once.
+void fill_scalars(const dadam_handle* h, uint64_t t, Scalars* s) {
+  const double b1 = (double)h->cfg.beta1, b2 = (double)h->cfg.beta2, bv = h->betav;
+  const uint64_t S = h->cfg.accum_s;
+  const double th = (double)((t + S - 1) / S);  // t_hat = ceil(t / s)
+  s->beta1 = (float)b1;
+  s->omb1 = (float)(1.0 - b1);
+  s->beta2 = (float)b2;
+  s->omb2 = (float)(1.0 - b2);
+  s->betav = (float)bv;
+  s->ombv = (float)(1.0 - bv);
+  s->inv_c1 = (float)(1.0 / (1.0 - std::pow(b1, th)));
+  s->inv_c2 = (float)(1.0 / (1.0 - std::pow(b2, th)));
+  s->eps = h->cfg.eps;
+  s->lr = h->lr;
+  s->inv_s = (float)(1.0 / (double)S);
+}
+
+Phase fused_phase(const dadam_handle* h, uint64_t t) {
+  const uint64_t S = h->cfg.accum_s;
+  if (S == 1) return kAlg1;
+  if (t % S == 0) return kFold;
+  if ((t - 1) % S == 0) return kLoopStart;
+  return kPlain;
+}
+
+// Decide tile or direct mode for this slot and these flags; checks in-place legality.
+int choose_mode(const dadam_handle* h, const Slot& slot, uint32_t flags, bool* tile_mode) {
+  if ((flags & DADAM_FORCE_DIRECT) && (flags & DADAM_FORCE_TILE))
+    return fail(h, DADAM_EINVAL, "DADAM_FORCE_DIRECT and DADAM_FORCE_TILE are exclusive");
+  bool direct_legal = true;
+  for (uint32_t i = 0; i < h->cfg.n_rows; ++i) {
+    int32_t c = h->inplace_col[i];
+    if (c < 0) continue;
+    int32_t sr = slot.sole_reader[c];
+    if (!(sr == -1 || sr == (int32_t)i)) direct_legal = false;
+  }
+  if (flags & DADAM_FORCE_TILE) {
+    if (!h->tile_possible) return fail(h, DADAM_EINVAL, "tile mode needs the source tile to fit in LDS");
+    *tile_mode = true;
+  } else if (flags & DADAM_FORCE_DIRECT) {
+    if (!direct_legal)
+      return fail(h, DADAM_EALIAS, "in-place update of a source that another row reads needs tile mode");
+    *tile_mode = false;
+  } else {
+    *tile_mode = h->tile_possible && (slot.reuse || !direct_legal);
+    if (!*tile_mode && !direct_legal)
+      return fail(h, DADAM_EALIAS, "in-place update of a shared source is impossible: tile does not fit in LDS");
+  }
+  return DADAM_OK;
+}
+
+int resolve_range(const dadam_handle* h, uint32_t tb, uint32_t te, bool whole, uint64_t* lo,
+                  uint64_t* hi, uint32_t* s0, uint32_t* s1, bool* empty) {
+  *empty = false;
+  if (whole) {
+    if (h->segs.empty()) { *empty = true; return DADAM_OK; }
+    *lo = h->segs.front().lo;
+    *hi = h->segs.back().hi;
+    *s0 = 0;
+    *s1 = (uint32_t)h->segs.size() - 1;
+    return DADAM_OK;
+  }
+  if (tb > te || te > h->tensors.size())
+    return fail(h, DADAM_EINVAL, "tensor range [%u, %u) outside [0, %zu]", tb, te, h->tensors.size());
+  uint32_t first = UINT32_MAX, last = UINT32_MAX;
+  for (uint32_t k = tb; k < te; ++k)
+    if (h->tensor_seg[k] != UINT32_MAX) { if (first == UINT32_MAX) first = k; last = k; }
+  if (first == UINT32_MAX) { *empty = true; return DADAM_OK; }
+  *lo = h->tensors[first].offset_elems;
+  *hi = h->tensors[last].offset_elems + h->tensors[last].numel;
+  *s0 = h->tensor_seg[first];
+  *s1 = h->tensor_seg[last];
+  return DADAM_OK;
+}
+
+int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint64_t t, uint32_t flags,
+              bool whole, uint32_t tb, uint32_t te, bool mix_only, void* stream) {
+  if (!h) return DADAM_EINVAL;
+  int rc = check_launchable(h);
+  if (rc) return rc;
+  if (slot_id >= DADAM_MAX_SLOTS || !h->slots[slot_id].set)
+    return fail(h, DADAM_ESTATE, "topology slot %u is not set", slot_id);
+  if (flags & ~(DADAM_FUSE_ACCUM | DADAM_FORCE_DIRECT | DADAM_FORCE_TILE))
+    return fail(h, DADAM_EINVAL, "unknown flag bits 0x%x", flags);
+  const Slot& slot = h->slots[slot_id];
+  Phase phase = kMixOnly;
+  if (!mix_only) {
+    if (t == 0) return fail(h, DADAM_EINVAL, "iterations are numbered from 1");
+    rc = check_grads(h, grads);
+    if (rc) return rc;
+    phase = (flags & DADAM_FUSE_ACCUM) ? fused_phase(h, t) : kUpdateOnly;
+    if (h->cfg.accum_s > 1 && (flags & DADAM_FUSE_ACCUM))
+      for (uint32_t i = 0; i < h->cfg.n_rows; ++i)
+        if (!h->acc[i]) return fail(h, DADAM_ESTATE, "accumulator of row %u is not bound", i);
+  }
+  bool tile_mode = false;
+  rc = choose_mode(h, slot, flags, &tile_mode);
+  if (rc) return rc;
+  uint64_t lo = 0, hi = 0;
+  uint32_t s0 = 0, s1 = 0;
+  bool empty = false;
+  rc = resolve_range(h, tb, te, whole, &lo, &hi, &s0, &s1, &empty);
+  if (rc) return rc;
+  if (empty) return DADAM_OK;
+  uint32_t w0 = 0, w1 = 0;
+  work_range(h, tile_mode, s0, s1, lo, hi, &w0, &w1);
+  StepArgs a;
+  fill_args(h, &slot, mix_only ? nullptr : grads, &a);
+  a.work_begin = w0;
+  a.clip_lo = lo;
+  a.clip_hi = hi;
+  fill_scalars(h, mix_only ? 1 : t, &a.s);
+  DeviceGuard guard(h->cfg.device);
+  if (guard.err != hipSuccess) return fail(h, DADAM_EHIP, "hipSetDevice: %s", hipGetErrorString(guard.err));
+  int e = tile_mode
+              ? launch_tile((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase, h->shape, a, w1 - w0, h->lds_bytes, stream)
+              : launch_direct((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase, a, w1 - w0, stream);
+  if (e != (int)hipSuccess)
+    return fail(h, DADAM_EHIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)e));
+  return DADAM_OK;
+}
+
+void free_slot(Slot& s) {
+  if (s.d_row_ptr) (void)hipFree(s.d_row_ptr);
+  if (s.d_col) (void)hipFree(s.d_col);
+  if (s.d_w) (void)hipFree(s.d_w);
+  s = Slot();
+}
+
+}  // namespace
+
+// -------------------------------------------------------------------------------------------------
+// C ABI
+// -------------------------------------------------------------------------------------------------
+extern "C" {
+
+int dadam_init(const dadam_config* cfg, dadam_handle** out) {
+  if (!cfg || !out) return fail(nullptr, DADAM_EINVAL, "cfg or out is null");
+  if (cfg->abi_version != DADAM_ABI_VERSION)
+    return fail(nullptr, DADAM_EINVAL, "abi_version %u, library has %u", cfg->abi_version, DADAM_ABI_VERSION);
+  if (cfg->n_rows == 0 || cfg->n_rows > DADAM_MAX_ROWS || cfg->n_cols == 0 || cfg->n_cols > DADAM_MAX_ROWS)
+    return fail(nullptr, DADAM_EINVAL, "n_rows and n_cols must be in [1, %u]", DADAM_MAX_ROWS);
+  if (cfg->d == 0) return fail(nullptr, DADAM_EINVAL, "d is zero");
+  if (cfg->d > (1ull << 40)) return fail(nullptr, DADAM_EINVAL, "d too large");
+  if (cfg->param_dtype > DADAM_BF16 || cfg->grad_dtype > DADAM_BF16)
+    return fail(nullptr, DADAM_EINVAL, "unknown dtype");
+  if (cfg->accum_s == 0) return fail(nullptr, DADAM_EINVAL, "accum_s must be >= 1");
+  if (!std::isfinite(cfg->lr)) return fail(nullptr, DADAM_EINVAL, "lr is not finite");
+  if (!(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f))
+    return fail(nullptr, DADAM_EINVAL, "betas must be in [0, 1)");
+  if (!(cfg->eps >= 0.f) || !std::isfinite(cfg->eps)) return fail(nullptr, DADAM_EINVAL, "eps must be finite and >= 0");
+  if (cfg->n_tensors > 0 && !cfg->tensors) return fail(nullptr, DADAM_EINVAL, "tensors is null");
+  if (cfg->n_tensors == 0) return fail(nullptr, DADAM_EINVAL, "the layout has no tensors");
+  if (cfg->device < 0 && cfg->device != DADAM_DEVICE_NONE) return fail(nullptr, DADAM_EINVAL, "bad device ordinal");
+  double betav = (double)cfg->beta2;
+  if (!std::isnan(cfg->beta_vhat) && cfg->beta_vhat >= 0.f) {
+    if (!(cfg->beta_vhat < 1.f)) return fail(nullptr, DADAM_EINVAL, "beta_vhat must be in [0, 1)");
+    betav = (double)cfg->beta_vhat;
+  }
+  uint64_t prev_end = 0;
+  for (uint32_t k = 0; k < cfg->n_tensors; ++k) {
+    const dadam_tensor_desc& t = cfg->tensors[k];
+    if (t.offset_elems < prev_end)
+      return fail(nullptr, DADAM_EINVAL, "tensor %u starts before tensor %u ends (list must be ordered and disjoint)", k, k ? k - 1 : 0);
+    if (t.numel > cfg->d || t.offset_elems > cfg->d - t.numel)
+      return fail(nullptr, DADAM_EINVAL, "tensor %u reaches beyond d", k);
+    if (t.weight_decay != 0.f || t.flags != 0)
+      return fail(nullptr, DADAM_EINVAL, "tensor %u: weight_decay and flags are reserved and must be 0", k);
+    prev_end = t.offset_elems + t.numel;
+  }
+  dadam_handle* h = new (std::nothrow) dadam_handle();
+  if (!h) return fail(nullptr, DADAM_EINVAL, "out of host memory");
+  h->cfg = *cfg;
+  h->tensors.assign(cfg->tensors, cfg->tensors + cfg->n_tensors);
+  h->cfg.tensors = nullptr;
+  h->lr = cfg->lr;
+  h->betav = betav;
+  for (int i = 0; i < kMaxRows; ++i) h->inplace_col[i] = -1;
+
+  // tile geometry: 16 bytes per lane and vector, `ut` vectors per lane, all source buffers' slices
+  // of one tile resident in LDS.  Two vectors per lane when that keeps the tile at or below 32 KB.
+  h->vec = vec_elems((int)cfg->param_dtype);
+  TileShape shape;
+  shape.ut = (cfg->n_cols * 2u * 1024u <= 32768u) ? 2 : 1;
+  shape.waves = cfg->n_rows >= 32 ? 8 : 4;
+  shape.ut = env_int("DADAM_TILE_UT", shape.ut);
+  shape.waves = env_int("DADAM_TILE_WAVES", shape.waves);
+  if (!tile_shape_supported(shape)) {
+    delete h;
+    return fail(nullptr, DADAM_EINVAL, "unsupported tile shape (waves %d, ut %d)", shape.waves, shape.ut);
+  }
+  h->shape = shape;
+  h->tile_elems = (uint32_t)(kWave * h->vec * shape.ut);
+  h->direct_elems = (uint32_t)(kDirectThreads * h->vec * direct_unroll());
+  h->lds_bytes = cfg->n_cols * (uint32_t)shape.ut * kWave * 16u;
+  h->tile_possible = h->lds_bytes <= 65536u;
+  int rc = plan(h);
+  if (rc) { delete h; return rc; }
+
+  if (cfg->device != DADAM_DEVICE_NONE) {
+    DeviceGuard guard(cfg->device);
+    hipError_t e = guard.err;
+    if (e == hipSuccess && !h->segs.empty()) {
+      e = hipMalloc((void**)&h->d_segs, h->segs.size() * sizeof(Segment));
+      if (e == hipSuccess)
+        e = hipMemcpy(h->d_segs, h->segs.data(), h->segs.size() * sizeof(Segment), hipMemcpyHostToDevice);
+    }
+    if (e != hipSuccess) {
+      if (h->d_segs) (void)hipFree(h->d_segs);
+      delete h;
+      return fail(nullptr, DADAM_EHIP, "device set-up failed: %s", hipGetErrorString(e));
+    }
+  }
+  *out = h;
+  return DADAM_OK;
+}
+
+int dadam_set_topology(dadam_handle* h, uint32_t slot_id, const int32_t* row_ptr, const int32_t* col_idx,
+                       const float* w, uint32_t* warn) {
+  if (!h) return DADAM_EINVAL;
+  if (warn) *warn = 0;
+  if (slot_id >= DADAM_MAX_SLOTS) return fail(h, DADAM_EINVAL, "slot %u out of range", slot_id);
+  if (!row_ptr || !col_idx || !w) return fail(h, DADAM_EINVAL, "null neighbour list");
+  const uint32_t R = h->cfg.n_rows, C = h->cfg.n_cols;
+  if (row_ptr[0] != 0) return fail(h, DADAM_ETOPO, "row_ptr[0] must be 0");
+  for (uint32_t i = 0; i < R; ++i) {
+    if (row_ptr[i + 1] <= row_ptr[i]) return fail(h, DADAM_ETOPO, "row %u is empty or row_ptr decreases", i);
+    if ((uint32_t)(row_ptr[i + 1] - row_ptr[i]) > C) return fail(h, DADAM_ETOPO, "row %u has more entries than sources", i);
+  }
+  const int32_t nnz = row_ptr[R];
+  std::vector<double> colsum(C, 0.0);
+  std::vector<int32_t> sole(C, -1);
+  bool reuse = false;
+  for (uint32_t i = 0; i < R; ++i) {
+    double sum = 0.0;
+    std::vector<char> seen(C, 0);
+    for (int32_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) {
+      int32_t c = col_idx[k];
+      if (c < 0 || (uint32_t)c >= C) return fail(h, DADAM_ETOPO, "row %u: column %d out of range", i, c);
+      if (seen[c]) return fail(h, DADAM_ETOPO, "row %u lists source %d twice", i, c);
+      seen[c] = 1;
+      if (!(w[k] > 0.f) || !std::isfinite(w[k])) return fail(h, DADAM_ETOPO, "row %u: weight %d is not finite and positive", i, k);
+      sum += (double)w[k];
+      colsum[c] += (double)w[k];
+      if (sole[c] == -1) sole[c] = (int32_t)i; else { sole[c] = -2; reuse = true; }
+    }
+    if (std::fabs(sum - 1.0) > 1e-5) return fail(h, DADAM_ETOPO, "row %u sums to %.9g, not 1", i, sum);
+  }
+  if (R == C && warn)
+    for (uint32_t c = 0; c < C; ++c)
+      if (std::fabs(colsum[c] - 1.0) > 1e-5) *warn |= DADAM_WARN_NOT_COLUMN_STOCHASTIC;
+
+  Slot fresh;
+  fresh.set = true;
+  fresh.row_ptr.assign(row_ptr, row_ptr + R + 1);
+  fresh.col.assign(col_idx, col_idx + nnz);
+  fresh.w.assign(w, w + nnz);
+  fresh.reuse = reuse;
+  fresh.sole_reader = sole;
+  if (h->cfg.device != DADAM_DEVICE_NONE) {
+    DeviceGuard guard(h->cfg.device);
+    hipError_t e = guard.err;
+    if (e == hipSuccess) e = hipMalloc((void**)&fresh.d_row_ptr, (R + 1) * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&fresh.d_col, (size_t)nnz * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&fresh.d_w, (size_t)nnz * sizeof(float));
+    if (e == hipSuccess) e = hipMemcpy(fresh.d_row_ptr, row_ptr, (R + 1) * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(fresh.d_col, col_idx, (size_t)nnz * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(fresh.d_w, w, (size_t)nnz * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      free_slot(fresh);
+      return fail(h, DADAM_EHIP, "uploading the neighbour list failed: %s", hipGetErrorString(e));
+    }
+  }
+  if (h->cfg.device != DADAM_DEVICE_NONE) {
+    DeviceGuard guard(h->cfg.device);
+    free_slot(h->slots[slot_id]);
+  }
+  h->slots[slot_id] = fresh;
+  return DADAM_OK;
+}
+
+int dadam_bind(dadam_handle* h, const dadam_buffers* b) {
+  if (!h) return DADAM_EINVAL;
+  if (!b || !b->x_src || !b->x_dst || !b->m_hat || !b->v_hat) return fail(h, DADAM_EINVAL, "null buffer table");
+  const uint32_t R = h->cfg.n_rows, C = h->cfg.n_cols;
+  if (!b->acc && h->cfg.accum_s > 1) return fail(h, DADAM_EINVAL, "acc table is null but accum_s > 1");
+  const size_t xb = h->cfg.d * dtype_bytes(h->cfg.param_dtype);
+  const size_t sb = h->cfg.d * 4;
+  std::vector<Interval> iv;
+  for (uint32_t c = 0; c < C; ++c) {
+    if (!b->x_src[c]) return fail(h, DADAM_EINVAL, "x_src[%u] is null", c);
+    if (!aligned16(b->x_src[c])) return fail(h, DADAM_EALIGN, "x_src[%u] is not 16-byte aligned", c);
+    iv.push_back({(uintptr_t)b->x_src[c], (uintptr_t)b->x_src[c] + xb, 0, (int)c});
+  }
+  for (uint32_t i = 0; i < R; ++i) {
+    const void* ps[4] = {b->x_dst[i], b->m_hat[i], b->v_hat[i], b->acc ? b->acc[i] : nullptr};
+    const char* names[4] = {"x_dst", "m_hat", "v_hat", "acc"};
+    for (int q = 0; q < 4; ++q) {
+      if (!ps[q]) {
+        if (q == 3 && h->cfg.accum_s == 1) continue;
+        return fail(h, DADAM_EINVAL, "%s[%u] is null", names[q], i);
+      }
+      if (!aligned16(ps[q])) return fail(h, DADAM_EALIGN, "%s[%u] is not 16-byte aligned", names[q], i);
+      iv.push_back({(uintptr_t)ps[q], (uintptr_t)ps[q] + (q == 0 ? xb : sb), q == 0 ? 1 : 2, (int)i});
+    }
+  }
+  int32_t inplace[kMaxRows];
+  for (int i = 0; i < kMaxRows; ++i) inplace[i] = -1;
+  for (size_t p = 0; p < iv.size(); ++p)
+    for (size_t q = p + 1; q < iv.size(); ++q) {
+      const Interval& a = iv[p];
+      const Interval& c = iv[q];
+      if (!overlaps(a, c)) continue;
+      if (a.kind == 0 && c.kind == 0) continue;  // two read-only sources may coincide
+      if (a.kind == 0 && c.kind == 1 && a.lo == c.lo) {  // update in place
+        if (inplace[c.index] < 0) inplace[c.index] = a.index;
+        continue;
+      }
+      return fail(h, DADAM_EALIAS, "buffers overlap: kind %d index %d and kind %d index %d (0 x_src, 1 x_dst, 2 state)",
+                  a.kind, a.index, c.kind, c.index);
+    }
+  for (uint32_t c = 0; c < C; ++c) h->x_src[c] = b->x_src[c];
+  for (uint32_t i = 0; i < R; ++i) {
+    h->x_dst[i] = b->x_dst[i];
+    h->m_hat[i] = b->m_hat[i];
+    h->v_hat[i] = b->v_hat[i];
+    h->acc[i] = b->acc ? b->acc[i] : nullptr;
+    h->inplace_col[i] = inplace[i];
+  }
+  h->bound = true;
+  return DADAM_OK;
+}
+
+int dadam_swap_x(dadam_handle* h) {
+  if (!h) return DADAM_EINVAL;
+  if (!h->bound) return fail(h, DADAM_ESTATE, "no buffers bound");
+  if (h->cfg.n_rows != h->cfg.n_cols) return fail(h, DADAM_ESTATE, "swap needs n_rows == n_cols");
+  for (uint32_t i = 0; i < h->cfg.n_rows; ++i) {
+    if (h->inplace_col[i] >= 0) continue;  // in-place rows stay as they are
+    void* s = const_cast<void*>(h->x_src[i]);
+    h->x_src[i] = h->x_dst[i];
+    h->x_dst[i] = s;
+  }
+  return DADAM_OK;
+}
+
+int dadam_gossip_step(dadam_handle* h, uint32_t slot, const void* const* grads, uint64_t t, uint32_t flags,
+                      void* hip_stream) {
+  return step_impl(h, slot, grads, t, flags, true, 0, 0, false, hip_stream);
+}
+
+int dadam_gossip_step_range(dadam_handle* h, uint32_t slot, const void* const* grads, uint64_t t,
+                            uint32_t flags, uint32_t tensor_begin, uint32_t tensor_end, void* hip_stream) {
+  return step_impl(h, slot, grads, t, flags, false, tensor_begin, tensor_end, false, hip_stream);
+}
+
+int dadam_mix(dadam_handle* h, uint32_t slot, uint32_t flags, void* hip_stream) {
+  if (h && (flags & DADAM_FUSE_ACCUM)) return fail(h, DADAM_EINVAL, "dadam_mix takes only the FORCE flags");
+  return step_impl(h, slot, nullptr, 1, flags, true, 0, 0, true, hip_stream);
+}
+
+int dadam_accumulate(dadam_handle* h, const void* const* grads, uint64_t t, void* hip_stream) {
+  if (!h) return DADAM_EINVAL;
+  int rc = check_launchable(h);
+  if (rc) return rc;
+  if (t == 0) return fail(h, DADAM_EINVAL, "iterations are numbered from 1");
+  rc = check_grads(h, grads);
+  if (rc) return rc;
+  if (h->cfg.accum_s > 1)
+    for (uint32_t i = 0; i < h->cfg.n_rows; ++i)
+      if (!h->acc[i]) return fail(h, DADAM_ESTATE, "accumulator of row %u is not bound", i);
+  if (h->segs.empty()) return DADAM_OK;
+  StepArgs a;
+  fill_args(h, nullptr, grads, &a);
+  uint32_t w0 = 0, w1 = 0;
+  work_range(h, false, 0, (uint32_t)h->segs.size() - 1, h->segs.front().lo, h->segs.back().hi, &w0, &w1);
+  a.work_begin = w0;
+  a.clip_lo = h->segs.front().lo;
+  a.clip_hi = h->segs.back().hi;
+  fill_scalars(h, t, &a.s);
+  DeviceGuard guard(h->cfg.device);
+  if (guard.err != hipSuccess) return fail(h, DADAM_EHIP, "hipSetDevice: %s", hipGetErrorString(guard.err));
+  int e = launch_accumulate((int)h->cfg.grad_dtype, fused_phase(h, t), a, w1 - w0, hip_stream, h->vec);
+  if (e != (int)hipSuccess)
+    return fail(h, DADAM_EHIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)e));
+  return DADAM_OK;
+}
+
+int dadam_set_lr(dadam_handle* h, float lr) {
+  if (!h) return DADAM_EINVAL;
+  if (!std::isfinite(lr)) return fail(h, DADAM_EINVAL, "lr is not finite");
+  h->lr = lr;
+  return DADAM_OK;
+}
+
+int dadam_get_plan_info(const dadam_handle* h, dadam_plan_info* out) {
+  if (!h || !out) return DADAM_EINVAL;
+  out->n_segments = (uint32_t)h->segs.size();
+  out->tile_elems = h->tile_elems;
+  out->direct_elems = h->direct_elems;
+  out->n_tiles_tile = h->n_work_t;
+  out->n_tiles_direct = h->n_work_d;
+  out->lds_bytes_tile = h->lds_bytes;
+  out->tile_mode_possible = h->tile_possible ? 1u : 0u;
+  return DADAM_OK;
+}
+
+int dadam_slot_uses_tile_mode(const dadam_handle* h, uint32_t slot) {
+  if (!h) return DADAM_EINVAL;
+  if (slot >= DADAM_MAX_SLOTS || !h->slots[slot].set) return fail(h, DADAM_ESTATE, "topology slot %u is not set", slot);
+  bool tile = false;
+  int rc = choose_mode(h, h->slots[slot], 0, &tile);
+  if (rc) return rc;
+  return tile ? 1 : 0;
+}
+
+int dadam_pack_offsets(const uint64_t* numel, uint32_t n, uint32_t align_elems, uint64_t* offsets, uint64_t* d_out) {
+  if (!numel || !offsets || !d_out || align_elems == 0) return DADAM_EINVAL;
+  uint64_t cur = 0;
+  for (uint32_t k = 0; k < n; ++k) {
+    offsets[k] = cur;
+    cur += (numel[k] + align_elems - 1) / align_elems * align_elems;
+  }
+  *d_out = cur;
+  return DADAM_OK;
+}
+
+const char* dadam_last_error(const dadam_handle* h) { return h ? h->err.c_str() : g_init_error.c_str(); }
+
+void dadam_destroy(dadam_handle* h) {
+  if (!h) return;
+  if (h->cfg.device != DADAM_DEVICE_NONE) {
+    DeviceGuard guard(h->cfg.device);
+    for (Slot& s : h->slots) free_slot(s);
+    if (h->d_segs) (void)hipFree(h->d_segs);
+  }
+  delete h;
+}
+
+}  // extern "C"

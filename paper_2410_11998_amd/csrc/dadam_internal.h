@@ -1,0 +1,88 @@
+// Internal interface between the host side of libdadam (validation, planning, launch set-up) and
+// the gfx950 kernels.  Nothing in here is part of the public C ABI (see include/dadam.h).
+#ifndef DADAM_INTERNAL_H_
+#define DADAM_INTERNAL_H_
+
+#include <stdint.h>
+
+#include "dadam.h"
+
+namespace dadam {
+
+constexpr int kMaxRows = DADAM_MAX_ROWS;
+constexpr int kWave = 64;            // gfx950 wavefront
+constexpr int kDirectThreads = 256;  // workgroup of the direct and accumulate kernels
+
+// A maximal run of contiguous tensors: elements [lo, hi) of every buffer.  Work items are tiles of a
+// fixed grid anchored at element 0, so that vector accesses are 16-byte aligned whenever the
+// buffers are; a tile that sticks out of [lo, hi) is clipped element by element.
+struct Segment {
+  uint64_t lo, hi;
+  uint64_t first_tile_t;  // index of the first tile-mode tile that intersects the segment
+  uint64_t first_tile_d;  // same for direct-mode tiles
+  uint32_t work0_t;       // number of tile-mode work items in earlier segments
+  uint32_t work0_d;       // same for direct mode (per row)
+};
+
+// Scalars of one iteration, computed on the host in double and rounded once.
+struct Scalars {
+  float beta1, omb1;     // beta1, 1 - beta1
+  float beta2, omb2;     // beta2, 1 - beta2
+  float betav, ombv;     // decay of v_hat in the fold and its complement
+  float inv_c1, inv_c2;  // 1 / (1 - beta1^t_hat), 1 / (1 - beta2^t_hat)
+  float eps, lr, inv_s;
+};
+
+// What a step does with the optimizer state (Algorithm 3, lines 6-13).
+enum Phase : int {
+  kMixOnly = 0,     // x_dst = W x_src
+  kUpdateOnly = 1,  // lines 6-8 only
+  kPlain = 2,       // lines 6-9, inside a loop
+  kLoopStart = 3,   // lines 6-9, first iteration of a loop: b is known to be zero and not read
+  kFold = 4,        // lines 6-13, last iteration of a loop (s > 1)
+  kAlg1 = 5,        // s == 1: Algorithm 1, moments updated every iteration, no accumulator
+  kNumPhases = 6
+};
+
+// Kernel argument block (passed by value; about 3.2 KB of the 4 KB kernarg segment).
+struct StepArgs {
+  const void* x_src[kMaxRows];
+  void* x_dst[kMaxRows];
+  float* m_hat[kMaxRows];
+  float* v_hat[kMaxRows];
+  float* acc[kMaxRows];
+  const void* grad[kMaxRows];
+  const int32_t* row_ptr;  // device CSR of the slot
+  const int32_t* col;
+  const float* w;
+  const Segment* seg;  // device
+  uint32_t n_seg;
+  uint32_t n_rows, n_cols;
+  uint32_t work_begin;  // first work item (in tiles) of this launch
+  uint64_t clip_lo, clip_hi;  // element range of this launch (whole layout or a tensor range)
+  Scalars s;
+};
+
+struct TileShape {
+  int waves;  // wavefronts per workgroup (rows are dealt round-robin to them)
+  int ut;     // 16-byte vectors per lane and row
+};
+
+// Launchers.  All of them enqueue on `stream` and return the hipError_t of the launch as int.
+// xdt / gdt are DADAM_F32 | DADAM_BF16.  n_work is the number of tiles in this launch.
+int launch_tile(int xdt, int gdt, Phase phase, TileShape shape, const StepArgs& a, uint32_t n_work,
+                uint32_t lds_bytes, void* stream);
+int launch_direct(int xdt, int gdt, Phase phase, const StepArgs& a, uint32_t n_work_tiles,
+                  void* stream);
+// vec = elements per direct-mode parameter vector of the handle (fixes the tile grid).
+int launch_accumulate(int gdt, Phase phase, const StepArgs& a, uint32_t n_work_tiles, void* stream,
+                      int vec);
+
+// Geometry the host planner needs.
+int vec_elems(int xdt);              // elements per 16-byte parameter vector: 4 (f32) or 8 (bf16)
+int direct_unroll();                 // vectors per thread in the direct and accumulate kernels
+bool tile_shape_supported(TileShape s);
+
+}  // namespace dadam
+
+#endif  // DADAM_INTERNAL_H_

@@ -1,0 +1,688 @@
+// gfx950 kernels of the decentralized (accumulated) Adam step and their launchers.
+//
+// The work is streaming and elementwise over the packed parameter vector; neighbour mixing couples
+// replicas, never elements.  Three kernels:
+//
+//   k_tile    one workgroup owns a tile of elements for ALL rows: every source buffer's slice of the
+//             tile is read from HBM once and parked in LDS, then the wavefronts of the group deal the
+//             rows among themselves and update each from LDS.  Lane l of every wavefront works on
+//             the same elements for all rows, so LDS is a per-lane indexable store - no lane ever
+//             reads what another lane wrote, one barrier separates staging from use.  All sources
+//             of the tile are read before anything is written, so updating in place is legal.
+//   k_direct  one workgroup updates one tile of one row and streams the row's sources from global
+//             memory (a node's own parameters plus receive buffers: no source is shared by two rows).
+//   k_acc     accumulate / fold only (Algorithm 3 lines 9-13).
+//
+// Every access of a full tile is a 128-bit load or store per lane; lanes at the ragged edge of a
+// segment fall back to element accesses.  Neighbour lists are read once per row as one coalesced
+// load (one entry per lane) and handed out with readlane, so the inner loop has no dependent
+// scalar memory traffic.
+#include <hip/hip_runtime.h>
+
+#include "dadam_internal.h"
+
+namespace dadam {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+
+struct TF32 {
+  static constexpr int id = DADAM_F32;
+  static constexpr int bytes = 4;
+};
+struct TBF16 {
+  static constexpr int id = DADAM_BF16;
+  static constexpr int bytes = 2;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// float32 -> bfloat16, round to nearest even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  uint32_t r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+  return (f != f) ? ((u >> 16) | 0x40u) : r;
+}
+
+template <typename T>
+__device__ __forceinline__ float load_elem(const void* base, uint64_t e) {
+  if constexpr (T::bytes == 4) {
+    return reinterpret_cast<const float*>(base)[e];
+  } else {
+    return bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(base)[e]);
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ void store_elem(void* base, uint64_t e, float v) {
+  if constexpr (T::bytes == 4) {
+    reinterpret_cast<float*>(base)[e] = v;
+  } else {
+    reinterpret_cast<uint16_t*>(base)[e] = (uint16_t)f32_to_bf16_bits(v);
+  }
+}
+
+// VEC consecutive elements of type T starting at element e (e a multiple of VEC * ... such that the
+// address is 16-byte aligned), widened to float.  MASKED lanes that are not wholly inside [lo, hi)
+// touch only the elements that are; the others read as zero.
+template <typename T, int VEC, bool MASKED>
+__device__ __forceinline__ void load_vals(const void* base, uint64_t e, uint64_t lo, uint64_t hi,
+                                          float (&out)[VEC]) {
+  if (!MASKED || (e >= lo && e + VEC <= hi)) {
+    if constexpr (T::bytes == 4) {
+      const f4* p = reinterpret_cast<const f4*>(reinterpret_cast<const float*>(base) + e);
+#pragma unroll
+      for (int q = 0; q < VEC / 4; ++q) {
+        f4 v = p[q];
+        out[4 * q + 0] = v.x; out[4 * q + 1] = v.y; out[4 * q + 2] = v.z; out[4 * q + 3] = v.w;
+      }
+    } else if constexpr (VEC == 8) {
+      u4 v = *reinterpret_cast<const u4*>(reinterpret_cast<const uint16_t*>(base) + e);
+      out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xFFFF0000u);
+      out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xFFFF0000u);
+      out[4] = __uint_as_float(v.z << 16); out[5] = __uint_as_float(v.z & 0xFFFF0000u);
+      out[6] = __uint_as_float(v.w << 16); out[7] = __uint_as_float(v.w & 0xFFFF0000u);
+    } else {
+      u2 v = *reinterpret_cast<const u2*>(reinterpret_cast<const uint16_t*>(base) + e);
+      out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xFFFF0000u);
+      out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xFFFF0000u);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      uint64_t ej = e + j;
+      out[j] = (ej >= lo && ej < hi) ? load_elem<T>(base, ej) : 0.0f;
+    }
+  }
+}
+
+template <typename T, int VEC, bool MASKED>
+__device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, uint64_t hi,
+                                           const float (&in)[VEC]) {
+  if (!MASKED || (e >= lo && e + VEC <= hi)) {
+    if constexpr (T::bytes == 4) {
+      f4* p = reinterpret_cast<f4*>(reinterpret_cast<float*>(base) + e);
+#pragma unroll
+      for (int q = 0; q < VEC / 4; ++q) {
+        f4 v;
+        v.x = in[4 * q + 0]; v.y = in[4 * q + 1]; v.z = in[4 * q + 2]; v.w = in[4 * q + 3];
+        p[q] = v;
+      }
+    } else if constexpr (VEC == 8) {
+      u4 v;
+      v.x = f32_to_bf16_bits(in[0]) | (f32_to_bf16_bits(in[1]) << 16);
+      v.y = f32_to_bf16_bits(in[2]) | (f32_to_bf16_bits(in[3]) << 16);
+      v.z = f32_to_bf16_bits(in[4]) | (f32_to_bf16_bits(in[5]) << 16);
+      v.w = f32_to_bf16_bits(in[6]) | (f32_to_bf16_bits(in[7]) << 16);
+      *reinterpret_cast<u4*>(reinterpret_cast<uint16_t*>(base) + e) = v;
+    } else {
+      u2 v;
+      v.x = f32_to_bf16_bits(in[0]) | (f32_to_bf16_bits(in[1]) << 16);
+      v.y = f32_to_bf16_bits(in[2]) | (f32_to_bf16_bits(in[3]) << 16);
+      *reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(base) + e) = v;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      uint64_t ej = e + j;
+      if (ej >= lo && ej < hi) store_elem<T>(base, ej, in[j]);
+    }
+  }
+}
+
+// The 16 raw bytes of a parameter vector (4 float32 or 8 bfloat16), as they are parked in LDS.
+template <typename XT, bool MASKED>
+__device__ __forceinline__ u4 load_raw(const void* base, uint64_t e, uint64_t lo, uint64_t hi) {
+  constexpr int VEC = 16 / XT::bytes;
+  if (!MASKED || (e >= lo && e + VEC <= hi)) {
+    return *reinterpret_cast<const u4*>(reinterpret_cast<const char*>(base) + e * XT::bytes);
+  }
+  u4 r = {0u, 0u, 0u, 0u};
+  if constexpr (XT::bytes == 4) {
+    const uint32_t* p = reinterpret_cast<const uint32_t*>(base);
+    if (e + 0 >= lo && e + 0 < hi) r.x = p[e + 0];
+    if (e + 1 >= lo && e + 1 < hi) r.y = p[e + 1];
+    if (e + 2 >= lo && e + 2 < hi) r.z = p[e + 2];
+    if (e + 3 >= lo && e + 3 < hi) r.w = p[e + 3];
+  } else {
+    const uint16_t* p = reinterpret_cast<const uint16_t*>(base);
+    uint32_t h[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) h[j] = (e + j >= lo && e + j < hi) ? (uint32_t)p[e + j] : 0u;
+    r.x = h[0] | (h[1] << 16); r.y = h[2] | (h[3] << 16);
+    r.z = h[4] | (h[5] << 16); r.w = h[6] | (h[7] << 16);
+  }
+  return r;
+}
+
+template <typename XT>
+__device__ __forceinline__ void unpack_raw(u4 r, float (&out)[16 / XT::bytes]) {
+  if constexpr (XT::bytes == 4) {
+    out[0] = __uint_as_float(r.x); out[1] = __uint_as_float(r.y);
+    out[2] = __uint_as_float(r.z); out[3] = __uint_as_float(r.w);
+  } else {
+    out[0] = __uint_as_float(r.x << 16); out[1] = __uint_as_float(r.x & 0xFFFF0000u);
+    out[2] = __uint_as_float(r.y << 16); out[3] = __uint_as_float(r.y & 0xFFFF0000u);
+    out[4] = __uint_as_float(r.z << 16); out[5] = __uint_as_float(r.z & 0xFFFF0000u);
+    out[6] = __uint_as_float(r.w << 16); out[7] = __uint_as_float(r.w & 0xFFFF0000u);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Algorithm 3, lines 6-13, for one element.  mix is the finished neighbour sum of line 8.
+// Returns x^(t); updates mh, vh, b in registers according to the phase.
+// ---------------------------------------------------------------------------------------------
+template <int PHASE>
+__device__ __forceinline__ float element_step(const Scalars& s, float mix, float g, float& mh,
+                                              float& vh, float& b) {
+  if constexpr (PHASE == kMixOnly) return mix;
+  // lines 6-7: temporary moments from the persistent ones and the fresh gradient
+  float m = fmaf(s.beta1, mh, s.omb1 * g);
+  float v = fmaf(s.beta2, vh, s.omb2 * (g * g));
+  // line 8: bias correction with exponent t_hat, epsilon outside the root
+  float denom = sqrtf(v * s.inv_c2) + s.eps;
+  float u = (m * s.inv_c1) / denom;
+  float x = fmaf(-s.lr, u, mix);
+  // line 9
+  if constexpr (PHASE == kPlain || PHASE == kFold) b = fmaf(g, s.inv_s, b);
+  if constexpr (PHASE == kLoopStart || PHASE == kAlg1) b = g * s.inv_s;
+  // lines 10-13
+  if constexpr (PHASE == kFold || PHASE == kAlg1) {
+    mh = fmaf(s.beta1, mh, s.omb1 * b);
+    vh = fmaf(s.betav, vh, s.ombv * (b * b));
+    b = 0.0f;
+  }
+  return x;
+}
+
+template <int PHASE>
+struct Needs {
+  static constexpr bool grad = PHASE != kMixOnly;
+  static constexpr bool moments_in = PHASE != kMixOnly;
+  static constexpr bool acc_in = PHASE == kPlain || PHASE == kFold;
+  static constexpr bool acc_out = PHASE == kPlain || PHASE == kLoopStart || PHASE == kFold;
+  static constexpr bool moments_out = PHASE == kFold || PHASE == kAlg1;
+};
+
+// Which segment does work item `work` belong to, and which tile of the fixed grid is it?
+template <bool TILE_MODE>
+__device__ __forceinline__ void locate(const StepArgs& a, uint32_t work, uint64_t& tile_index,
+                                       uint64_t& lo, uint64_t& hi) {
+  uint32_t s = 0;
+  if (a.n_seg > 1) {
+    uint32_t l = 0, r = a.n_seg;
+    while (r - l > 1) {
+      uint32_t mid = (l + r) >> 1;
+      uint32_t w0 = TILE_MODE ? a.seg[mid].work0_t : a.seg[mid].work0_d;
+      if (w0 <= work) l = mid; else r = mid;
+    }
+    s = l;
+  }
+  const Segment sg = a.seg[s];
+  tile_index = (TILE_MODE ? sg.first_tile_t : sg.first_tile_d) + (work - (TILE_MODE ? sg.work0_t : sg.work0_d));
+  lo = sg.lo > a.clip_lo ? sg.lo : a.clip_lo;
+  hi = sg.hi < a.clip_hi ? sg.hi : a.clip_hi;
+}
+
+// Row i's slice of the neighbour list, one entry per lane, and its bounds as wave-uniform values.
+struct RowList {
+  int32_t col_v;
+  float w_v;
+  int deg;
+};
+
+__device__ __forceinline__ RowList load_row_list(const StepArgs& a, int row, int lane) {
+  // row_ptr entries are read by every lane from the same address (one broadcast transaction)
+  int k0 = __builtin_amdgcn_readfirstlane(a.row_ptr[row]);
+  int k1 = __builtin_amdgcn_readfirstlane(a.row_ptr[row + 1]);
+  RowList r;
+  r.deg = k1 - k0;  // host guarantees 1 <= deg <= n_cols <= 64
+  int idx = k0 + (lane < r.deg ? lane : 0);
+  r.col_v = a.col[idx];
+  r.w_v = a.w[idx];
+  return r;
+}
+
+__device__ __forceinline__ int list_col(const RowList& r, int k) {
+  return __builtin_amdgcn_readlane(r.col_v, k);
+}
+__device__ __forceinline__ float list_w(const RowList& r, int k) {
+  return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(r.w_v), k));
+}
+
+// ---------------------------------------------------------------------------------------------
+// tile mode
+// ---------------------------------------------------------------------------------------------
+template <typename XT, typename GT, int PHASE, int W, int UT, bool MASKED>
+__device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t tbase, uint64_t lo,
+                                          uint64_t hi, int lane, int wave) {
+  constexpr int VEC = 16 / XT::bytes;
+  uint64_t e[UT];
+#pragma unroll
+  for (int u = 0; u < UT; ++u) e[u] = tbase + (uint64_t)(u * kWave + lane) * VEC;
+
+  // stage every source buffer's slice of the tile: HBM -> registers -> LDS, once
+  const int n_cols = (int)a.n_cols;
+  for (int c = wave; c < n_cols; c += W) {
+    const void* src = a.x_src[c];
+    u4 r[UT];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) r[u] = load_raw<XT, MASKED>(src, e[u], lo, hi);
+#pragma unroll
+    for (int u = 0; u < UT; ++u) lds[(c * UT + u) * kWave + lane] = r[u];
+  }
+  __syncthreads();
+
+  const int n_rows = (int)a.n_rows;
+  for (int i = wave; i < n_rows; i += W) {
+    RowList rl = load_row_list(a, i, lane);
+    float g[UT][VEC], mh[UT][VEC], vh[UT][VEC], b[UT][VEC];
+    if constexpr (Needs<PHASE>::grad) {
+      const void* gp = a.grad[i];
+#pragma unroll
+      for (int u = 0; u < UT; ++u) load_vals<GT, VEC, MASKED>(gp, e[u], lo, hi, g[u]);
+    }
+    if constexpr (Needs<PHASE>::moments_in) {
+      const float* mp = a.m_hat[i];
+      const float* vp = a.v_hat[i];
+#pragma unroll
+      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+#pragma unroll
+      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+    }
+    if constexpr (Needs<PHASE>::acc_in) {
+      const float* bp = a.acc[i];
+#pragma unroll
+      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+    }
+
+    // neighbour sum in the order the row lists its entries: first a product, then fused
+    // multiply-adds
+    float mix[UT][VEC];
+    {
+      const int c0 = list_col(rl, 0);
+      const float w0 = list_w(rl, 0);
+#pragma unroll
+      for (int u = 0; u < UT; ++u) {
+        float xs[VEC];
+        unpack_raw<XT>(lds[(c0 * UT + u) * kWave + lane], xs);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) mix[u][j] = w0 * xs[j];
+      }
+    }
+    for (int k = 1; k < rl.deg; ++k) {
+      const int c = list_col(rl, k);
+      const float wk = list_w(rl, k);
+#pragma unroll
+      for (int u = 0; u < UT; ++u) {
+        float xs[VEC];
+        unpack_raw<XT>(lds[(c * UT + u) * kWave + lane], xs);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) mix[u][j] = fmaf(wk, xs[j], mix[u][j]);
+      }
+    }
+
+    float xo[UT][VEC];
+#pragma unroll
+    for (int u = 0; u < UT; ++u)
+#pragma unroll
+      for (int j = 0; j < VEC; ++j)
+        xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j]);
+
+    void* xd = a.x_dst[i];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) store_vals<XT, VEC, MASKED>(xd, e[u], lo, hi, xo[u]);
+    if constexpr (Needs<PHASE>::acc_out) {
+      float* bp = a.acc[i];
+#pragma unroll
+      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+    }
+    if constexpr (Needs<PHASE>::moments_out) {
+      float* mp = a.m_hat[i];
+      float* vp = a.v_hat[i];
+#pragma unroll
+      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+#pragma unroll
+      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+    }
+  }
+}
+
+template <typename XT, typename GT, int PHASE, int W, int UT>
+__global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
+  constexpr int VEC = 16 / XT::bytes;
+  constexpr uint64_t TILE = (uint64_t)kWave * VEC * UT;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_bytes[];
+  u4* lds = reinterpret_cast<u4*>(lds_bytes);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  uint64_t tile_index, lo, hi;
+  locate<true>(a, a.work_begin + blockIdx.x, tile_index, lo, hi);
+  const uint64_t tbase = tile_index * TILE;
+  if (tbase >= lo && tbase + TILE <= hi) {
+    tile_body<XT, GT, PHASE, W, UT, false>(a, lds, tbase, lo, hi, lane, wave);
+  } else {
+    tile_body<XT, GT, PHASE, W, UT, true>(a, lds, tbase, lo, hi, lane, wave);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// direct mode
+// ---------------------------------------------------------------------------------------------
+constexpr int kUD = 2;  // 16-byte parameter vectors per thread
+
+// Neighbour sum with all loads of DEG sources issued before the first use.  DEG == 0: any degree.
+template <typename XT, int DEG, bool MASKED>
+__device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
+                                           const uint64_t (&e)[kUD], uint64_t lo, uint64_t hi,
+                                           float (&mix)[kUD][16 / XT::bytes]) {
+  constexpr int VEC = 16 / XT::bytes;
+  if constexpr (DEG > 0) {
+    u4 r[DEG][kUD];
+    float wk[DEG];
+#pragma unroll
+    for (int k = 0; k < DEG; ++k) {
+      const void* src = a.x_src[list_col(rl, k)];
+      wk[k] = list_w(rl, k);
+#pragma unroll
+      for (int u = 0; u < kUD; ++u) r[k][u] = load_raw<XT, MASKED>(src, e[u], lo, hi);
+    }
+#pragma unroll
+    for (int k = 0; k < DEG; ++k)
+#pragma unroll
+      for (int u = 0; u < kUD; ++u) {
+        float xs[VEC];
+        unpack_raw<XT>(r[k][u], xs);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) mix[u][j] = (k == 0) ? wk[0] * xs[j] : fmaf(wk[k], xs[j], mix[u][j]);
+      }
+  } else {
+    {
+      const void* src = a.x_src[list_col(rl, 0)];
+      const float w0 = list_w(rl, 0);
+#pragma unroll
+      for (int u = 0; u < kUD; ++u) {
+        float xs[VEC];
+        unpack_raw<XT>(load_raw<XT, MASKED>(src, e[u], lo, hi), xs);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) mix[u][j] = w0 * xs[j];
+      }
+    }
+    for (int k = 1; k < rl.deg; ++k) {
+      const void* src = a.x_src[list_col(rl, k)];
+      const float wk = list_w(rl, k);
+#pragma unroll
+      for (int u = 0; u < kUD; ++u) {
+        float xs[VEC];
+        unpack_raw<XT>(load_raw<XT, MASKED>(src, e[u], lo, hi), xs);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) mix[u][j] = fmaf(wk, xs[j], mix[u][j]);
+      }
+    }
+  }
+}
+
+template <typename XT, typename GT, int PHASE, bool MASKED>
+__device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t tbase, uint64_t lo,
+                                            uint64_t hi, int lane) {
+  constexpr int VEC = 16 / XT::bytes;
+  uint64_t e[kUD];
+#pragma unroll
+  for (int u = 0; u < kUD; ++u) e[u] = tbase + (uint64_t)(u * kDirectThreads + threadIdx.x) * VEC;
+  // the neighbour list is fetched while every lane is still active: readlane below must find a
+  // loaded value in whichever lane it asks
+  RowList rl = load_row_list(a, row, lane);
+  if (MASKED) {
+    // a thread whose vectors all lie outside the range has nothing to do (no barrier in this kernel)
+    bool any = false;
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) any = any || (e[u] < hi && e[u] + VEC > lo);
+    if (!any) return;
+  }
+  float g[kUD][VEC], mh[kUD][VEC], vh[kUD][VEC], b[kUD][VEC];
+  if constexpr (Needs<PHASE>::grad) {
+    const void* gp = a.grad[row];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, MASKED>(gp, e[u], lo, hi, g[u]);
+  }
+  if constexpr (Needs<PHASE>::moments_in) {
+    const float* mp = a.m_hat[row];
+    const float* vp = a.v_hat[row];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+  }
+  if constexpr (Needs<PHASE>::acc_in) {
+    const float* bp = a.acc[row];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+  }
+  float mix[kUD][VEC];
+  switch (rl.deg) {
+    case 1: mix_direct<XT, 1, MASKED>(a, rl, e, lo, hi, mix); break;
+    case 2: mix_direct<XT, 2, MASKED>(a, rl, e, lo, hi, mix); break;
+    case 3: mix_direct<XT, 3, MASKED>(a, rl, e, lo, hi, mix); break;
+    case 4: mix_direct<XT, 4, MASKED>(a, rl, e, lo, hi, mix); break;
+    case 5: mix_direct<XT, 5, MASKED>(a, rl, e, lo, hi, mix); break;
+    default: mix_direct<XT, 0, MASKED>(a, rl, e, lo, hi, mix); break;
+  }
+  float xo[kUD][VEC];
+#pragma unroll
+  for (int u = 0; u < kUD; ++u)
+#pragma unroll
+    for (int j = 0; j < VEC; ++j)
+      xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j]);
+  void* xd = a.x_dst[row];
+#pragma unroll
+  for (int u = 0; u < kUD; ++u) store_vals<XT, VEC, MASKED>(xd, e[u], lo, hi, xo[u]);
+  if constexpr (Needs<PHASE>::acc_out) {
+    float* bp = a.acc[row];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+  }
+  if constexpr (Needs<PHASE>::moments_out) {
+    float* mp = a.m_hat[row];
+    float* vp = a.v_hat[row];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+  }
+}
+
+// Work items are numbered tile-major, row-minor, so that workgroups running at the same time work
+// on the same elements of different rows.
+template <typename XT, typename GT, int PHASE>
+__global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
+  constexpr int VEC = 16 / XT::bytes;
+  constexpr uint64_t TILE = (uint64_t)kDirectThreads * VEC * kUD;
+  const int lane = threadIdx.x & (kWave - 1);
+  const uint32_t n_rows = a.n_rows;
+  const uint32_t t = blockIdx.x / n_rows;
+  const int row = (int)(blockIdx.x - t * n_rows);
+  uint64_t tile_index, lo, hi;
+  locate<false>(a, a.work_begin + t, tile_index, lo, hi);
+  const uint64_t tbase = tile_index * TILE;
+  if (tbase >= lo && tbase + TILE <= hi) {
+    direct_body<XT, GT, PHASE, false>(a, row, tbase, lo, hi, lane);
+  } else {
+    direct_body<XT, GT, PHASE, true>(a, row, tbase, lo, hi, lane);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// accumulate / fold only (Algorithm 3 lines 9-13).  Tiles have the direct-mode size of a float32
+// layout: 4 elements per 16-byte state vector.
+// ---------------------------------------------------------------------------------------------
+template <int PHASE>
+__device__ __forceinline__ void acc_step(const Scalars& s, float g, float& mh, float& vh, float& b) {
+  if constexpr (PHASE == kPlain || PHASE == kFold) b = fmaf(g, s.inv_s, b);
+  if constexpr (PHASE == kLoopStart || PHASE == kAlg1) b = g * s.inv_s;
+  if constexpr (PHASE == kFold || PHASE == kAlg1) {
+    mh = fmaf(s.beta1, mh, s.omb1 * b);
+    vh = fmaf(s.betav, vh, s.ombv * (b * b));
+    b = 0.0f;
+  }
+}
+
+template <typename GT, int VEC, int PHASE, bool MASKED>
+__device__ __forceinline__ void acc_body(const StepArgs& a, int row, uint64_t tbase, uint64_t lo,
+                                         uint64_t hi) {
+  uint64_t e[kUD];
+#pragma unroll
+  for (int u = 0; u < kUD; ++u) e[u] = tbase + (uint64_t)(u * kDirectThreads + threadIdx.x) * VEC;
+  float g[kUD][VEC], mh[kUD][VEC], vh[kUD][VEC], b[kUD][VEC];
+  const void* gp = a.grad[row];
+#pragma unroll
+  for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, MASKED>(gp, e[u], lo, hi, g[u]);
+  if constexpr (Needs<PHASE>::moments_out) {
+    const float* mp = a.m_hat[row];
+    const float* vp = a.v_hat[row];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+  }
+  if constexpr (Needs<PHASE>::acc_in) {
+    const float* bp = a.acc[row];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < kUD; ++u)
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc_step<PHASE>(a.s, g[u][j], mh[u][j], vh[u][j], b[u][j]);
+  if constexpr (Needs<PHASE>::acc_out) {
+    float* bp = a.acc[row];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+  }
+  if constexpr (Needs<PHASE>::moments_out) {
+    float* mp = a.m_hat[row];
+    float* vp = a.v_hat[row];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+  }
+}
+
+// VEC is the element count of a direct-mode parameter vector of this handle, so that the
+// accumulate kernel walks the same tile grid as the direct kernel.
+template <typename GT, int VEC, int PHASE>
+__global__ __launch_bounds__(kDirectThreads) void k_acc(const StepArgs a) {
+  constexpr uint64_t TILE = (uint64_t)kDirectThreads * VEC * kUD;
+  const uint32_t n_rows = a.n_rows;
+  const uint32_t t = blockIdx.x / n_rows;
+  const int row = (int)(blockIdx.x - t * n_rows);
+  uint64_t tile_index, lo, hi;
+  locate<false>(a, a.work_begin + t, tile_index, lo, hi);
+  const uint64_t tbase = tile_index * TILE;
+  if (tbase >= lo && tbase + TILE <= hi) {
+    acc_body<GT, VEC, PHASE, false>(a, row, tbase, lo, hi);
+  } else {
+    acc_body<GT, VEC, PHASE, true>(a, row, tbase, lo, hi);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dispatch tables
+// ---------------------------------------------------------------------------------------------
+typedef void (*KernelFn)(const StepArgs);
+
+template <typename XT, typename GT, int W, int UT>
+KernelFn tile_kernel_for_phase(int phase) {
+  switch (phase) {
+    case kMixOnly: return k_tile<XT, GT, kMixOnly, W, UT>;
+    case kUpdateOnly: return k_tile<XT, GT, kUpdateOnly, W, UT>;
+    case kPlain: return k_tile<XT, GT, kPlain, W, UT>;
+    case kLoopStart: return k_tile<XT, GT, kLoopStart, W, UT>;
+    case kFold: return k_tile<XT, GT, kFold, W, UT>;
+    case kAlg1: return k_tile<XT, GT, kAlg1, W, UT>;
+  }
+  return nullptr;
+}
+
+template <typename XT, typename GT>
+KernelFn tile_kernel_for_shape(int phase, TileShape s) {
+  if (s.waves == 4 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 4, 1>(phase);
+  if (s.waves == 4 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 4, 2>(phase);
+  if (s.waves == 8 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 8, 1>(phase);
+  if (s.waves == 8 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 8, 2>(phase);
+  return nullptr;
+}
+
+template <typename XT, typename GT>
+KernelFn direct_kernel_for_phase(int phase) {
+  switch (phase) {
+    case kMixOnly: return k_direct<XT, GT, kMixOnly>;
+    case kUpdateOnly: return k_direct<XT, GT, kUpdateOnly>;
+    case kPlain: return k_direct<XT, GT, kPlain>;
+    case kLoopStart: return k_direct<XT, GT, kLoopStart>;
+    case kFold: return k_direct<XT, GT, kFold>;
+    case kAlg1: return k_direct<XT, GT, kAlg1>;
+  }
+  return nullptr;
+}
+
+template <typename GT, int VEC>
+KernelFn acc_kernel_for_phase(int phase) {
+  switch (phase) {
+    case kPlain: return k_acc<GT, VEC, kPlain>;
+    case kLoopStart: return k_acc<GT, VEC, kLoopStart>;
+    case kFold: return k_acc<GT, VEC, kFold>;
+    case kAlg1: return k_acc<GT, VEC, kAlg1>;
+  }
+  return nullptr;
+}
+
+int launch(KernelFn fn, uint32_t grid, uint32_t block, uint32_t lds, const StepArgs& a, void* stream) {
+  if (fn == nullptr) return (int)hipErrorInvalidDeviceFunction;
+  if (grid == 0) return (int)hipSuccess;
+  hipLaunchKernelGGL(fn, dim3(grid), dim3(block), lds, reinterpret_cast<hipStream_t>(stream), a);
+  return (int)hipGetLastError();
+}
+
+static_assert(sizeof(StepArgs) <= 4096, "kernel argument block must fit the kernarg segment");
+
+}  // namespace
+
+int vec_elems(int xdt) { return xdt == DADAM_BF16 ? 8 : 4; }
+int direct_unroll() { return kUD; }
+bool tile_shape_supported(TileShape s) {
+  return (s.waves == 4 || s.waves == 8) && (s.ut == 1 || s.ut == 2);
+}
+
+int launch_tile(int xdt, int gdt, Phase phase, TileShape shape, const StepArgs& a, uint32_t n_work,
+                uint32_t lds_bytes, void* stream) {
+  KernelFn fn = nullptr;
+  if (xdt == DADAM_F32 && gdt == DADAM_F32) fn = tile_kernel_for_shape<TF32, TF32>(phase, shape);
+  if (xdt == DADAM_BF16 && gdt == DADAM_BF16) fn = tile_kernel_for_shape<TBF16, TBF16>(phase, shape);
+  if (xdt == DADAM_BF16 && gdt == DADAM_F32) fn = tile_kernel_for_shape<TBF16, TF32>(phase, shape);
+  if (xdt == DADAM_F32 && gdt == DADAM_BF16) fn = tile_kernel_for_shape<TF32, TBF16>(phase, shape);
+  return launch(fn, n_work, (uint32_t)(kWave * shape.waves), lds_bytes, a, stream);
+}
+
+int launch_direct(int xdt, int gdt, Phase phase, const StepArgs& a, uint32_t n_work_tiles, void* stream) {
+  KernelFn fn = nullptr;
+  if (xdt == DADAM_F32 && gdt == DADAM_F32) fn = direct_kernel_for_phase<TF32, TF32>(phase);
+  if (xdt == DADAM_BF16 && gdt == DADAM_BF16) fn = direct_kernel_for_phase<TBF16, TBF16>(phase);
+  if (xdt == DADAM_BF16 && gdt == DADAM_F32) fn = direct_kernel_for_phase<TBF16, TF32>(phase);
+  if (xdt == DADAM_F32 && gdt == DADAM_BF16) fn = direct_kernel_for_phase<TF32, TBF16>(phase);
+  return launch(fn, n_work_tiles * a.n_rows, kDirectThreads, 0, a, stream);
+}
+
+int launch_accumulate(int gdt, Phase phase, const StepArgs& a, uint32_t n_work_tiles, void* stream,
+                      int vec) {
+  KernelFn fn = nullptr;
+  if (gdt == DADAM_F32 && vec == 4) fn = acc_kernel_for_phase<TF32, 4>(phase);
+  if (gdt == DADAM_F32 && vec == 8) fn = acc_kernel_for_phase<TF32, 8>(phase);
+  if (gdt == DADAM_BF16 && vec == 4) fn = acc_kernel_for_phase<TBF16, 4>(phase);
+  if (gdt == DADAM_BF16 && vec == 8) fn = acc_kernel_for_phase<TBF16, 8>(phase);
+  return launch(fn, n_work_tiles * a.n_rows, kDirectThreads, 0, a, stream);
+}
+
+}  // namespace dadam

@@ -1,0 +1,267 @@
+"""Side-by-side driver for the parity tests: runs the HIP path through the C ABI binding and
+the CPU oracle on the same seeded inputs, on all coordinates or on a sampled subset (the
+iteration is separable per coordinate, so any subset is checked exactly).
+
+Not collected by pytest (no test_ prefix)."""
+
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from oracle import dadam_oracle as O
+from paper_2410_11998_amd import binding as B
+from paper_2410_11998_amd import workloads as WL
+
+TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
+ABI_DT = {"f32": B.DADAM_F32, "bf16": B.DADAM_BF16}
+
+# Tolerances of the parity bar.  float32: 1e-6 of the magnitude of the terms that make up a
+# value (a float32 evaluation of one iteration commits about a dozen roundings of 2^-24 = 6e-8
+# each, relative to those terms).  bfloat16 parameters: 1e-2, which is a little above one unit
+# in the last place of a bfloat16 number (2^-7), so a rounding decision that flips because the
+# float32 value before it differs in its last bits stays inside.
+RTOL = {"f32": 1e-6, "bf16": 1e-2}
+
+
+def f32(x: float) -> float:
+    return float(np.float32(x))
+
+
+@dataclass
+class HyperF32:
+    lr: float = 1e-3
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    s: int = 1
+    beta_vhat: float = -1.0
+
+    def oracle(self) -> O.Hyper:
+        """The same numbers as the float32 fields of the C configuration, widened exactly."""
+        return O.Hyper(f32(self.lr), f32(self.beta1), f32(self.beta2), f32(self.eps), self.s,
+                       None if self.beta_vhat < 0 else f32(self.beta_vhat))
+
+
+class GpuSim:
+    """Device buffers of one handle plus the calls of the binding."""
+
+    def __init__(self, n_rows: int, n_cols: int, layout: WL.PackedLayout, hp: HyperF32, csrs: Sequence,
+                 param_dtype: str = "f32", grad_dtype: str = "f32", inplace: bool = False,
+                 pad_fill: Optional[float] = None, device: str = "cuda:0"):
+        self.R, self.C, self.layout, self.hp = n_rows, n_cols, layout, hp
+        self.pd, self.gd = param_dtype, grad_dtype
+        self.dev = torch.device(device)
+        d = layout.d
+        self.d = d
+        z = lambda dt: torch.zeros(d, dtype=dt, device=self.dev)
+        self.x_src = [z(TORCH_DT[param_dtype]) for _ in range(n_cols)]
+        self.inplace = inplace
+        if inplace:
+            assert n_rows <= n_cols
+            self.x_dst = [self.x_src[i] for i in range(n_rows)]
+        else:
+            self.x_dst = [z(TORCH_DT[param_dtype]) for _ in range(n_rows)]
+        self.m = [z(torch.float32) for _ in range(n_rows)]
+        self.v = [z(torch.float32) for _ in range(n_rows)]
+        self.b = [z(torch.float32) for _ in range(n_rows)] if hp.s > 1 else None
+        if pad_fill is not None:
+            # sentinel in the padding between tensors only; it must still be there afterwards
+            inv = torch.from_numpy(~valid_mask(layout)).to(self.dev)
+            for t in ([] if inplace else self.x_dst) + self.m + self.v + (self.b or []):
+                t[inv] = pad_fill
+        self.h = B.dadam_init(n_rows, n_cols, d, layout.offsets, layout.numels, ABI_DT[param_dtype], ABI_DT[grad_dtype],
+                              hp.lr, hp.beta1, hp.beta2, hp.eps, hp.s, hp.beta_vhat, device=self.dev.index or 0)
+        self.csrs = list(csrs)
+        for k, (rp, col, w) in enumerate(self.csrs):
+            B.dadam_set_topology(self.h, k, rp, col, w)
+        self.bind()
+
+    def bind(self):
+        B.dadam_bind(self.h, self.x_src, self.x_dst, self.m, self.v, self.b)
+
+    def close(self):
+        torch.cuda.synchronize()
+        B.dadam_destroy(self.h)
+        self.h = None
+
+    def stream(self) -> int:
+        return B.current_stream()
+
+    def step(self, grads, t: int, slot: int = 0, flags: int = B.DADAM_FUSE_ACCUM):
+        B.dadam_gossip_step(self.h, slot, grads, t, flags, self.stream())
+
+    def step_range(self, grads, t: int, tb: int, te: int, slot: int = 0, flags: int = B.DADAM_FUSE_ACCUM):
+        B.dadam_gossip_step_range(self.h, slot, grads, t, flags, tb, te, self.stream())
+
+    def accumulate(self, grads, t: int):
+        B.dadam_accumulate(self.h, grads, t, self.stream())
+
+    def mix(self, slot: int = 0, flags: int = 0):
+        B.dadam_mix(self.h, slot, flags, self.stream())
+
+    def swap(self):
+        """Ping-pong: the outputs of this iteration are the sources of the next."""
+        if self.inplace:
+            return
+        assert self.R == self.C
+        self.x_src, self.x_dst = self.x_dst, self.x_src
+        B.dadam_swap_x(self.h)
+
+    # ---- host copies (float64) of selected coordinates -------------------------------------
+    def _get(self, tensors, idx):
+        out = []
+        for t in tensors:
+            g = t if idx is None else t[idx]
+            out.append(g.to(torch.float64).cpu().numpy())
+        return out
+
+    def snapshot(self, idx=None) -> O.State:
+        zeros = [np.zeros(self.d if idx is None else len(idx))] * self.R
+        return O.State(self._get(self.x_src, idx), self._get(self.m, idx), self._get(self.v, idx),
+                       self._get(self.b, idx) if self.b is not None else [z.copy() for z in zeros])
+
+    def outputs(self, idx=None):
+        return (self._get(self.x_dst, idx), self._get(self.m, idx), self._get(self.v, idx),
+                self._get(self.b, idx) if self.b is not None else None)
+
+
+def valid_mask(layout: WL.PackedLayout) -> np.ndarray:
+    m = np.zeros(layout.d, dtype=bool)
+    for o, n in zip(layout.offsets, layout.numels):
+        m[int(o):int(o) + int(n)] = True
+    return m
+
+
+def csr_oracle(t3) -> O.Csr:
+    rp, col, w = t3
+    return O.Csr(np.asarray(rp), np.asarray(col), np.asarray(w, dtype=np.float32).astype(np.float64))
+
+
+def state_scales(prev: O.State, grads64, t: int, hp: O.Hyper):
+    """Magnitudes of the terms of b, m_hat, v_hat after iteration t (for relative bounds)."""
+    sb, sm, sv = [], [], []
+    fold = (t % hp.s == 0)
+    for i in range(len(grads64)):
+        g = np.abs(grads64[i])
+        bmag = np.abs(prev.b[i]) + g / hp.s
+        sb.append(bmag)
+        if fold:
+            sm.append(hp.beta1 * np.abs(prev.m_hat[i]) + (1 - hp.beta1) * bmag)
+            sv.append(hp.bv() * np.abs(prev.v_hat[i]) + (1 - hp.bv()) * bmag * bmag)
+        else:
+            sm.append(np.abs(prev.m_hat[i]))
+            sv.append(np.abs(prev.v_hat[i]))
+    return sb, sm, sv
+
+
+def compare_step(prev: O.State, ref_x, ref_state: O.State, got, grads64, csr: O.Csr, t: int, hp: O.Hyper,
+                 param_dtype: str, mask: Optional[np.ndarray] = None, what: str = "") -> dict:
+    """Element-by-element comparison of one iteration's outputs.  ``prev`` is the state both
+    sides started the iteration from (teacher forcing) or the oracle's own previous state
+    (free running).  Returns the worst ratios error / bound (all must be <= 1)."""
+    gx, gm, gv, gb = got
+    xs = O.magnitude_scale(prev, grads64, csr, t, hp)
+    sb, sm, sv = state_scales(prev, grads64, t, hp)
+    rt = RTOL[param_dtype]
+    worst = {"x": 0.0, "m": 0.0, "v": 0.0, "b": 0.0}
+    for i in range(csr.n_rows):
+        sel = slice(None) if mask is None else mask
+        ex = np.abs(gx[i][sel] - ref_x[i][sel]) / (rt * xs[i][sel] + 1e-300)
+        assert np.all(np.isfinite(gx[i][sel])), f"{what}: non-finite x in row {i}"
+        worst["x"] = max(worst["x"], float(ex.max(initial=0.0)))
+        for key, g, r, sc in (("m", gm, ref_state.m_hat, sm), ("v", gv, ref_state.v_hat, sv)):
+            e = np.abs(g[i][sel] - r[i][sel]) / (1e-6 * sc[i][sel] + 1e-300)
+            worst[key] = max(worst[key], float(e.max(initial=0.0)))
+        if gb is not None:
+            e = np.abs(gb[i][sel] - ref_state.b[i][sel]) / (1e-6 * sb[i][sel] + 1e-300)
+            worst["b"] = max(worst["b"], float(e.max(initial=0.0)))
+    return worst
+
+
+def assert_within(worst: dict, what: str):
+    for k, v in worst.items():
+        assert v <= 1.0, f"{what}: {k} off by {v:.3f} x the tolerance"
+
+
+def to_device(arr: np.ndarray, dtype: str, dev) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(arr)).to(device=dev, dtype=TORCH_DT[dtype])
+
+
+def run_parity(wl_name: str, n_rows: int, n_cols: int, layout: WL.PackedLayout, hp: HyperF32, csrs, slot_of_t,
+               T: int, seed: int, param_dtype="f32", grad_dtype="f32", grad_std=1e-2, flags=B.DADAM_FUSE_ACCUM,
+               inplace=False, shared_init=False, refresh_extra_sources=False, unfused=False, free_running=True,
+               pad_fill: Optional[float] = 777.0):
+    """Whole-vector parity over T iterations.  Each iteration is checked teacher-forced (the
+    oracle restarts from the device's previous state) and, with free_running, a second oracle
+    that never sees device state is compared at the end."""
+    dev = torch.device("cuda:0")
+    sim = GpuSim(n_rows, n_cols, layout, hp, csrs, param_dtype, grad_dtype, inplace=inplace, pad_fill=pad_fill)
+    ohp = hp.oracle()
+    mask = valid_mask(layout)
+    d = layout.d
+    x0 = [WL.normal_np(seed * 100 + (0 if shared_init else c), d, 0.02) for c in range(n_cols)]
+    for c in range(n_cols):
+        sim.x_src[c].copy_(to_device(x0[c], param_dtype, dev))
+    free = sim.snapshot() if free_running else None
+    worst_all = {"x": 0.0, "m": 0.0, "v": 0.0, "b": 0.0}
+    pads = [t.clone() for t in sim.x_dst] if (pad_fill is not None and not inplace) else None
+    for t in range(1, T + 1):
+        slot = slot_of_t(t)
+        csr = csr_oracle(csrs[slot])
+        g_np = [WL.normal_np(seed * 100 + 10 + t * 64 + i, d, grad_std) for i in range(n_rows)]
+        grads = [to_device(g, grad_dtype, dev) for g in g_np]
+        g64 = [g.to(torch.float64).cpu().numpy() for g in grads]
+        if refresh_extra_sources and t > 1:
+            for c in range(n_rows, n_cols):
+                sim.x_src[c].copy_(to_device(WL.normal_np(seed * 100 + 5000 + t * 64 + c, d, 0.02), param_dtype, dev))
+            if free is not None:
+                for c in range(n_rows, n_cols):
+                    free.x_src[c] = sim.x_src[c].to(torch.float64).cpu().numpy()
+        prev = sim.snapshot()
+        if unfused:
+            sim.step(grads, t, slot, flags & ~B.DADAM_FUSE_ACCUM)
+            sim.accumulate(grads, t)
+        else:
+            sim.step(grads, t, slot, flags)
+        torch.cuda.synchronize()
+        got = sim.outputs()
+        ref_state = O.State(prev.x_src, list(prev.m_hat), list(prev.v_hat), list(prev.b))
+        ref_x = O.dadam_step(ref_state, g64, csr, t, ohp, "O32m", param_dtype)
+        w = compare_step(prev, ref_x, ref_state, got, g64, csr, t, ohp, param_dtype, mask, f"{wl_name} t={t}")
+        assert_within(w, f"{wl_name} teacher-forced t={t}")
+        for k in worst_all:
+            worst_all[k] = max(worst_all[k], w[k])
+        if free is not None:
+            fprev = O.State(list(free.x_src), list(free.m_hat), list(free.v_hat), list(free.b))
+            fx = O.dadam_step(free, g64, csr, t, ohp, "O32m", param_dtype)
+            wf = compare_step(fprev, fx, free, got, g64, csr, t, ohp, param_dtype, mask, f"{wl_name} free t={t}")
+            # free running: rounding differences of earlier iterations ride along, at most one
+            # tolerance per elapsed iteration
+            for k, v in wf.items():
+                assert v <= float(t), f"{wl_name} free-running t={t}: {k} off by {v:.3f} x the tolerance"
+            for i in range(n_rows):
+                free.x_src[i] = fx[i]
+        if not inplace:
+            # padding between tensors is never written
+            if pads is not None:
+                inv = torch.from_numpy(~mask).to(dev)
+                for i in range(n_rows):
+                    assert torch.equal(sim.x_dst[i][inv], pads[i][inv]), f"{wl_name}: padding of x_dst[{i}] was written"
+            if n_rows == n_cols:
+                sim.swap()
+                pads = [t_.clone() for t_ in sim.x_dst] if pads is not None else None
+            else:
+                for i in range(n_rows):
+                    sim.x_src[i].copy_(sim.x_dst[i])
+    if pad_fill is not None:
+        inv = torch.from_numpy(~mask).to(dev)
+        for i in range(n_rows):
+            for name, arr in (("m_hat", sim.m), ("v_hat", sim.v)) + ((("b", sim.b),) if sim.b is not None else ()):
+                vals = arr[i][inv]
+                assert bool(torch.all(vals == pad_fill)), f"{wl_name}: padding of {name}[{i}] was written"
+    sim.close()
+    return worst_all

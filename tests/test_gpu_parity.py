@@ -1,0 +1,385 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle element by
+element on the same seeded inputs.  Bit-exact where the work is selection and copying;
+within 1e-6 (float32) / 1e-2 (bfloat16 parameters) of the terms' magnitude on values."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dadam_oracle as O
+from paper_2410_11998_amd import binding as B
+from paper_2410_11998_amd import workloads as WL
+
+import harness as H
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+MODES = {"tile": B.DADAM_FORCE_TILE, "direct": B.DADAM_FORCE_DIRECT, "auto": 0}
+
+
+def flat_layout(d):
+    return WL.pack([("flat", (d,))])
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ---------------------------------------------------------------------------------------------
+# neighbour selection: permutation matrices copy bit-exactly
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode", ["tile", "direct"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layout_name", ["flat", "odd"])
+def test_permutation_mixing_is_a_bit_exact_copy(mode, dtype, layout_name):
+    say("case", mode, dtype, layout_name)
+    n = 7
+    layout = flat_layout(5000) if layout_name == "flat" else WL.pack(WL.odd_shapes())
+    perm = [3, 0, 6, 1, 5, 2, 4]
+    sim = H.GpuSim(n, n, layout, H.HyperF32(s=2), [WL.permutation(perm)], dtype, dtype, pad_fill=None)
+    d = layout.d
+    # every element carries a code of (source, position) that is exact in the storage type
+    for c in range(n):
+        if dtype == "f32":
+            code = torch.arange(d, dtype=torch.float32) + float(c) * 16384.0
+            code[::7] = -0.0
+        else:
+            code = ((torch.arange(d) % 128).to(torch.float32) + 128.0) * float(2 ** c)   # 8 significant bits
+        sim.x_src[c].copy_(code.to(H.TORCH_DT[dtype]))
+    for i in range(n):
+        sim.x_dst[i].fill_(-1.0)
+    sim.mix(0, MODES[mode])
+    torch.cuda.synchronize()
+    mask = torch.from_numpy(H.valid_mask(layout)).to(DEV)
+    view = torch.int32 if dtype == "f32" else torch.int16
+    for i in range(n):
+        got = sim.x_dst[i].view(view)[mask]
+        want = sim.x_src[perm[i]].view(view)[mask]
+        assert torch.equal(got, want), f"row {i} is not a bit copy of source {perm[i]}"
+        if layout_name == "odd":
+            assert bool(torch.all(sim.x_dst[i][~mask] == -1.0)), "padding was written"
+    sim.close()
+
+
+@pytest.mark.parametrize("mode", ["tile", "direct"])
+def test_step_with_permutation_and_zero_direction_copies_bit_exact(mode):
+    """The fused kernels select neighbours the same way: zero gradient and zero moments give a
+    zero direction, so x_dst must again be a bit copy."""
+    say("case", mode)
+    n, d = 5, 3001
+    perm = [4, 2, 0, 1, 3]
+    sim = H.GpuSim(n, n, flat_layout(d), H.HyperF32(s=2), [WL.permutation(perm)], pad_fill=None)
+    for c in range(n):
+        sim.x_src[c].copy_(torch.arange(d, dtype=torch.float32) * 0.25 + 1000.0 * c)
+    zeros = [torch.zeros(d, device=DEV) for _ in range(n)]
+    sim.step(zeros, 1, 0, B.DADAM_FUSE_ACCUM | MODES[mode])
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert torch.equal(sim.x_dst[i].view(torch.int32), sim.x_src[perm[i]].view(torch.int32))
+        assert bool(torch.all(sim.b[i] == 0)) and bool(torch.all(sim.m[i] == 0))
+    sim.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mix_matches_oracle_rectangular_random_rows(dtype):
+    say("case", dtype)
+    rng = np.random.default_rng(5)
+    R, C, d = 3, 9, 4099
+    row_ptr, col, w = [0], [], []
+    for i in range(R):
+        deg = [1, 9, 4][i]
+        cols = rng.permutation(C)[:deg]
+        ww = rng.random(deg).astype(np.float32) + np.float32(0.1)
+        ww = (ww / ww.sum(dtype=np.float32)).astype(np.float32)
+        col += list(cols); w += list(ww); row_ptr.append(len(col))
+    t3 = (np.array(row_ptr, np.int32), np.array(col, np.int32), np.array(w, np.float32))
+    sim = H.GpuSim(R, C, flat_layout(d), H.HyperF32(s=1), [t3], dtype, dtype)
+    for c in range(C):
+        sim.x_src[c].copy_(H.to_device(WL.normal_np(100 + c, d, 1.0), dtype, DEV))
+    sim.mix()
+    torch.cuda.synchronize()
+    xs = sim._get(sim.x_src, None)
+    csr = H.csr_oracle(t3)
+    ref = O.mix_only(xs, csr, "O32m", dtype)
+    got = sim._get(sim.x_dst, None)
+    for i in range(R):
+        scale = sum(abs(csr.w[k]) * np.abs(xs[csr.col[k]]) for k in range(csr.row_ptr[i], csr.row_ptr[i + 1]))
+        assert np.all(np.abs(got[i] - ref[i]) <= H.RTOL[dtype] * scale)
+    sim.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# configuration 1 whole, and small copies of configurations 2-5 whole
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode", ["tile", "direct"])
+def test_config1_every_element_every_step(mode):
+    say("case", mode)
+    wl = WL.workload(1)
+    hp = H.HyperF32(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.s)
+    worst = H.run_parity(wl.name, wl.n_rows, wl.n_cols, wl.layout(), hp, [wl.csr()], lambda t: 0, wl.steps,
+                         seed=wl.cfg, grad_std=wl.grad_std, flags=B.DADAM_FUSE_ACCUM | MODES[mode])
+    say("worst error / tolerance:", worst)
+
+
+@pytest.mark.parametrize("cfg,div,mode", [(2, 16, "auto"), (2, 16, "direct"), (3, 16, "auto"), (3, 16, "tile"),
+                                         (4, 4, "auto"), (4, 4, "direct"), (5, 16, "auto"), (5, 16, "direct")])
+def test_scaled_configs_every_element(cfg, div, mode):
+    say("case", cfg, div, mode)
+    wl = WL.workload(cfg, scale_div=div)
+    hp = H.HyperF32(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.s)
+    csrs = [wl.csr(k) for k in range(wl.n_slots())]
+    T = min(wl.steps, 2 * wl.s + 1)
+    worst = H.run_parity(wl.name, wl.n_rows, wl.n_cols, wl.layout(), hp, csrs, lambda t: wl.slot_of_step(t), T,
+                         seed=10 + cfg, param_dtype=wl.param_dtype, grad_dtype=wl.grad_dtype, grad_std=wl.grad_std,
+                         flags=B.DADAM_FUSE_ACCUM | MODES[mode], refresh_extra_sources=(cfg == 3),
+                         inplace=(cfg == 3), pad_fill=None)
+    say("worst error / tolerance:", worst)
+
+
+# ---------------------------------------------------------------------------------------------
+# ragged layouts, every phase, both modes, all dtype pairs
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode", ["tile", "direct"])
+@pytest.mark.parametrize("pd,gd", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32"), ("f32", "bf16")])
+@pytest.mark.parametrize("s", [1, 3])
+def test_odd_layout_all_phases(mode, pd, gd, s):
+    say("case", mode, pd, gd, s)
+    n = 3
+    layout = WL.pack(WL.odd_shapes())
+    hp = H.HyperF32(lr=2e-3, s=s)
+    worst = H.run_parity("odd", n, n, layout, hp, [WL.ring(n)], lambda t: 0, 2 * s + 1, seed=77, param_dtype=pd,
+                         grad_dtype=gd, grad_std=1e-2, flags=B.DADAM_FUSE_ACCUM | MODES[mode])
+    say("worst error / tolerance:", worst)
+
+
+@pytest.mark.parametrize("mode", ["tile", "direct"])
+def test_unfused_sequence_matches_oracle_and_fused_bitwise(mode):
+    say("case", mode)
+    n, s, T = 4, 2, 5
+    layout = WL.pack(WL.odd_shapes())
+    hp = H.HyperF32(s=s)
+    H.run_parity("unfused", n, n, layout, hp, [WL.ring(n)], lambda t: 0, T, seed=78, unfused=True,
+                 flags=B.DADAM_FUSE_ACCUM | MODES[mode])
+    # and the two call sequences give identical bits
+    sims = [H.GpuSim(n, n, layout, hp, [WL.ring(n)], pad_fill=None) for _ in range(2)]
+    for sim in sims:
+        for c in range(n):
+            sim.x_src[c].copy_(H.to_device(WL.normal_np(900 + c, layout.d, 0.02), "f32", DEV))
+    for t in range(1, T + 1):
+        grads = [H.to_device(WL.normal_np(1000 + t * 8 + i, layout.d, 1e-2), "f32", DEV) for i in range(n)]
+        sims[0].step(grads, t, 0, B.DADAM_FUSE_ACCUM | MODES[mode])
+        sims[1].step(grads, t, 0, MODES[mode])
+        sims[1].accumulate(grads, t)
+        torch.cuda.synchronize()
+        for a, b in zip(sims[0].x_dst + sims[0].m + sims[0].v + sims[0].b, sims[1].x_dst + sims[1].m + sims[1].v + sims[1].b):
+            assert torch.equal(a, b)
+        for sim in sims:
+            sim.swap()
+    for sim in sims:
+        sim.close()
+
+
+def test_in_place_tile_mode_equals_ping_pong_bitwise():
+    n, T = 8, 4
+    wl = WL.workload(2, scale_div=32)
+    layout = wl.layout()
+    hp = H.HyperF32(s=2)
+    csr = WL.static_exponential(n)
+    a = H.GpuSim(n, n, layout, hp, [csr], inplace=False)
+    b = H.GpuSim(n, n, layout, hp, [csr], inplace=True)
+    assert B.dadam_slot_uses_tile_mode(b.h, 0)
+    for c in range(n):
+        x0 = H.to_device(WL.normal_np(300 + c, layout.d, 0.02), "f32", DEV)
+        a.x_src[c].copy_(x0); b.x_src[c].copy_(x0)
+    for t in range(1, T + 1):
+        grads = [H.to_device(WL.normal_np(400 + t * 8 + i, layout.d, 1e-3), "f32", DEV) for i in range(n)]
+        a.step(grads, t); b.step(grads, t)
+        torch.cuda.synchronize()
+        for i in range(n):
+            assert torch.equal(a.x_dst[i], b.x_dst[i])
+        a.swap()
+    with pytest.raises(B.DadamError) as e:
+        b.step(grads, T + 1, 0, B.DADAM_FUSE_ACCUM | B.DADAM_FORCE_DIRECT)
+    assert e.value.code == B.DADAM_EALIAS
+    a.close(); b.close()
+
+
+def test_bucket_ranges_compose_to_the_whole_step():
+    """Stepping tensor ranges one after the other (buckets) gives the bits of one whole step."""
+    n = 4
+    layout = WL.pack(WL.odd_shapes() + [("big", (70001,))])
+    hp = H.HyperF32(s=2)
+    nt = len(layout.names)
+    for mode in ("tile", "direct"):
+        say("case", mode)
+        a = H.GpuSim(n, n, layout, hp, [WL.ring(n)])
+        b = H.GpuSim(n, n, layout, hp, [WL.ring(n)])
+        for c in range(n):
+            x0 = H.to_device(WL.normal_np(500 + c, layout.d, 0.02), "f32", DEV)
+            a.x_src[c].copy_(x0); b.x_src[c].copy_(x0)
+        for t in (1, 2, 3):
+            grads = [H.to_device(WL.normal_np(600 + t * 8 + i, layout.d, 1e-2), "f32", DEV) for i in range(n)]
+            a.step(grads, t, 0, B.DADAM_FUSE_ACCUM | MODES[mode])
+            for tb, te in ((nt - 1, nt), (5, nt - 1), (0, 2), (2, 5), (3, 3)):
+                b.step_range(grads, t, tb, te, 0, B.DADAM_FUSE_ACCUM | MODES[mode])
+            torch.cuda.synchronize()
+            for u, v in zip(a.x_dst + a.m + a.v + a.b, b.x_dst + b.m + b.v + b.b):
+                assert torch.equal(u, v)
+            a.swap(); b.swap()
+        a.close(); b.close()
+
+
+def test_resume_from_saved_buffers_is_bit_identical():
+    n, T, T1 = 4, 7, 3
+    layout = flat_layout(10007)
+    hp = H.HyperF32(s=4)
+    def fresh():
+        s = H.GpuSim(n, n, layout, hp, [WL.ring(n)], pad_fill=None)
+        return s
+    grads_of = lambda t: [H.to_device(WL.normal_np(700 + t * 8 + i, layout.d, 1e-2), "f32", DEV) for i in range(n)]
+    a = fresh()
+    for c in range(n):
+        a.x_src[c].copy_(H.to_device(WL.normal_np(650 + c, layout.d, 0.02), "f32", DEV))
+    x0 = [x.clone() for x in a.x_src]
+    for t in range(1, T + 1):
+        a.step(grads_of(t), t); a.swap()
+    b = fresh()
+    for c in range(n):
+        b.x_src[c].copy_(x0[c])
+    for t in range(1, T1 + 1):
+        b.step(grads_of(t), t); b.swap()
+    torch.cuda.synchronize()
+    saved = [[x.clone() for x in grp] for grp in (b.x_src, b.m, b.v, b.b)]
+    b.close()
+    c_ = fresh()
+    for grp, src in zip((c_.x_src, c_.m, c_.v, c_.b), saved):
+        for dst, s_ in zip(grp, src):
+            dst.copy_(s_)
+    for t in range(T1 + 1, T + 1):
+        c_.step(grads_of(t), t); c_.swap()
+    torch.cuda.synchronize()
+    for u, v in zip(a.x_src + a.m + a.v + a.b, c_.x_src + c_.m + c_.v + c_.b):
+        assert torch.equal(u, v)
+    a.close(); c_.close()
+
+
+def test_zero_gradient_zero_state_is_pure_mixing_without_nan():
+    n, d = 4, 2049
+    sim = H.GpuSim(n, n, flat_layout(d), H.HyperF32(s=2), [WL.ring(n)], pad_fill=None)
+    for c in range(n):
+        sim.x_src[c].copy_(H.to_device(WL.normal_np(800 + c, d, 0.02), "f32", DEV))
+    zeros = [torch.zeros(d, device=DEV) for _ in range(n)]
+    sim.step(zeros, 1)
+    torch.cuda.synchronize()
+    stepped = [x.clone() for x in sim.x_dst]
+    sim.mix()
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert bool(torch.all(torch.isfinite(stepped[i]))) and torch.equal(stepped[i], sim.x_dst[i])
+    sim.close()
+
+
+def test_max_rows_complete_graph_and_lr_change():
+    """64 rows x 64 sources, every row of full degree: the largest neighbour list the
+    library takes; then a change of step size through dadam_set_lr."""
+    n, d = 64, 1500
+    hp = H.HyperF32(s=1)
+    layout = flat_layout(d)
+    for mode in ("tile", "direct"):
+        say("case", mode)
+        H.run_parity("complete64", n, n, layout, hp, [WL.complete(n)], lambda t: 0, 2, seed=91,
+                     flags=B.DADAM_FUSE_ACCUM | MODES[mode], pad_fill=None)
+    sim = H.GpuSim(2, 2, layout, hp, [WL.identity(2)], pad_fill=None)
+    g = [torch.full((d,), 0.5, device=DEV) for _ in range(2)]
+    sim.step(g, 1)
+    B.dadam_set_lr(sim.h, 0.25)
+    sim.swap()
+    sim.step(g, 2)
+    torch.cuda.synchronize()
+    # constant gradient: every iteration moves by lr * c / (|c| + eps)
+    want = -(np.float32(1e-3) + np.float32(0.25)) * 0.5 / (0.5 + 1e-8)
+    np.testing.assert_allclose(sim.x_dst[0].cpu().numpy(), want, rtol=1e-6)
+    sim.close()
+
+
+def test_literal_beta1_fold_selectable():
+    n, d, s = 2, 1000, 2
+    hp = H.HyperF32(s=s, beta_vhat=0.9)
+    H.run_parity("literal", n, n, flat_layout(d), hp, [WL.ring(n)], lambda t: 0, 4, seed=92, pad_fill=None)
+
+
+# ---------------------------------------------------------------------------------------------
+# full-size configurations in the benchmark's launch configuration, sampled coordinates
+# ---------------------------------------------------------------------------------------------
+
+def sample_coordinates(layout, rng, n_random):
+    d = layout.d
+    pick = [np.arange(0, min(4096, d)), np.arange(max(0, d - 4096), d)]
+    for o, n in zip(layout.offsets, layout.numels):
+        for edge in (int(o), int(o) + int(n)):
+            pick.append(np.arange(max(0, edge - 64), min(d, edge + 64)))
+    pick.append(rng.integers(0, d, size=n_random))
+    return np.unique(np.concatenate(pick))
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_configs_sampled(cfg):
+    say("case", cfg)
+    wl = WL.workload(cfg)
+    layout = wl.layout()
+    hp = H.HyperF32(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.s)
+    ohp = hp.oracle()
+    csrs = [wl.csr(k) for k in range(wl.n_slots())]
+    dev = torch.device(DEV)
+    sim = H.GpuSim(wl.n_rows, wl.n_cols, layout, hp, csrs, wl.param_dtype, wl.grad_dtype, inplace=(cfg == 3), pad_fill=None)
+    rng = np.random.default_rng(cfg)
+    idx_np = sample_coordinates(layout, rng, 1 << (16 if wl.n_rows >= 16 else 18))
+    idx = torch.from_numpy(idx_np).to(dev)
+    x0 = WL.normal_torch(WL.seed_for(cfg, 0), (layout.d,), wl.param_std, dev, H.TORCH_DT[wl.param_dtype])
+    for c in range(wl.n_rows):
+        sim.x_src[c].copy_(x0)
+        # replicas start equal (Algorithm 1 line 1); perturb so that mixing is visible at once
+        sim.x_src[c].add_(WL.normal_torch(WL.seed_for(cfg, 500 + c), (layout.d,), 1e-3, dev, H.TORCH_DT[wl.param_dtype]))
+    del x0
+    T = wl.s + 1
+    grads = [torch.empty(layout.d, dtype=H.TORCH_DT[wl.grad_dtype], device=dev) for _ in range(wl.n_rows)]
+    gen = torch.Generator(device=dev)
+    for t in range(1, T + 1):
+        for c in range(wl.n_rows, wl.n_cols):
+            sim.x_src[c].copy_(WL.normal_torch(WL.seed_for(cfg, 1) + 7 * t + c, (layout.d,), wl.param_std, dev, H.TORCH_DT[wl.param_dtype]))
+        gen.manual_seed(WL.seed_for(cfg, 2 + t))
+        for g in grads:
+            if wl.grad_dtype == "f32":
+                g.normal_(0.0, wl.grad_std, generator=gen)
+            else:
+                g.copy_(torch.empty(layout.d, dtype=torch.float32, device=dev).normal_(0.0, wl.grad_std, generator=gen))
+        slot = wl.slot_of_step(t)
+        prev = sim.snapshot(idx)
+        g64 = [g[idx].to(torch.float64).cpu().numpy() for g in grads]
+        sim.step(grads, t, slot)
+        torch.cuda.synchronize()
+        got = sim.outputs(idx)
+        ref_state = O.State(prev.x_src, list(prev.m_hat), list(prev.v_hat), list(prev.b))
+        csr = H.csr_oracle(csrs[slot])
+        ref_x = O.dadam_step(ref_state, g64, csr, t, ohp, "O32m", wl.param_dtype)
+        w = H.compare_step(prev, ref_x, ref_state, got, g64, csr, t, ohp, wl.param_dtype, None, f"{wl.name} t={t}")
+        say(f"t={t} worst error / tolerance: {w}")
+        H.assert_within(w, f"{wl.name} full size t={t}")
+        sim.swap()
+    # a property that holds at any size: with a doubly stochastic W the replica mean moves only
+    # by the mean direction, so mixing alone leaves it where it was (checked on a slice)
+    if wl.n_rows == wl.n_cols:
+        sl = slice(0, 1 << 20)
+        before = torch.stack([x[sl].to(torch.float64) for x in sim.x_src]).mean(0)
+        sim.mix(0)
+        torch.cuda.synchronize()
+        after = torch.stack([x[sl].to(torch.float64) for x in sim.x_dst]).mean(0)
+        tol = 1e-6 if wl.param_dtype == "f32" else 1e-2
+        assert float((after - before).abs().max()) <= tol * float(before.abs().max())
+    sim.close()
+    del sim, grads
+    torch.cuda.empty_cache()

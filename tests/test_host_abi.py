@@ -1,0 +1,191 @@
+"""Host-side tests of the C ABI that need no GPU: the library loads and exports every symbol the
+header declares; argument validation, neighbour-list validation, aliasing rules and the planner
+are exercised through a host-only handle (device = DADAM_DEVICE_NONE).  No kernel is launched."""
+
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2410_11998_amd import binding as B
+from paper_2410_11998_amd import workloads as WL
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    txt = open(os.path.join(ROOT, "include", "dadam.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(dadam_[a-z_0-9]+)\s*\(", txt)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(B.lib, n), f"{n} declared in include/dadam.h but not exported"
+    assert sorted(B.EXPORTS) == names
+
+
+def test_constants_match_header():
+    txt = open(os.path.join(ROOT, "include", "dadam.h")).read()
+    def macro(name):
+        m = re.search(r"#define\s+" + name + r"\s+\(?(-?\d+)u?\)?", txt)
+        assert m, name
+        return int(m.group(1))
+    for name in ("DADAM_ABI_VERSION", "DADAM_MAX_ROWS", "DADAM_MAX_SLOTS", "DADAM_DEVICE_NONE", "DADAM_F32", "DADAM_BF16",
+                 "DADAM_EINVAL", "DADAM_EALIGN", "DADAM_ETOPO", "DADAM_EALIAS", "DADAM_ESTATE", "DADAM_EHIP",
+                 "DADAM_FUSE_ACCUM", "DADAM_FORCE_DIRECT", "DADAM_FORCE_TILE"):
+        assert getattr(B, name) == macro(name), name
+
+
+def host_handle(n_rows=4, n_cols=4, shapes=None, **kw):
+    L = WL.pack(shapes or [("flat", (10000,))])
+    return B.dadam_init(n_rows, n_cols, L.d, L.offsets, L.numels, device=B.DADAM_DEVICE_NONE, **kw), L
+
+
+def expect(code, fn, *a, **kw):
+    with pytest.raises(B.DadamError) as e:
+        fn(*a, **kw)
+    assert e.value.code == code, str(e.value)
+    return str(e.value)
+
+
+def test_init_rejects_bad_configurations():
+    L = WL.pack([("a", (100,)), ("b", (50,))])
+    ok = dict(n_rows=2, n_cols=2, d=L.d, offsets=L.offsets, numels=L.numels, device=B.DADAM_DEVICE_NONE)
+    B.dadam_destroy(B.dadam_init(**ok))
+    for bad in (dict(n_rows=0), dict(n_rows=65), dict(n_cols=0), dict(n_cols=65), dict(d=0), dict(accum_s=0),
+                dict(param_dtype=2), dict(grad_dtype=7), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=-1.0),
+                dict(lr=float("inf")), dict(abi_version=99), dict(beta_vhat=1.5), dict(device=-3),
+                dict(offsets=[0, 50]), dict(offsets=[104, 0]), dict(d=120), dict(offsets=[], numels=[]),
+                dict(weight_decay=[0.0, 0.1]), dict(tensor_flags=[1, 0])):
+        expect(B.DADAM_EINVAL, B.dadam_init, **{**ok, **bad})
+    assert "tensor" in B.dadam_last_error(None)
+
+
+def test_planner_segments_and_tiles():
+    # contiguous tensors merge into one segment, a gap starts a new one, empty tensors are skipped
+    h = B.dadam_init(2, 2, 5000, [0, 100, 300, 300, 1000], [100, 200, 0, 10, 4000], device=B.DADAM_DEVICE_NONE)
+    info = B.dadam_get_plan_info(h)
+    assert info.n_segments == 2       # [0,310) [1000,5000)
+    assert info.tile_elems == 64 * 4 * 2 and info.lds_bytes_tile == 2 * 2 * 64 * 16
+    assert info.direct_elems == 256 * 4 * 2
+    T = info.tile_elems
+    want = sum((hi - 1) // T - lo // T + 1 for lo, hi in ((0, 310), (1000, 5000)))
+    assert info.n_tiles_tile == want
+    D = info.direct_elems
+    assert info.n_tiles_direct == sum((hi - 1) // D - lo // D + 1 for lo, hi in ((0, 310), (1000, 5000)))
+    B.dadam_destroy(h)
+    for cfg, segs in ((2, 1), (3, 1), (4, 1), (5, 1)):
+        wl = WL.workload(cfg)
+        L = wl.layout()
+        h = B.dadam_init(wl.n_rows, wl.n_cols, L.d, L.offsets, L.numels, B.DADAM_BF16 if wl.param_dtype == "bf16" else 0,
+                         B.DADAM_BF16 if wl.grad_dtype == "bf16" else 0, accum_s=wl.s, device=B.DADAM_DEVICE_NONE)
+        info = B.dadam_get_plan_info(h)
+        assert info.n_segments == segs and info.tile_mode_possible == 1
+        assert info.n_tiles_tile == -(-L.d // info.tile_elems)
+        assert info.lds_bytes_tile <= 65536
+        B.dadam_destroy(h)
+
+
+def test_pack_offsets_matches_workload_packer():
+    L = WL.pack(WL.odd_shapes(), align_elems=8)
+    off, d = B.dadam_pack_offsets([int(n) for n in L.numels], 8)
+    assert np.array_equal(off, L.offsets) and d == L.d
+    off, d = B.dadam_pack_offsets([5, 1, 8], 4)
+    assert list(off) == [0, 8, 12] and d == 20
+
+
+def test_set_topology_validation():
+    h, _ = host_handle(4, 4)
+    rp, col, w = WL.ring(4)
+    assert B.dadam_set_topology(h, 0, rp, col, w) == 0
+    assert B.dadam_slot_uses_tile_mode(h, 0) is True          # ring: sources are shared
+    assert B.dadam_set_topology(h, 1, *WL.identity(4)) == 0
+    assert B.dadam_slot_uses_tile_mode(h, 1) is False         # nothing shared: stream directly
+    expect(B.DADAM_EINVAL, B.dadam_set_topology, h, 16, rp, col, w)
+    expect(B.DADAM_ESTATE, B.dadam_slot_uses_tile_mode, h, 5)
+    bad = rp.copy(); bad[0] = 1
+    expect(B.DADAM_ETOPO, B.dadam_set_topology, h, 2, bad, col, w)
+    bad = rp.copy(); bad[2] = bad[1]
+    expect(B.DADAM_ETOPO, B.dadam_set_topology, h, 2, bad, col, w)           # empty row
+    bad = col.copy(); bad[1] = 4
+    expect(B.DADAM_ETOPO, B.dadam_set_topology, h, 2, rp, bad, w)            # column out of range
+    bad = col.copy(); bad[1] = -1
+    expect(B.DADAM_ETOPO, B.dadam_set_topology, h, 2, rp, bad, w)
+    bad = col.copy(); bad[1] = bad[0]
+    expect(B.DADAM_ETOPO, B.dadam_set_topology, h, 2, rp, bad, w)            # duplicate in a row
+    for val in (0.0, -0.5, float("nan"), float("inf")):
+        bad = w.copy(); bad[3] = val
+        expect(B.DADAM_ETOPO, B.dadam_set_topology, h, 2, rp, col, bad)
+    bad = w.copy(); bad[:3] = 0.3
+    assert "sums" in expect(B.DADAM_ETOPO, B.dadam_set_topology, h, 2, rp, col, bad)
+    # rows fine, columns not: a warning, not an error
+    rp2 = np.array([0, 1, 2, 3, 4], np.int32)
+    assert B.dadam_set_topology(h, 2, rp2, np.array([0, 0, 1, 2], np.int32), np.ones(4, np.float32)) == B.DADAM_WARN_NOT_COLUMN_STOCHASTIC
+    assert B.dadam_set_topology(h, 3, *WL.one_peer_exponential(4, 1)) == 0
+    B.dadam_destroy(h)
+
+
+def test_bind_alignment_and_aliasing_rules():
+    h, L = host_handle(2, 3, accum_s=2)
+    nb = L.d * 4
+    base = 1 << 20
+    P = lambda k: base + k * (nb + 256)       # disjoint, 16-byte aligned fake device addresses
+    good = dict(x_src=[P(0), P(1), P(2)], x_dst=[P(3), P(4)], m_hat=[P(5), P(6)], v_hat=[P(7), P(8)], acc=[P(9), P(10)])
+    B.dadam_bind(h, **good)
+    expect(B.DADAM_EALIGN, B.dadam_bind, h, **{**good, "x_dst": [P(3) + 4, P(4)]})
+    expect(B.DADAM_EALIGN, B.dadam_bind, h, **{**good, "acc": [P(9), P(10) + 8]})
+    expect(B.DADAM_EINVAL, B.dadam_bind, h, **{**good, "m_hat": [0, P(6)]})
+    expect(B.DADAM_EINVAL, B.dadam_bind, h, **{**good, "acc": None})
+    # partial overlap of an output with a source
+    expect(B.DADAM_EALIAS, B.dadam_bind, h, **{**good, "x_dst": [P(0) + 16, P(4)]})
+    # two outputs on the same memory
+    expect(B.DADAM_EALIAS, B.dadam_bind, h, **{**good, "x_dst": [P(3), P(3)]})
+    # state on top of parameters
+    expect(B.DADAM_EALIAS, B.dadam_bind, h, **{**good, "v_hat": [P(7), P(1)]})
+    expect(B.DADAM_EALIAS, B.dadam_bind, h, **{**good, "acc": [P(9), P(5)]})
+    # exact in-place is accepted; whether a step may run depends on the neighbour list
+    B.dadam_bind(h, **{**good, "x_dst": [P(0), P(1)]})
+    rp = np.array([0, 2, 4], np.int32)
+    w = np.full(4, 0.5, np.float32)
+    B.dadam_set_topology(h, 0, rp, np.array([0, 2, 1, 2], np.int32), w)   # sources 0 and 1 each read by their own row only
+    assert B.dadam_slot_uses_tile_mode(h, 0) is True                       # source 2 is shared -> tile mode
+    B.dadam_set_topology(h, 1, np.array([0, 1, 2], np.int32), np.array([0, 1], np.int32), np.ones(2, np.float32))
+    assert B.dadam_slot_uses_tile_mode(h, 1) is False                      # in place, nothing shared: direct is legal
+    B.dadam_set_topology(h, 2, np.array([0, 1, 2], np.int32), np.array([1, 0], np.int32), np.ones(2, np.float32))
+    assert B.dadam_slot_uses_tile_mode(h, 2) is True                       # rows read each other's buffer: needs the tile
+    # launching on a host-only handle is a state error, whatever the arguments
+    expect(B.DADAM_ESTATE, B.dadam_gossip_step, h, 0, [P(11), P(12)], 1)
+    expect(B.DADAM_ESTATE, B.dadam_accumulate, h, [P(11), P(12)], 1)
+    expect(B.DADAM_ESTATE, B.dadam_mix, h, 0)
+    B.dadam_destroy(h)
+
+
+def test_swap_needs_square_and_bound():
+    h, L = host_handle(2, 3)
+    expect(B.DADAM_ESTATE, B.dadam_swap_x, h)
+    B.dadam_destroy(h)
+    h, L = host_handle(2, 2)
+    expect(B.DADAM_ESTATE, B.dadam_swap_x, h)     # nothing bound yet
+    nb = L.d * 4 + 256
+    B.dadam_bind(h, [4096, 4096 + nb], [4096 + 2 * nb, 4096 + 3 * nb], [4096 + 4 * nb, 4096 + 5 * nb],
+                 [4096 + 6 * nb, 4096 + 7 * nb], None)
+    B.dadam_swap_x(h)
+    B.dadam_set_lr(h, 0.5)
+    expect(B.DADAM_EINVAL, B.dadam_set_lr, h, float("nan"))
+    B.dadam_destroy(h)
+
+
+def test_null_handle_is_an_error_not_a_crash():
+    null = C.c_void_p(None)
+    assert B.lib.dadam_swap_x(null) == B.DADAM_EINVAL
+    assert B.lib.dadam_set_lr(null, 0.1) == B.DADAM_EINVAL
+    assert B.lib.dadam_mix(null, 0, 0, None) == B.DADAM_EINVAL
+    assert B.lib.dadam_accumulate(null, None, 1, None) == B.DADAM_EINVAL
+    assert B.lib.dadam_gossip_step(null, 0, None, 1, 1, None) == B.DADAM_EINVAL
+    assert B.lib.dadam_init(None, None) == B.DADAM_EINVAL
+    B.lib.dadam_destroy(null)
