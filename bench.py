@@ -83,7 +83,10 @@ def main() -> int:
     ap.add_argument("--pool", type=int, default=2, help="number of pre-generated gradient sets cycled through")
     ap.add_argument("--scale-div", type=int, default=1, help="divide tensor dimensions (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 20)
+    ap.add_argument("--cpu-sample", type=int, default=None, help="coordinates per row given to the CPU oracle")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device copies of a known size (1 GiB read + 1 GiB written each), so that "
+                         "profiler byte counters can be scaled by what they read for a known transfer")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -141,7 +144,8 @@ def main() -> int:
     tile_mode = (args.mode == "tile") or (args.mode == "auto" and B.dadam_slot_uses_tile_mode(h, 0))
 
     # sample for the CPU baseline, taken before anything is updated
-    ns = min(args.cpu_sample, d)
+    # about 1e9 replica-param updates of CPU work: 2^26 / R coordinates per row
+    ns = min(args.cpu_sample if args.cpu_sample else (1 << 26) // R, d)
     if not args.no_cpu_baseline:
         x0_sample = [x[:ns].to(torch.float64).cpu().numpy() for x in x_src]
         g_samples = [[g[:ns].to(torch.float64).cpu().numpy() for g in gs] for gs in pool]
@@ -211,10 +215,18 @@ def main() -> int:
 
     torch.cuda.synchronize()
     B.dadam_destroy(h)
+    if args.copy_calibration:
+        n_cal = (1 << 30) // 4
+        src = torch.empty(n_cal, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         del x_src, x_dst, m_hat, v_hat, acc, pool
         torch.cuda.empty_cache()
-        iters = wl.s + 1
+        iters = min(wl.steps, max(wl.s + 1, int(1.2e9 // (R * ns))))
         v, dt = cpu_baseline(wl, x0_sample, g_samples, csrs, iters)
         out["cpu_baseline"] = {
             "value": v, "unit": "replica-params/s", "cores": 1, "kind": "oracle",

@@ -57,7 +57,8 @@ struct dadam_handle {
   std::vector<uint32_t> tensor_seg;  // segment of each non-empty tensor, UINT32_MAX for empty ones
   std::vector<Segment> segs;
   Segment* d_segs = nullptr;
-  TileShape shape{4, 1};
+  TileShape shape{4, 1, false};
+  bool nontemporal = false;
   int vec = 4;
   uint32_t tile_elems = 0, direct_elems = 0, lds_bytes = 0;
   bool tile_possible = false;
@@ -321,7 +322,7 @@ int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint6
   if (guard.err != hipSuccess) return fail(h, DADAM_EHIP, "hipSetDevice: %s", hipGetErrorString(guard.err));
   int e = tile_mode
               ? launch_tile((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase, h->shape, a, w1 - w0, h->lds_bytes, stream)
-              : launch_direct((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase, a, w1 - w0, stream);
+              : launch_direct((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase, h->nontemporal, a, w1 - w0, stream);
   if (e != (int)hipSuccess)
     return fail(h, DADAM_EHIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)e));
   return DADAM_OK;
@@ -390,6 +391,12 @@ int dadam_init(const dadam_config* cfg, dadam_handle** out) {
   TileShape shape;
   shape.ut = (cfg->n_cols * 2u * 1024u <= 32768u) ? 2 : 1;
   shape.waves = cfg->n_rows >= 32 ? 8 : 4;
+  // Non-temporal accesses pay off when an iteration's working set cannot stay in the last-level
+  // cache anyway; small problems keep ordinary accesses so that one iteration finds the previous
+  // one's output on chip.
+  const double touched = (double)cfg->d * cfg->n_rows * 24.0;
+  h->nontemporal = env_int("DADAM_NT", touched > 512.0 * 1024 * 1024 ? 1 : 0) != 0;
+  shape.nontemporal = h->nontemporal;
   shape.ut = env_int("DADAM_TILE_UT", shape.ut);
   shape.waves = env_int("DADAM_TILE_WAVES", shape.waves);
   if (!tile_shape_supported(shape)) {
@@ -587,7 +594,7 @@ int dadam_accumulate(dadam_handle* h, const void* const* grads, uint64_t t, void
   fill_scalars(h, t, &a.s);
   DeviceGuard guard(h->cfg.device);
   if (guard.err != hipSuccess) return fail(h, DADAM_EHIP, "hipSetDevice: %s", hipGetErrorString(guard.err));
-  int e = launch_accumulate((int)h->cfg.grad_dtype, fused_phase(h, t), a, w1 - w0, hip_stream, h->vec);
+  int e = launch_accumulate((int)h->cfg.grad_dtype, fused_phase(h, t), h->nontemporal, a, w1 - w0, hip_stream, h->vec);
   if (e != (int)hipSuccess)
     return fail(h, DADAM_EHIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)e));
   return DADAM_OK;

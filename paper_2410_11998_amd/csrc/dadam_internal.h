@@ -66,17 +66,18 @@ struct StepArgs {
 struct TileShape {
   int waves;  // wavefronts per workgroup (rows are dealt round-robin to them)
   int ut;     // 16-byte vectors per lane and row
+  bool nontemporal;  // streaming hint on every full-vector global access
 };
 
 // Launchers.  All of them enqueue on `stream` and return the hipError_t of the launch as int.
 // xdt / gdt are DADAM_F32 | DADAM_BF16.  n_work is the number of tiles in this launch.
 int launch_tile(int xdt, int gdt, Phase phase, TileShape shape, const StepArgs& a, uint32_t n_work,
                 uint32_t lds_bytes, void* stream);
-int launch_direct(int xdt, int gdt, Phase phase, const StepArgs& a, uint32_t n_work_tiles,
-                  void* stream);
+int launch_direct(int xdt, int gdt, Phase phase, bool nontemporal, const StepArgs& a,
+                  uint32_t n_work_tiles, void* stream);
 // vec = elements per direct-mode parameter vector of the handle (fixes the tile grid).
-int launch_accumulate(int gdt, Phase phase, const StepArgs& a, uint32_t n_work_tiles, void* stream,
-                      int vec);
+int launch_accumulate(int gdt, Phase phase, bool nontemporal, const StepArgs& a, uint32_t n_work_tiles,
+                      void* stream, int vec);
 
 // Geometry the host planner needs.
 int vec_elems(int xdt);              // elements per 16-byte parameter vector: 4 (f32) or 8 (bf16)

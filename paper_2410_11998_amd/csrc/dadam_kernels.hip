@@ -67,7 +67,20 @@ __device__ __forceinline__ void store_elem(void* base, uint64_t e, float v) {
 // VEC consecutive elements of type T starting at element e (e a multiple of VEC * ... such that the
 // address is 16-byte aligned), widened to float.  MASKED lanes that are not wholly inside [lo, hi)
 // touch only the elements that are; the others read as zero.
-template <typename T, int VEC, bool MASKED>
+// Streaming accesses: every global datum of a step is touched exactly once, so full-vector
+// accesses may carry the non-temporal hint (NT) and leave the caches to nobody in particular.
+template <bool NT, typename V>
+__device__ __forceinline__ V vload(const V* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT, typename V>
+__device__ __forceinline__ void vstore(V* p, V v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+template <typename T, int VEC, bool MASKED, bool NT>
 __device__ __forceinline__ void load_vals(const void* base, uint64_t e, uint64_t lo, uint64_t hi,
                                           float (&out)[VEC]) {
   if (!MASKED || (e >= lo && e + VEC <= hi)) {
@@ -75,17 +88,17 @@ __device__ __forceinline__ void load_vals(const void* base, uint64_t e, uint64_t
       const f4* p = reinterpret_cast<const f4*>(reinterpret_cast<const float*>(base) + e);
 #pragma unroll
       for (int q = 0; q < VEC / 4; ++q) {
-        f4 v = p[q];
+        f4 v = vload<NT>(p + q);
         out[4 * q + 0] = v.x; out[4 * q + 1] = v.y; out[4 * q + 2] = v.z; out[4 * q + 3] = v.w;
       }
     } else if constexpr (VEC == 8) {
-      u4 v = *reinterpret_cast<const u4*>(reinterpret_cast<const uint16_t*>(base) + e);
+      u4 v = vload<NT>(reinterpret_cast<const u4*>(reinterpret_cast<const uint16_t*>(base) + e));
       out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xFFFF0000u);
       out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xFFFF0000u);
       out[4] = __uint_as_float(v.z << 16); out[5] = __uint_as_float(v.z & 0xFFFF0000u);
       out[6] = __uint_as_float(v.w << 16); out[7] = __uint_as_float(v.w & 0xFFFF0000u);
     } else {
-      u2 v = *reinterpret_cast<const u2*>(reinterpret_cast<const uint16_t*>(base) + e);
+      u2 v = vload<NT>(reinterpret_cast<const u2*>(reinterpret_cast<const uint16_t*>(base) + e));
       out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xFFFF0000u);
       out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xFFFF0000u);
     }
@@ -98,7 +111,7 @@ __device__ __forceinline__ void load_vals(const void* base, uint64_t e, uint64_t
   }
 }
 
-template <typename T, int VEC, bool MASKED>
+template <typename T, int VEC, bool MASKED, bool NT>
 __device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, uint64_t hi,
                                            const float (&in)[VEC]) {
   if (!MASKED || (e >= lo && e + VEC <= hi)) {
@@ -108,7 +121,7 @@ __device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, 
       for (int q = 0; q < VEC / 4; ++q) {
         f4 v;
         v.x = in[4 * q + 0]; v.y = in[4 * q + 1]; v.z = in[4 * q + 2]; v.w = in[4 * q + 3];
-        p[q] = v;
+        vstore<NT>(p + q, v);
       }
     } else if constexpr (VEC == 8) {
       u4 v;
@@ -116,12 +129,12 @@ __device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, 
       v.y = f32_to_bf16_bits(in[2]) | (f32_to_bf16_bits(in[3]) << 16);
       v.z = f32_to_bf16_bits(in[4]) | (f32_to_bf16_bits(in[5]) << 16);
       v.w = f32_to_bf16_bits(in[6]) | (f32_to_bf16_bits(in[7]) << 16);
-      *reinterpret_cast<u4*>(reinterpret_cast<uint16_t*>(base) + e) = v;
+      vstore<NT>(reinterpret_cast<u4*>(reinterpret_cast<uint16_t*>(base) + e), v);
     } else {
       u2 v;
       v.x = f32_to_bf16_bits(in[0]) | (f32_to_bf16_bits(in[1]) << 16);
       v.y = f32_to_bf16_bits(in[2]) | (f32_to_bf16_bits(in[3]) << 16);
-      *reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(base) + e) = v;
+      vstore<NT>(reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(base) + e), v);
     }
   } else {
 #pragma unroll
@@ -133,11 +146,11 @@ __device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, 
 }
 
 // The 16 raw bytes of a parameter vector (4 float32 or 8 bfloat16), as they are parked in LDS.
-template <typename XT, bool MASKED>
+template <typename XT, bool MASKED, bool NT>
 __device__ __forceinline__ u4 load_raw(const void* base, uint64_t e, uint64_t lo, uint64_t hi) {
   constexpr int VEC = 16 / XT::bytes;
   if (!MASKED || (e >= lo && e + VEC <= hi)) {
-    return *reinterpret_cast<const u4*>(reinterpret_cast<const char*>(base) + e * XT::bytes);
+    return vload<NT>(reinterpret_cast<const u4*>(reinterpret_cast<const char*>(base) + e * XT::bytes));
   }
   u4 r = {0u, 0u, 0u, 0u};
   if constexpr (XT::bytes == 4) {
@@ -255,7 +268,7 @@ __device__ __forceinline__ float list_w(const RowList& r, int k) {
 // ---------------------------------------------------------------------------------------------
 // tile mode
 // ---------------------------------------------------------------------------------------------
-template <typename XT, typename GT, int PHASE, int W, int UT, bool MASKED>
+template <typename XT, typename GT, int PHASE, int W, int UT, bool MASKED, bool NT>
 __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t tbase, uint64_t lo,
                                           uint64_t hi, int lane, int wave) {
   constexpr int VEC = 16 / XT::bytes;
@@ -269,7 +282,7 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
     const void* src = a.x_src[c];
     u4 r[UT];
 #pragma unroll
-    for (int u = 0; u < UT; ++u) r[u] = load_raw<XT, MASKED>(src, e[u], lo, hi);
+    for (int u = 0; u < UT; ++u) r[u] = load_raw<XT, MASKED, NT>(src, e[u], lo, hi);
 #pragma unroll
     for (int u = 0; u < UT; ++u) lds[(c * UT + u) * kWave + lane] = r[u];
   }
@@ -282,20 +295,20 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
     if constexpr (Needs<PHASE>::grad) {
       const void* gp = a.grad[i];
 #pragma unroll
-      for (int u = 0; u < UT; ++u) load_vals<GT, VEC, MASKED>(gp, e[u], lo, hi, g[u]);
+      for (int u = 0; u < UT; ++u) load_vals<GT, VEC, MASKED, NT>(gp, e[u], lo, hi, g[u]);
     }
     if constexpr (Needs<PHASE>::moments_in) {
       const float* mp = a.m_hat[i];
       const float* vp = a.v_hat[i];
 #pragma unroll
-      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
     }
     if constexpr (Needs<PHASE>::acc_in) {
       const float* bp = a.acc[i];
 #pragma unroll
-      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
     }
 
     // neighbour sum in the order the row lists its entries: first a product, then fused
@@ -333,24 +346,24 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
 
     void* xd = a.x_dst[i];
 #pragma unroll
-    for (int u = 0; u < UT; ++u) store_vals<XT, VEC, MASKED>(xd, e[u], lo, hi, xo[u]);
+    for (int u = 0; u < UT; ++u) store_vals<XT, VEC, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
     if constexpr (Needs<PHASE>::acc_out) {
       float* bp = a.acc[i];
 #pragma unroll
-      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
     }
     if constexpr (Needs<PHASE>::moments_out) {
       float* mp = a.m_hat[i];
       float* vp = a.v_hat[i];
 #pragma unroll
-      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
     }
   }
 }
 
-template <typename XT, typename GT, int PHASE, int W, int UT>
+template <typename XT, typename GT, int PHASE, int W, int UT, bool NT>
 __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
   constexpr int VEC = 16 / XT::bytes;
   constexpr uint64_t TILE = (uint64_t)kWave * VEC * UT;
@@ -362,9 +375,9 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
   locate<true>(a, a.work_begin + blockIdx.x, tile_index, lo, hi);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
-    tile_body<XT, GT, PHASE, W, UT, false>(a, lds, tbase, lo, hi, lane, wave);
+    tile_body<XT, GT, PHASE, W, UT, false, NT>(a, lds, tbase, lo, hi, lane, wave);
   } else {
-    tile_body<XT, GT, PHASE, W, UT, true>(a, lds, tbase, lo, hi, lane, wave);
+    tile_body<XT, GT, PHASE, W, UT, true, NT>(a, lds, tbase, lo, hi, lane, wave);
   }
 }
 
@@ -374,7 +387,7 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
 constexpr int kUD = 2;  // 16-byte parameter vectors per thread
 
 // Neighbour sum with all loads of DEG sources issued before the first use.  DEG == 0: any degree.
-template <typename XT, int DEG, bool MASKED>
+template <typename XT, int DEG, bool MASKED, bool NT>
 __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
                                            const uint64_t (&e)[kUD], uint64_t lo, uint64_t hi,
                                            float (&mix)[kUD][16 / XT::bytes]) {
@@ -387,7 +400,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
       const void* src = a.x_src[list_col(rl, k)];
       wk[k] = list_w(rl, k);
 #pragma unroll
-      for (int u = 0; u < kUD; ++u) r[k][u] = load_raw<XT, MASKED>(src, e[u], lo, hi);
+      for (int u = 0; u < kUD; ++u) r[k][u] = load_raw<XT, MASKED, NT>(src, e[u], lo, hi);
     }
 #pragma unroll
     for (int k = 0; k < DEG; ++k)
@@ -405,7 +418,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
 #pragma unroll
       for (int u = 0; u < kUD; ++u) {
         float xs[VEC];
-        unpack_raw<XT>(load_raw<XT, MASKED>(src, e[u], lo, hi), xs);
+        unpack_raw<XT>(load_raw<XT, MASKED, NT>(src, e[u], lo, hi), xs);
 #pragma unroll
         for (int j = 0; j < VEC; ++j) mix[u][j] = w0 * xs[j];
       }
@@ -416,7 +429,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
 #pragma unroll
       for (int u = 0; u < kUD; ++u) {
         float xs[VEC];
-        unpack_raw<XT>(load_raw<XT, MASKED>(src, e[u], lo, hi), xs);
+        unpack_raw<XT>(load_raw<XT, MASKED, NT>(src, e[u], lo, hi), xs);
 #pragma unroll
         for (int j = 0; j < VEC; ++j) mix[u][j] = fmaf(wk, xs[j], mix[u][j]);
       }
@@ -424,7 +437,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
   }
 }
 
-template <typename XT, typename GT, int PHASE, bool MASKED>
+template <typename XT, typename GT, int PHASE, bool MASKED, bool NT>
 __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t tbase, uint64_t lo,
                                             uint64_t hi, int lane) {
   constexpr int VEC = 16 / XT::bytes;
@@ -445,29 +458,29 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
   if constexpr (Needs<PHASE>::grad) {
     const void* gp = a.grad[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, MASKED>(gp, e[u], lo, hi, g[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, MASKED, NT>(gp, e[u], lo, hi, g[u]);
   }
   if constexpr (Needs<PHASE>::moments_in) {
     const float* mp = a.m_hat[row];
     const float* vp = a.v_hat[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
   if constexpr (Needs<PHASE>::acc_in) {
     const float* bp = a.acc[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   float mix[kUD][VEC];
   switch (rl.deg) {
-    case 1: mix_direct<XT, 1, MASKED>(a, rl, e, lo, hi, mix); break;
-    case 2: mix_direct<XT, 2, MASKED>(a, rl, e, lo, hi, mix); break;
-    case 3: mix_direct<XT, 3, MASKED>(a, rl, e, lo, hi, mix); break;
-    case 4: mix_direct<XT, 4, MASKED>(a, rl, e, lo, hi, mix); break;
-    case 5: mix_direct<XT, 5, MASKED>(a, rl, e, lo, hi, mix); break;
-    default: mix_direct<XT, 0, MASKED>(a, rl, e, lo, hi, mix); break;
+    case 1: mix_direct<XT, 1, MASKED, NT>(a, rl, e, lo, hi, mix); break;
+    case 2: mix_direct<XT, 2, MASKED, NT>(a, rl, e, lo, hi, mix); break;
+    case 3: mix_direct<XT, 3, MASKED, NT>(a, rl, e, lo, hi, mix); break;
+    case 4: mix_direct<XT, 4, MASKED, NT>(a, rl, e, lo, hi, mix); break;
+    case 5: mix_direct<XT, 5, MASKED, NT>(a, rl, e, lo, hi, mix); break;
+    default: mix_direct<XT, 0, MASKED, NT>(a, rl, e, lo, hi, mix); break;
   }
   float xo[kUD][VEC];
 #pragma unroll
@@ -477,25 +490,25 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
       xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j]);
   void* xd = a.x_dst[row];
 #pragma unroll
-  for (int u = 0; u < kUD; ++u) store_vals<XT, VEC, MASKED>(xd, e[u], lo, hi, xo[u]);
+  for (int u = 0; u < kUD; ++u) store_vals<XT, VEC, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
   if constexpr (Needs<PHASE>::acc_out) {
     float* bp = a.acc[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   if constexpr (Needs<PHASE>::moments_out) {
     float* mp = a.m_hat[row];
     float* vp = a.v_hat[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
 }
 
 // Work items are numbered tile-major, row-minor, so that workgroups running at the same time work
 // on the same elements of different rows.
-template <typename XT, typename GT, int PHASE>
+template <typename XT, typename GT, int PHASE, bool NT>
 __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
   constexpr int VEC = 16 / XT::bytes;
   constexpr uint64_t TILE = (uint64_t)kDirectThreads * VEC * kUD;
@@ -507,9 +520,9 @@ __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
   locate<false>(a, a.work_begin + t, tile_index, lo, hi);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
-    direct_body<XT, GT, PHASE, false>(a, row, tbase, lo, hi, lane);
+    direct_body<XT, GT, PHASE, false, NT>(a, row, tbase, lo, hi, lane);
   } else {
-    direct_body<XT, GT, PHASE, true>(a, row, tbase, lo, hi, lane);
+    direct_body<XT, GT, PHASE, true, NT>(a, row, tbase, lo, hi, lane);
   }
 }
 
@@ -528,7 +541,7 @@ __device__ __forceinline__ void acc_step(const Scalars& s, float g, float& mh, f
   }
 }
 
-template <typename GT, int VEC, int PHASE, bool MASKED>
+template <typename GT, int VEC, int PHASE, bool MASKED, bool NT>
 __device__ __forceinline__ void acc_body(const StepArgs& a, int row, uint64_t tbase, uint64_t lo,
                                          uint64_t hi) {
   uint64_t e[kUD];
@@ -537,19 +550,19 @@ __device__ __forceinline__ void acc_body(const StepArgs& a, int row, uint64_t tb
   float g[kUD][VEC], mh[kUD][VEC], vh[kUD][VEC], b[kUD][VEC];
   const void* gp = a.grad[row];
 #pragma unroll
-  for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, MASKED>(gp, e[u], lo, hi, g[u]);
+  for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, MASKED, NT>(gp, e[u], lo, hi, g[u]);
   if constexpr (Needs<PHASE>::moments_out) {
     const float* mp = a.m_hat[row];
     const float* vp = a.v_hat[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
   if constexpr (Needs<PHASE>::acc_in) {
     const float* bp = a.acc[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
 #pragma unroll
   for (int u = 0; u < kUD; ++u)
@@ -558,21 +571,21 @@ __device__ __forceinline__ void acc_body(const StepArgs& a, int row, uint64_t tb
   if constexpr (Needs<PHASE>::acc_out) {
     float* bp = a.acc[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(bp, e[u], lo, hi, b[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   if constexpr (Needs<PHASE>::moments_out) {
     float* mp = a.m_hat[row];
     float* vp = a.v_hat[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(mp, e[u], lo, hi, mh[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED>(vp, e[u], lo, hi, vh[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
 }
 
 // VEC is the element count of a direct-mode parameter vector of this handle, so that the
 // accumulate kernel walks the same tile grid as the direct kernel.
-template <typename GT, int VEC, int PHASE>
+template <typename GT, int VEC, int PHASE, bool NT>
 __global__ __launch_bounds__(kDirectThreads) void k_acc(const StepArgs a) {
   constexpr uint64_t TILE = (uint64_t)kDirectThreads * VEC * kUD;
   const uint32_t n_rows = a.n_rows;
@@ -582,9 +595,9 @@ __global__ __launch_bounds__(kDirectThreads) void k_acc(const StepArgs a) {
   locate<false>(a, a.work_begin + t, tile_index, lo, hi);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
-    acc_body<GT, VEC, PHASE, false>(a, row, tbase, lo, hi);
+    acc_body<GT, VEC, PHASE, false, NT>(a, row, tbase, lo, hi);
   } else {
-    acc_body<GT, VEC, PHASE, true>(a, row, tbase, lo, hi);
+    acc_body<GT, VEC, PHASE, true, NT>(a, row, tbase, lo, hi);
   }
 }
 
@@ -593,48 +606,52 @@ __global__ __launch_bounds__(kDirectThreads) void k_acc(const StepArgs a) {
 // ---------------------------------------------------------------------------------------------
 typedef void (*KernelFn)(const StepArgs);
 
-template <typename XT, typename GT, int W, int UT>
+template <typename XT, typename GT, int W, int UT, bool NT>
 KernelFn tile_kernel_for_phase(int phase) {
   switch (phase) {
-    case kMixOnly: return k_tile<XT, GT, kMixOnly, W, UT>;
-    case kUpdateOnly: return k_tile<XT, GT, kUpdateOnly, W, UT>;
-    case kPlain: return k_tile<XT, GT, kPlain, W, UT>;
-    case kLoopStart: return k_tile<XT, GT, kLoopStart, W, UT>;
-    case kFold: return k_tile<XT, GT, kFold, W, UT>;
-    case kAlg1: return k_tile<XT, GT, kAlg1, W, UT>;
+    case kMixOnly: return k_tile<XT, GT, kMixOnly, W, UT, NT>;
+    case kUpdateOnly: return k_tile<XT, GT, kUpdateOnly, W, UT, NT>;
+    case kPlain: return k_tile<XT, GT, kPlain, W, UT, NT>;
+    case kLoopStart: return k_tile<XT, GT, kLoopStart, W, UT, NT>;
+    case kFold: return k_tile<XT, GT, kFold, W, UT, NT>;
+    case kAlg1: return k_tile<XT, GT, kAlg1, W, UT, NT>;
   }
   return nullptr;
 }
 
+template <typename XT, typename GT, bool NT>
+KernelFn tile_kernel_for_shape_nt(int phase, TileShape s) {
+  if (s.waves == 4 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 4, 1, NT>(phase);
+  if (s.waves == 4 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 4, 2, NT>(phase);
+  if (s.waves == 8 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 8, 1, NT>(phase);
+  if (s.waves == 8 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 8, 2, NT>(phase);
+  return nullptr;
+}
 template <typename XT, typename GT>
 KernelFn tile_kernel_for_shape(int phase, TileShape s) {
-  if (s.waves == 4 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 4, 1>(phase);
-  if (s.waves == 4 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 4, 2>(phase);
-  if (s.waves == 8 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 8, 1>(phase);
-  if (s.waves == 8 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 8, 2>(phase);
-  return nullptr;
+  return s.nontemporal ? tile_kernel_for_shape_nt<XT, GT, true>(phase, s) : tile_kernel_for_shape_nt<XT, GT, false>(phase, s);
 }
 
-template <typename XT, typename GT>
+template <typename XT, typename GT, bool NT>
 KernelFn direct_kernel_for_phase(int phase) {
   switch (phase) {
-    case kMixOnly: return k_direct<XT, GT, kMixOnly>;
-    case kUpdateOnly: return k_direct<XT, GT, kUpdateOnly>;
-    case kPlain: return k_direct<XT, GT, kPlain>;
-    case kLoopStart: return k_direct<XT, GT, kLoopStart>;
-    case kFold: return k_direct<XT, GT, kFold>;
-    case kAlg1: return k_direct<XT, GT, kAlg1>;
+    case kMixOnly: return k_direct<XT, GT, kMixOnly, NT>;
+    case kUpdateOnly: return k_direct<XT, GT, kUpdateOnly, NT>;
+    case kPlain: return k_direct<XT, GT, kPlain, NT>;
+    case kLoopStart: return k_direct<XT, GT, kLoopStart, NT>;
+    case kFold: return k_direct<XT, GT, kFold, NT>;
+    case kAlg1: return k_direct<XT, GT, kAlg1, NT>;
   }
   return nullptr;
 }
 
-template <typename GT, int VEC>
+template <typename GT, int VEC, bool NT>
 KernelFn acc_kernel_for_phase(int phase) {
   switch (phase) {
-    case kPlain: return k_acc<GT, VEC, kPlain>;
-    case kLoopStart: return k_acc<GT, VEC, kLoopStart>;
-    case kFold: return k_acc<GT, VEC, kFold>;
-    case kAlg1: return k_acc<GT, VEC, kAlg1>;
+    case kPlain: return k_acc<GT, VEC, kPlain, NT>;
+    case kLoopStart: return k_acc<GT, VEC, kLoopStart, NT>;
+    case kFold: return k_acc<GT, VEC, kFold, NT>;
+    case kAlg1: return k_acc<GT, VEC, kAlg1, NT>;
   }
   return nullptr;
 }
@@ -666,22 +683,26 @@ int launch_tile(int xdt, int gdt, Phase phase, TileShape shape, const StepArgs& 
   return launch(fn, n_work, (uint32_t)(kWave * shape.waves), lds_bytes, a, stream);
 }
 
-int launch_direct(int xdt, int gdt, Phase phase, const StepArgs& a, uint32_t n_work_tiles, void* stream) {
+int launch_direct(int xdt, int gdt, Phase phase, bool nt, const StepArgs& a, uint32_t n_work_tiles, void* stream) {
   KernelFn fn = nullptr;
-  if (xdt == DADAM_F32 && gdt == DADAM_F32) fn = direct_kernel_for_phase<TF32, TF32>(phase);
-  if (xdt == DADAM_BF16 && gdt == DADAM_BF16) fn = direct_kernel_for_phase<TBF16, TBF16>(phase);
-  if (xdt == DADAM_BF16 && gdt == DADAM_F32) fn = direct_kernel_for_phase<TBF16, TF32>(phase);
-  if (xdt == DADAM_F32 && gdt == DADAM_BF16) fn = direct_kernel_for_phase<TF32, TBF16>(phase);
+#define DADAM_PICK(XT, GT) (nt ? direct_kernel_for_phase<XT, GT, true>(phase) : direct_kernel_for_phase<XT, GT, false>(phase))
+  if (xdt == DADAM_F32 && gdt == DADAM_F32) fn = DADAM_PICK(TF32, TF32);
+  if (xdt == DADAM_BF16 && gdt == DADAM_BF16) fn = DADAM_PICK(TBF16, TBF16);
+  if (xdt == DADAM_BF16 && gdt == DADAM_F32) fn = DADAM_PICK(TBF16, TF32);
+  if (xdt == DADAM_F32 && gdt == DADAM_BF16) fn = DADAM_PICK(TF32, TBF16);
+#undef DADAM_PICK
   return launch(fn, n_work_tiles * a.n_rows, kDirectThreads, 0, a, stream);
 }
 
-int launch_accumulate(int gdt, Phase phase, const StepArgs& a, uint32_t n_work_tiles, void* stream,
+int launch_accumulate(int gdt, Phase phase, bool nt, const StepArgs& a, uint32_t n_work_tiles, void* stream,
                       int vec) {
   KernelFn fn = nullptr;
-  if (gdt == DADAM_F32 && vec == 4) fn = acc_kernel_for_phase<TF32, 4>(phase);
-  if (gdt == DADAM_F32 && vec == 8) fn = acc_kernel_for_phase<TF32, 8>(phase);
-  if (gdt == DADAM_BF16 && vec == 4) fn = acc_kernel_for_phase<TBF16, 4>(phase);
-  if (gdt == DADAM_BF16 && vec == 8) fn = acc_kernel_for_phase<TBF16, 8>(phase);
+#define DADAM_PICK(GT, VEC) (nt ? acc_kernel_for_phase<GT, VEC, true>(phase) : acc_kernel_for_phase<GT, VEC, false>(phase))
+  if (gdt == DADAM_F32 && vec == 4) fn = DADAM_PICK(TF32, 4);
+  if (gdt == DADAM_F32 && vec == 8) fn = DADAM_PICK(TF32, 8);
+  if (gdt == DADAM_BF16 && vec == 4) fn = DADAM_PICK(TBF16, 4);
+  if (gdt == DADAM_BF16 && vec == 8) fn = DADAM_PICK(TBF16, 8);
+#undef DADAM_PICK
   return launch(fn, n_work_tiles * a.n_rows, kDirectThreads, 0, a, stream);
 }
 
