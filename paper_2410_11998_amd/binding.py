@@ -18,7 +18,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdadam.so")
+LIB_PATH = os.environ.get("DADAM_LIB") or os.path.join(_HERE, "libdadam.so")   # DADAM_LIB: a differently tuned build
 
 DADAM_ABI_VERSION = 1
 DADAM_MAX_ROWS = 64

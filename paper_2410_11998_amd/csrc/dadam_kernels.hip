@@ -69,6 +69,13 @@ __device__ __forceinline__ void store_elem(void* base, uint64_t e, float v) {
 // touch only the elements that are; the others read as zero.
 // Streaming accesses: every global datum of a step is touched exactly once, so full-vector
 // accesses may carry the non-temporal hint (NT) and leave the caches to nobody in particular.
+#ifndef DADAM_NT_BITS
+#define DADAM_NT_BITS 5
+#endif
+constexpr bool kNtSource = (DADAM_NT_BITS & 1) != 0;  // parameter (source) loads
+constexpr bool kNtStream = (DADAM_NT_BITS & 2) != 0;  // gradient / moment / accumulator loads
+constexpr bool kNtStore = (DADAM_NT_BITS & 4) != 0;   // all stores
+
 template <bool NT, typename V>
 __device__ __forceinline__ V vload(const V* p) {
   if constexpr (NT) return __builtin_nontemporal_load(p);
@@ -88,17 +95,17 @@ __device__ __forceinline__ void load_vals(const void* base, uint64_t e, uint64_t
       const f4* p = reinterpret_cast<const f4*>(reinterpret_cast<const float*>(base) + e);
 #pragma unroll
       for (int q = 0; q < VEC / 4; ++q) {
-        f4 v = vload<NT>(p + q);
+        f4 v = vload<NT && kNtStream>(p + q);
         out[4 * q + 0] = v.x; out[4 * q + 1] = v.y; out[4 * q + 2] = v.z; out[4 * q + 3] = v.w;
       }
     } else if constexpr (VEC == 8) {
-      u4 v = vload<NT>(reinterpret_cast<const u4*>(reinterpret_cast<const uint16_t*>(base) + e));
+      u4 v = vload<NT && kNtStream>(reinterpret_cast<const u4*>(reinterpret_cast<const uint16_t*>(base) + e));
       out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xFFFF0000u);
       out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xFFFF0000u);
       out[4] = __uint_as_float(v.z << 16); out[5] = __uint_as_float(v.z & 0xFFFF0000u);
       out[6] = __uint_as_float(v.w << 16); out[7] = __uint_as_float(v.w & 0xFFFF0000u);
     } else {
-      u2 v = vload<NT>(reinterpret_cast<const u2*>(reinterpret_cast<const uint16_t*>(base) + e));
+      u2 v = vload<NT && kNtStream>(reinterpret_cast<const u2*>(reinterpret_cast<const uint16_t*>(base) + e));
       out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xFFFF0000u);
       out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xFFFF0000u);
     }
@@ -121,7 +128,7 @@ __device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, 
       for (int q = 0; q < VEC / 4; ++q) {
         f4 v;
         v.x = in[4 * q + 0]; v.y = in[4 * q + 1]; v.z = in[4 * q + 2]; v.w = in[4 * q + 3];
-        vstore<NT>(p + q, v);
+        vstore<NT && kNtStore>(p + q, v);
       }
     } else if constexpr (VEC == 8) {
       u4 v;
@@ -129,12 +136,12 @@ __device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, 
       v.y = f32_to_bf16_bits(in[2]) | (f32_to_bf16_bits(in[3]) << 16);
       v.z = f32_to_bf16_bits(in[4]) | (f32_to_bf16_bits(in[5]) << 16);
       v.w = f32_to_bf16_bits(in[6]) | (f32_to_bf16_bits(in[7]) << 16);
-      vstore<NT>(reinterpret_cast<u4*>(reinterpret_cast<uint16_t*>(base) + e), v);
+      vstore<NT && kNtStore>(reinterpret_cast<u4*>(reinterpret_cast<uint16_t*>(base) + e), v);
     } else {
       u2 v;
       v.x = f32_to_bf16_bits(in[0]) | (f32_to_bf16_bits(in[1]) << 16);
       v.y = f32_to_bf16_bits(in[2]) | (f32_to_bf16_bits(in[3]) << 16);
-      vstore<NT>(reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(base) + e), v);
+      vstore<NT && kNtStore>(reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(base) + e), v);
     }
   } else {
 #pragma unroll
@@ -150,7 +157,7 @@ template <typename XT, bool MASKED, bool NT>
 __device__ __forceinline__ u4 load_raw(const void* base, uint64_t e, uint64_t lo, uint64_t hi) {
   constexpr int VEC = 16 / XT::bytes;
   if (!MASKED || (e >= lo && e + VEC <= hi)) {
-    return vload<NT>(reinterpret_cast<const u4*>(reinterpret_cast<const char*>(base) + e * XT::bytes));
+    return vload<NT && kNtSource>(reinterpret_cast<const u4*>(reinterpret_cast<const char*>(base) + e * XT::bytes));
   }
   u4 r = {0u, 0u, 0u, 0u};
   if constexpr (XT::bytes == 4) {
@@ -384,7 +391,10 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
 // ---------------------------------------------------------------------------------------------
 // direct mode
 // ---------------------------------------------------------------------------------------------
-constexpr int kUD = 2;  // 16-byte parameter vectors per thread
+#ifndef DADAM_DIRECT_UNROLL
+#define DADAM_DIRECT_UNROLL 2
+#endif
+constexpr int kUD = DADAM_DIRECT_UNROLL;  // 16-byte parameter vectors per thread
 
 // Neighbour sum with all loads of DEG sources issued before the first use.  DEG == 0: any degree.
 template <typename XT, int DEG, bool MASKED, bool NT>
@@ -625,6 +635,14 @@ KernelFn tile_kernel_for_shape_nt(int phase, TileShape s) {
   if (s.waves == 4 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 4, 2, NT>(phase);
   if (s.waves == 8 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 8, 1, NT>(phase);
   if (s.waves == 8 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 8, 2, NT>(phase);
+#ifdef DADAM_ALL_SHAPES
+  if (s.waves == 1 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 1, 1, NT>(phase);
+  if (s.waves == 2 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 2, 1, NT>(phase);
+  if (s.waves == 2 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 2, 2, NT>(phase);
+  if (s.waves == 16 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 16, 1, NT>(phase);
+  if (s.waves == 4 && s.ut == 4) return tile_kernel_for_phase<XT, GT, 4, 4, NT>(phase);
+  if (s.waves == 8 && s.ut == 4) return tile_kernel_for_phase<XT, GT, 8, 4, NT>(phase);
+#endif
   return nullptr;
 }
 template <typename XT, typename GT>
@@ -670,6 +688,9 @@ static_assert(sizeof(StepArgs) <= 4096, "kernel argument block must fit the kern
 int vec_elems(int xdt) { return xdt == DADAM_BF16 ? 8 : 4; }
 int direct_unroll() { return kUD; }
 bool tile_shape_supported(TileShape s) {
+#ifdef DADAM_ALL_SHAPES
+  return true;
+#endif
   return (s.waves == 4 || s.waves == 8) && (s.ut == 1 || s.ut == 2);
 }
 

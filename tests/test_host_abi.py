@@ -71,7 +71,7 @@ def test_planner_segments_and_tiles():
     h = B.dadam_init(2, 2, 5000, [0, 100, 300, 300, 1000], [100, 200, 0, 10, 4000], device=B.DADAM_DEVICE_NONE)
     info = B.dadam_get_plan_info(h)
     assert info.n_segments == 2       # [0,310) [1000,5000)
-    assert info.tile_elems == 64 * 4 * 2 and info.lds_bytes_tile == 2 * 2 * 64 * 16
+    assert info.tile_elems == 64 * 4 and info.lds_bytes_tile == 2 * 64 * 16     # 16 bytes per lane and source
     assert info.direct_elems == 256 * 4 * 2
     T = info.tile_elems
     want = sum((hi - 1) // T - lo // T + 1 for lo, hi in ((0, 310), (1000, 5000)))
