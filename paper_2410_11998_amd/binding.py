@@ -103,8 +103,28 @@ def _ptr_array(ptrs: Sequence[int]):
     return arr
 
 
-def _ptrs_of(tensors) -> Sequence[int]:
-    return [t if isinstance(t, int) else t.data_ptr() for t in tensors]
+_SHAPE_OF_HANDLE = {}   # handle value -> (d, bytes per parameter, bytes per gradient): host-side size checks only
+
+
+def _ptrs_of(tensors, h=None, elem_bytes: int = 0, what: str = "") -> Sequence[int]:
+    """Device addresses of tensors (or integers taken as addresses).  When tensors are given, their
+    size is checked against the handle's d before the address is handed to the library: a buffer
+    shorter than d would be overrun by the kernels, which no later check can catch."""
+    out = []
+    info = _SHAPE_OF_HANDLE.get(getattr(h, "value", None)) if h is not None else None
+    for k, t in enumerate(tensors):
+        if isinstance(t, int):
+            out.append(t)
+            continue
+        if info is not None and elem_bytes:
+            if not t.is_contiguous():
+                raise ValueError(f"{what}[{k}] is not contiguous")
+            if t.element_size() != elem_bytes:
+                raise ValueError(f"{what}[{k}] has {t.element_size()}-byte elements, the handle expects {elem_bytes}")
+            if t.numel() < info[0]:
+                raise ValueError(f"{what}[{k}] holds {t.numel()} elements, the handle needs {info[0]}")
+        out.append(t.data_ptr())
+    return out
 
 
 def _check(h, rc: int) -> int:
@@ -145,6 +165,7 @@ def dadam_init(n_rows: int, n_cols: int, d: int, offsets: Sequence[int], numels:
     rc = lib.dadam_init(C.byref(cfg), C.byref(h))
     if rc < 0:
         raise DadamError(rc, (lib.dadam_last_error(None) or b"").decode())
+    _SHAPE_OF_HANDLE[h.value] = (int(d), 2 if param_dtype == DADAM_BF16 else 4, 2 if grad_dtype == DADAM_BF16 else 4)
     return h
 
 
@@ -159,8 +180,10 @@ def dadam_set_topology(h, slot: int, row_ptr, col_idx, w) -> int:
 
 
 def dadam_bind(h, x_src, x_dst, m_hat, v_hat, acc=None) -> None:
-    keep = [_ptr_array(_ptrs_of(x_src)), _ptr_array(_ptrs_of(x_dst)), _ptr_array(_ptrs_of(m_hat)), _ptr_array(_ptrs_of(v_hat)),
-            _ptr_array(_ptrs_of(acc)) if acc is not None else None]
+    px = _SHAPE_OF_HANDLE.get(h.value, (0, 0, 0))[1]
+    keep = [_ptr_array(_ptrs_of(x_src, h, px, "x_src")), _ptr_array(_ptrs_of(x_dst, h, px, "x_dst")),
+            _ptr_array(_ptrs_of(m_hat, h, 4, "m_hat")), _ptr_array(_ptrs_of(v_hat, h, 4, "v_hat")),
+            _ptr_array(_ptrs_of(acc, h, 4, "acc")) if acc is not None else None]
     b = dadam_buffers(keep[0], keep[1], keep[2], keep[3], keep[4] if keep[4] is not None else C.POINTER(C.c_void_p)())
     _check(h, lib.dadam_bind(h, C.byref(b)))
 
@@ -169,16 +192,20 @@ def dadam_swap_x(h) -> None:
     _check(h, lib.dadam_swap_x(h))
 
 
+def _grad_ptrs(h, grads):
+    return _ptr_array(_ptrs_of(grads, h, _SHAPE_OF_HANDLE.get(h.value, (0, 0, 0))[2], "grads"))
+
+
 def dadam_gossip_step(h, slot: int, grads, t: int, flags: int = DADAM_FUSE_ACCUM, stream: int = 0) -> None:
-    _check(h, lib.dadam_gossip_step(h, slot, _ptr_array(_ptrs_of(grads)), t, flags, C.c_void_p(stream)))
+    _check(h, lib.dadam_gossip_step(h, slot, _grad_ptrs(h, grads), t, flags, C.c_void_p(stream)))
 
 
 def dadam_gossip_step_range(h, slot: int, grads, t: int, flags: int, tensor_begin: int, tensor_end: int, stream: int = 0) -> None:
-    _check(h, lib.dadam_gossip_step_range(h, slot, _ptr_array(_ptrs_of(grads)), t, flags, tensor_begin, tensor_end, C.c_void_p(stream)))
+    _check(h, lib.dadam_gossip_step_range(h, slot, _grad_ptrs(h, grads), t, flags, tensor_begin, tensor_end, C.c_void_p(stream)))
 
 
 def dadam_accumulate(h, grads, t: int, stream: int = 0) -> None:
-    _check(h, lib.dadam_accumulate(h, _ptr_array(_ptrs_of(grads)), t, C.c_void_p(stream)))
+    _check(h, lib.dadam_accumulate(h, _grad_ptrs(h, grads), t, C.c_void_p(stream)))
 
 
 def dadam_mix(h, slot: int, flags: int = 0, stream: int = 0) -> None:
@@ -200,6 +227,7 @@ def dadam_slot_uses_tile_mode(h, slot: int) -> bool:
 
 
 def dadam_destroy(h) -> None:
+    _SHAPE_OF_HANDLE.pop(getattr(h, "value", None), None)
     lib.dadam_destroy(h)
 
 

@@ -189,3 +189,27 @@ def test_null_handle_is_an_error_not_a_crash():
     assert B.lib.dadam_gossip_step(null, 0, None, 1, 1, None) == B.DADAM_EINVAL
     assert B.lib.dadam_init(None, None) == B.DADAM_EINVAL
     B.lib.dadam_destroy(null)
+
+
+def test_binding_rejects_short_or_mistyped_tensors():
+    """The library cannot know how large a caller's buffer is; the binding can when it is handed
+    tensors, and must refuse a buffer shorter than d before any kernel could overrun it."""
+    import torch
+    h, L = host_handle(2, 2, accum_s=2)
+    full = lambda dt=torch.float32: torch.zeros(L.d, dtype=dt)
+    short = torch.zeros(L.d - 8)
+    good = dict(x_src=[full(), full()], x_dst=[full(), full()], m_hat=[full(), full()], v_hat=[full(), full()], acc=[full(), full()])
+    B.dadam_bind(h, **good)
+    for key in good:
+        bad = dict(good); bad[key] = [good[key][0], short]
+        with pytest.raises(ValueError):
+            B.dadam_bind(h, **bad)
+    with pytest.raises(ValueError):
+        B.dadam_bind(h, **{**good, "x_src": [full(torch.bfloat16), full()]})
+    with pytest.raises(ValueError):
+        B.dadam_bind(h, **{**good, "m_hat": [full()[::2], full()]})
+    with pytest.raises(ValueError):
+        B.dadam_gossip_step(h, 0, [full(), short], 1)
+    with pytest.raises(ValueError):
+        B.dadam_accumulate(h, [short, full()], 1)
+    B.dadam_destroy(h)
