@@ -25,6 +25,18 @@ if ROOT not in sys.path:
 
 HBM_PEAK_BYTES_PER_S = 8.0e12   # MI355X HBM3E, published peak
 
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, each in a run of
+# its own, each scaled by what the same counter reads for a plain 1 GiB device copy: FETCH_SIZE x 2.000,
+# WRITE_SIZE x 1.000), by workload and phase of the accumulation loop.  The summaries these come from
+# are profiles/fused_step_<workload>.txt.  They cannot be measured inside this script, so they are
+# quoted; a workload or kernel shape without a measurement reports null.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg2_exp16_gpt2small": {"loopstart": 47784529742, "plain": 55747879784, "fold": 71676151167},
+    "cfg3_nodeshare_gpt2medium": {"loopstart": 11354285401, "plain": 12773537619, "fold": 15612116211},
+    "cfg4_onepeer64_resnet50": {"loopstart": 39255220798, "fold": 58882770772},
+    "cfg5_ring8_gpt2large_bf16": {"loopstart": 111464158248, "plain": 136232861925, "fold": 185794734270},
+}
+
 
 def phase_of(t: int, s: int) -> str:
     if s == 1:
@@ -81,6 +93,10 @@ def main() -> int:
     ap.add_argument("--mode", choices=["auto", "tile", "direct"], default="auto")
     ap.add_argument("--inplace", action="store_true", help="update parameters in place instead of ping-pong")
     ap.add_argument("--pool", type=int, default=2, help="number of pre-generated gradient sets cycled through")
+    ap.add_argument("--layout", choices=["spread", "packed"], default="spread",
+                    help="spread: one arena over most of the free HBM, buffers at equal distances (faster, see "
+                         "paper_2410_11998_amd/arena.py); packed: one ordinary allocation per buffer")
+    ap.add_argument("--span-gib", type=int, default=0, help="arena size for --layout spread (default: free memory minus 12 GiB)")
     ap.add_argument("--scale-div", type=int, default=1, help="divide tensor dimensions (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=None, help="coordinates per row given to the CPU oracle")
@@ -115,24 +131,44 @@ def main() -> int:
     inplace = args.inplace or R != C
 
     # ---- resident inputs ----------------------------------------------------------------
+    # Buffers in layout order: sources (own replicas, then receive buffers), outputs (unless in
+    # place), m_hat, v_hat, b, then the gradient pool.
+    n_pool = max(1, args.pool)
+    kinds = [("x_src", pdt)] * C + ([] if inplace else [("x_dst", pdt)] * R) + [("m", torch.float32)] * R + \
+            [("v", torch.float32)] * R + ([("b", torch.float32)] * R if wl.s > 1 else []) + [("g", gdt)] * (R * n_pool)
+    esize = {torch.float32: 4, torch.bfloat16: 2}
+    if args.layout == "spread":
+        from paper_2410_11998_amd.arena import SpreadArena
+        arena = SpreadArena([d * esize[dt] for _, dt in kinds], dev,
+                            span_bytes=(args.span_gib << 30) if args.span_gib else None)
+        bufs = arena.views([dt for _, dt in kinds])
+        span_gib = arena.span_bytes / 2 ** 30
+    else:
+        bufs = [torch.empty(d, dtype=dt, device=dev) for _, dt in kinds]
+        span_gib = None
+    take = lambda name: [b for (k, _), b in zip(kinds, bufs) if k == name]
+    x_src = take("x_src")
+    x_dst = x_src[:R] if inplace else take("x_dst")
+    m_hat, v_hat = take("m"), take("v")
+    acc = take("b") if wl.s > 1 else None
+    gflat = take("g")
+    pool = [gflat[p * R:(p + 1) * R] for p in range(n_pool)]
     x0 = WL.normal_torch(WL.seed_for(wl.cfg, 0), (d,), wl.param_std, dev, pdt)     # one draw shared by all replicas
-    x_src = [x0.clone() for _ in range(R)]
+    for i in range(R):
+        x_src[i].copy_(x0)
     for c in range(R, C):                                                          # neighbours' receive buffers
-        x_src.append(WL.normal_torch(WL.seed_for(wl.cfg, 1) + c, (d,), wl.param_std, dev, pdt))
+        x_src[c].copy_(WL.normal_torch(WL.seed_for(wl.cfg, 1) + c, (d,), wl.param_std, dev, pdt))
     del x0
-    x_dst = x_src[:R] if inplace else [torch.zeros(d, dtype=pdt, device=dev) for _ in range(R)]
-    m_hat = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(R)]
-    v_hat = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(R)]
-    acc = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(R)] if wl.s > 1 else None
-    pool = []
+    for t_ in ([] if inplace else x_dst) + m_hat + v_hat + (acc or []):
+        t_.zero_()
     gen = torch.Generator(device=dev)
-    for p in range(max(1, args.pool)):
+    tmp = torch.empty(d, dtype=torch.float32, device=dev)
+    for p in range(n_pool):
         gen.manual_seed(WL.seed_for(wl.cfg, 2 + p))
-        gs = []
         for i in range(R):
-            g = torch.empty(d, dtype=torch.float32, device=dev).normal_(0.0, wl.grad_std, generator=gen)
-            gs.append(g if gdt == torch.float32 else g.to(gdt))
-        pool.append(gs)
+            tmp.normal_(0.0, wl.grad_std, generator=gen)
+            pool[p][i].copy_(tmp)
+    del tmp
 
     csrs = [wl.csr(k) for k in range(wl.n_slots())]
     h = B.dadam_init(R, C, d, layout.offsets, layout.numels, ADT[wl.param_dtype], ADT[wl.grad_dtype], wl.lr, wl.beta1,
@@ -183,6 +219,10 @@ def main() -> int:
     value = replica_params * K / elapsed
     bytes_per_launch = replica_params * sum(algorithmic_bytes_per_replica_param(wl, p) for p in phases) / K
     achieved = bytes_per_launch / avg_kernel_s
+    traffic = None
+    table = MEASURED_TRAFFIC_BYTES.get(wl.name)
+    if table is not None and args.mode == "auto" and all(p in table for p in phases):
+        traffic = sum(table[p] for p in phases) / K
     by_phase = {}
     for p, ms in zip(phases, kernel_ms):
         by_phase.setdefault(p, []).append(ms)
@@ -203,11 +243,12 @@ def main() -> int:
         "config": {
             "workload": wl.name, "n_rows": R, "n_sources": C, "d": d, "tensors": len(layout.names), "topology": wl.topology,
             "accum_s": wl.s, "kernel": ("k_tile" if tile_mode else "k_direct"), "x_buffers": "in-place" if inplace else "ping-pong",
+            "hbm_layout": args.layout if span_gib is None else f"spread over {span_gib:.0f} GiB",
             "grad_pool": len(pool),
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK_BYTES_PER_S / 1e9, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_BYTES_PER_S, "traffic": None,
+            "frac": achieved / HBM_PEAK_BYTES_PER_S, "traffic": traffic,
             "algorithmic_bytes_per_launch": bytes_per_launch, "avg_launch_ms": avg_kernel_s * 1e3,
             "ms_by_phase": {p: sum(v) / len(v) for p, v in by_phase.items()},
         },
@@ -224,7 +265,9 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
     if not args.no_cpu_baseline:
-        del x_src, x_dst, m_hat, v_hat, acc, pool
+        del x_src, x_dst, m_hat, v_hat, acc, pool, gflat, bufs
+        if args.layout == "spread":
+            del arena
         torch.cuda.empty_cache()
         iters = min(wl.steps, max(wl.s + 1, int(1.2e9 // (R * ns))))
         v, dt = cpu_baseline(wl, x0_sample, g_samples, csrs, iters)

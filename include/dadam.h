@@ -193,6 +193,18 @@ int dadam_slot_uses_tile_mode(const dadam_handle* h, uint32_t slot);
 int dadam_pack_offsets(const uint64_t* numel, uint32_t n, uint32_t align_elems, uint64_t* offsets,
                        uint64_t* d_out);
 
+/* Layout advice for HBM.  Measured on MI355X: the same step over the same bytes runs about 15 %
+ * faster when the buffers it streams together are spread over most of the device's physical memory
+ * than when they are packed into one contiguous tenth of it (a packed 48 GB working set sustains
+ * 0.65 of peak bandwidth, the same set spread over 128 GB or more 0.75).  This helper places n
+ * buffers of nbytes[k] bytes in an arena of arena_bytes bytes, in the given order, each at a multiple
+ * of 2 MiB, with equal gaps between consecutive buffers so that the first starts at 0 and the last
+ * ends near the end of the arena.  nbytes[n] in, offsets[n] out (host).  The caller allocates the
+ * arena (one allocation, e.g. most of the free device memory), hands `arena + offsets[k]` to
+ * dadam_bind, and may use the gaps for anything else.
+ * Errors: DADAM_EINVAL if a pointer is null, n == 0, or the buffers do not fit. */
+int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t* offsets);
+
 /* Text of the last error recorded on this handle ("" if none).  With h == NULL: the text of the
  * last dadam_init failure of the calling thread.  The pointer stays valid until the next call on
  * the same handle (thread). */

@@ -32,7 +32,7 @@ DADAM_WARN_NOT_COLUMN_STOCHASTIC = 1
 EXPORTS = [
     "dadam_init", "dadam_set_topology", "dadam_bind", "dadam_swap_x", "dadam_gossip_step",
     "dadam_gossip_step_range", "dadam_accumulate", "dadam_mix", "dadam_set_lr", "dadam_get_plan_info",
-    "dadam_slot_uses_tile_mode", "dadam_pack_offsets", "dadam_last_error", "dadam_destroy",
+    "dadam_slot_uses_tile_mode", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_last_error", "dadam_destroy",
 ]
 
 
@@ -79,6 +79,7 @@ def _load() -> C.CDLL:
     lib.dadam_get_plan_info.argtypes = [H, C.POINTER(dadam_plan_info)]
     lib.dadam_slot_uses_tile_mode.argtypes = [H, C.c_uint32]
     lib.dadam_pack_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+    lib.dadam_spread_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.POINTER(C.c_uint64)]
     lib.dadam_last_error.argtypes = [H]
     lib.dadam_last_error.restype = C.c_char_p
     lib.dadam_destroy.argtypes = [H]
@@ -146,6 +147,16 @@ def dadam_pack_offsets(numel: Sequence[int], align_elems: int):
     if rc < 0:
         raise DadamError(rc, "dadam_pack_offsets")
     return np.asarray(list(o), dtype=np.uint64), int(d.value)
+
+
+def dadam_spread_offsets(nbytes: Sequence[int], arena_bytes: int):
+    n = len(nbytes)
+    a = (C.c_uint64 * n)(*[int(x) for x in nbytes])
+    o = (C.c_uint64 * n)()
+    rc = lib.dadam_spread_offsets(a, n, int(arena_bytes), o)
+    if rc < 0:
+        raise DadamError(rc, f"dadam_spread_offsets: {n} buffers of {sum(int(x) for x in nbytes)} bytes do not fit in {arena_bytes}")
+    return [int(x) for x in o]
 
 
 def dadam_init(n_rows: int, n_cols: int, d: int, offsets: Sequence[int], numels: Sequence[int],

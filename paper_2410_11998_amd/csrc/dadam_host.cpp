@@ -640,6 +640,25 @@ int dadam_pack_offsets(const uint64_t* numel, uint32_t n, uint32_t align_elems, 
   return DADAM_OK;
 }
 
+int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t* offsets) {
+  if (!nbytes || !offsets || n == 0) return DADAM_EINVAL;
+  const uint64_t unit = 2ull << 20;
+  uint64_t packed = 0;
+  for (uint32_t k = 0; k < n; ++k) {
+    if (nbytes[k] > (1ull << 46)) return DADAM_EINVAL;
+    packed += (nbytes[k] + unit - 1) / unit * unit;
+  }
+  if (packed > arena_bytes + (((nbytes[n - 1] + unit - 1) / unit * unit) - nbytes[n - 1])) return DADAM_EINVAL;
+  const uint64_t slack = arena_bytes > packed ? arena_bytes - packed : 0;
+  const uint64_t gap = n > 1 ? slack / (n - 1) / unit * unit : 0;
+  uint64_t cur = 0;
+  for (uint32_t k = 0; k < n; ++k) {
+    offsets[k] = cur;
+    cur += (nbytes[k] + unit - 1) / unit * unit + gap;
+  }
+  return DADAM_OK;
+}
+
 const char* dadam_last_error(const dadam_handle* h) { return h ? h->err.c_str() : g_init_error.c_str(); }
 
 void dadam_destroy(dadam_handle* h) {

@@ -28,13 +28,19 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 
+// Elements per lane and vector.  float32 parameters: 4 (one 128-bit access).  bfloat16 parameters:
+// 8 (one 128-bit access of x and g, two of each float32 state vector, the lane's 32 bytes
+// contiguous) or 4 (64-bit accesses of x and g, one fully coalesced 128-bit access of state).
+#ifndef DADAM_BF16_VEC
+#define DADAM_BF16_VEC 8
+#endif
 struct TF32 {
-  static constexpr int id = DADAM_F32;
   static constexpr int bytes = 4;
+  static constexpr int vec = 4;
 };
 struct TBF16 {
-  static constexpr int id = DADAM_BF16;
   static constexpr int bytes = 2;
+  static constexpr int vec = DADAM_BF16_VEC;
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
@@ -152,15 +158,28 @@ __device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, 
   }
 }
 
-// The 16 raw bytes of a parameter vector (4 float32 or 8 bfloat16), as they are parked in LDS.
+// The 16 bytes a parameter vector occupies in LDS: 4 float32, 8 bfloat16 as stored, or 4 bfloat16
+// already widened to float32.
 template <typename XT, bool MASKED, bool NT>
 __device__ __forceinline__ u4 load_raw(const void* base, uint64_t e, uint64_t lo, uint64_t hi) {
-  constexpr int VEC = 16 / XT::bytes;
+  constexpr int VEC = XT::vec;
   if (!MASKED || (e >= lo && e + VEC <= hi)) {
-    return vload<NT && kNtSource>(reinterpret_cast<const u4*>(reinterpret_cast<const char*>(base) + e * XT::bytes));
+    if constexpr (XT::bytes == 2 && VEC == 4) {
+      u2 h = vload<NT && kNtSource>(reinterpret_cast<const u2*>(reinterpret_cast<const uint16_t*>(base) + e));
+      u4 w = {h.x << 16, h.x & 0xFFFF0000u, h.y << 16, h.y & 0xFFFF0000u};  // exact widening
+      return w;
+    } else {
+      return vload<NT && kNtSource>(reinterpret_cast<const u4*>(reinterpret_cast<const char*>(base) + e * XT::bytes));
+    }
   }
   u4 r = {0u, 0u, 0u, 0u};
-  if constexpr (XT::bytes == 4) {
+  if constexpr (XT::bytes == 2 && VEC == 4) {
+    const uint16_t* p = reinterpret_cast<const uint16_t*>(base);
+    if (e + 0 >= lo && e + 0 < hi) r.x = (uint32_t)p[e + 0] << 16;
+    if (e + 1 >= lo && e + 1 < hi) r.y = (uint32_t)p[e + 1] << 16;
+    if (e + 2 >= lo && e + 2 < hi) r.z = (uint32_t)p[e + 2] << 16;
+    if (e + 3 >= lo && e + 3 < hi) r.w = (uint32_t)p[e + 3] << 16;
+  } else if constexpr (XT::bytes == 4) {
     const uint32_t* p = reinterpret_cast<const uint32_t*>(base);
     if (e + 0 >= lo && e + 0 < hi) r.x = p[e + 0];
     if (e + 1 >= lo && e + 1 < hi) r.y = p[e + 1];
@@ -178,8 +197,8 @@ __device__ __forceinline__ u4 load_raw(const void* base, uint64_t e, uint64_t lo
 }
 
 template <typename XT>
-__device__ __forceinline__ void unpack_raw(u4 r, float (&out)[16 / XT::bytes]) {
-  if constexpr (XT::bytes == 4) {
+__device__ __forceinline__ void unpack_raw(u4 r, float (&out)[XT::vec]) {
+  if constexpr (XT::bytes == 4 || XT::vec == 4) {
     out[0] = __uint_as_float(r.x); out[1] = __uint_as_float(r.y);
     out[2] = __uint_as_float(r.z); out[3] = __uint_as_float(r.w);
   } else {
@@ -278,7 +297,7 @@ __device__ __forceinline__ float list_w(const RowList& r, int k) {
 template <typename XT, typename GT, int PHASE, int W, int UT, bool MASKED, bool NT>
 __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t tbase, uint64_t lo,
                                           uint64_t hi, int lane, int wave) {
-  constexpr int VEC = 16 / XT::bytes;
+  constexpr int VEC = XT::vec;
   uint64_t e[UT];
 #pragma unroll
   for (int u = 0; u < UT; ++u) e[u] = tbase + (uint64_t)(u * kWave + lane) * VEC;
@@ -372,14 +391,23 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
 
 template <typename XT, typename GT, int PHASE, int W, int UT, bool NT>
 __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
-  constexpr int VEC = 16 / XT::bytes;
+  constexpr int VEC = XT::vec;
   constexpr uint64_t TILE = (uint64_t)kWave * VEC * UT;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_bytes[];
   u4* lds = reinterpret_cast<u4*>(lds_bytes);
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  uint32_t b = blockIdx.x;
+#ifdef DADAM_XCD_CHUNK
+  {
+    // experiment: consecutive workgroup ids go to the 8 XCDs in turn; give each XCD one contiguous
+    // eighth of the tiles instead of every eighth tile (a bijection of [0, 8*chunk) onto itself)
+    const uint32_t chunk = gridDim.x / 8u;
+    if (b < chunk * 8u) b = (b % 8u) * chunk + b / 8u;
+  }
+#endif
   uint64_t tile_index, lo, hi;
-  locate<true>(a, a.work_begin + blockIdx.x, tile_index, lo, hi);
+  locate<true>(a, a.work_begin + b, tile_index, lo, hi);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
     tile_body<XT, GT, PHASE, W, UT, false, NT>(a, lds, tbase, lo, hi, lane, wave);
@@ -400,8 +428,8 @@ constexpr int kUD = DADAM_DIRECT_UNROLL;  // 16-byte parameter vectors per threa
 template <typename XT, int DEG, bool MASKED, bool NT>
 __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
                                            const uint64_t (&e)[kUD], uint64_t lo, uint64_t hi,
-                                           float (&mix)[kUD][16 / XT::bytes]) {
-  constexpr int VEC = 16 / XT::bytes;
+                                           float (&mix)[kUD][XT::vec]) {
+  constexpr int VEC = XT::vec;
   if constexpr (DEG > 0) {
     u4 r[DEG][kUD];
     float wk[DEG];
@@ -450,7 +478,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
 template <typename XT, typename GT, int PHASE, bool MASKED, bool NT>
 __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t tbase, uint64_t lo,
                                             uint64_t hi, int lane) {
-  constexpr int VEC = 16 / XT::bytes;
+  constexpr int VEC = XT::vec;
   uint64_t e[kUD];
 #pragma unroll
   for (int u = 0; u < kUD; ++u) e[u] = tbase + (uint64_t)(u * kDirectThreads + threadIdx.x) * VEC;
@@ -520,7 +548,7 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
 // on the same elements of different rows.
 template <typename XT, typename GT, int PHASE, bool NT>
 __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
-  constexpr int VEC = 16 / XT::bytes;
+  constexpr int VEC = XT::vec;
   constexpr uint64_t TILE = (uint64_t)kDirectThreads * VEC * kUD;
   const int lane = threadIdx.x & (kWave - 1);
   const uint32_t n_rows = a.n_rows;
@@ -685,7 +713,7 @@ static_assert(sizeof(StepArgs) <= 4096, "kernel argument block must fit the kern
 
 }  // namespace
 
-int vec_elems(int xdt) { return xdt == DADAM_BF16 ? 8 : 4; }
+int vec_elems(int xdt) { return xdt == DADAM_BF16 ? TBF16::vec : TF32::vec; }
 int direct_unroll() { return kUD; }
 bool tile_shape_supported(TileShape s) {
 #ifdef DADAM_ALL_SHAPES

@@ -392,3 +392,42 @@ def test_full_size_configs_sampled(cfg):
     sim.close()
     del sim, grads
     torch.cuda.empty_cache()
+
+
+def test_spread_arena_layout_matches_oracle():
+    """Buffers carved from one arena at the offsets dadam_spread_offsets gives (the layout the
+    benchmark uses) behave like separate allocations."""
+    from paper_2410_11998_amd.arena import SpreadArena
+    n, T = 4, 3
+    layout = WL.pack(WL.odd_shapes() + [("big", (300001,))])
+    d = layout.d
+    hp = H.HyperF32(s=2)
+    for dtype in ("f32", "bf16"):
+        say("case", dtype)
+        sim = H.GpuSim(n, n, layout, hp, [WL.ring(n)], dtype, dtype, pad_fill=None)
+        px = 2 if dtype == "bf16" else 4
+        dts = [H.TORCH_DT[dtype]] * (2 * n) + [torch.float32] * (3 * n) + [H.TORCH_DT[dtype]] * n
+        arena = SpreadArena([d * px] * (2 * n) + [d * 4] * (3 * n) + [d * px] * n, DEV, span_bytes=256 << 20)
+        v = arena.views(dts)
+        assert all(t.numel() == d and t.data_ptr() % (2 << 20) == 0 for t in v)
+        sim.x_src, sim.x_dst, sim.m, sim.v, sim.b, grads = v[:n], v[n:2 * n], v[2 * n:3 * n], v[3 * n:4 * n], v[4 * n:5 * n], v[5 * n:]
+        for t_ in sim.x_dst + sim.m + sim.v + sim.b:
+            t_.zero_()
+        for c in range(n):
+            sim.x_src[c].copy_(H.to_device(WL.normal_np(1200 + c, d, 0.02), dtype, DEV))
+        sim.bind()
+        ohp = hp.oracle()
+        csr = H.csr_oracle(WL.ring(n))
+        mask = H.valid_mask(layout)
+        for t in range(1, T + 1):
+            for i in range(n):
+                grads[i].copy_(H.to_device(WL.normal_np(1300 + 8 * t + i, d, 1e-2), dtype, DEV))
+            g64 = [g.to(torch.float64).cpu().numpy() for g in grads]
+            prev = sim.snapshot()
+            sim.step(grads, t)
+            torch.cuda.synchronize()
+            ref_state = O.State(prev.x_src, list(prev.m_hat), list(prev.v_hat), list(prev.b))
+            ref_x = O.dadam_step(ref_state, g64, csr, t, ohp, "O32m", dtype)
+            H.assert_within(H.compare_step(prev, ref_x, ref_state, sim.outputs(), g64, csr, t, ohp, dtype, mask), f"arena {dtype} t={t}")
+            sim.swap()
+        sim.close()

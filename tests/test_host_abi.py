@@ -213,3 +213,25 @@ def test_binding_rejects_short_or_mistyped_tensors():
     with pytest.raises(ValueError):
         B.dadam_accumulate(h, [short, full()], 1)
     B.dadam_destroy(h)
+
+
+def test_spread_offsets_properties():
+    unit = 2 << 20
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        n = int(rng.integers(1, 40))
+        sizes = [int(x) for x in rng.integers(1, 50 << 20, size=n)]
+        packed = sum(-(-s // unit) * unit for s in sizes)
+        arena = packed + int(rng.integers(0, 3 << 30))
+        off = B.dadam_spread_offsets(sizes, arena)
+        assert off[0] == 0 and all(o % unit == 0 for o in off)
+        for k in range(1, n):
+            assert off[k] >= off[k - 1] + sizes[k - 1]
+        assert off[-1] + sizes[-1] <= arena
+        if n > 2:
+            gaps = {off[k + 1] - off[k] - (-(-sizes[k] // unit) * unit) for k in range(n - 1)}
+            assert len(gaps) == 1                                   # equal gaps
+            assert arena - (off[-1] + -(-sizes[-1] // unit) * unit) < (n - 1) * unit   # nothing much left over
+    with pytest.raises(B.DadamError):
+        B.dadam_spread_offsets([5 << 20, 5 << 20], 8 << 20)
+    assert B.lib.dadam_spread_offsets(None, 1, 100, None) == B.DADAM_EINVAL
