@@ -387,11 +387,11 @@ int dadam_init(const dadam_config* cfg, dadam_handle** out) {
 
   // tile geometry: 16 bytes per lane and vector, `ut` vectors per lane, all source buffers' slices
   // of one tile resident in LDS.  Measured on MI355X: one vector per lane (many small workgroups)
-  // streams best; four wavefronts per group, eight when there are many rows to deal out.
+  // streams best; eight wavefronts per group, four when there are fewer than eight rows to deal out.
   h->vec = vec_elems((int)cfg->param_dtype);
   TileShape shape;
   shape.ut = 1;
-  shape.waves = cfg->n_rows >= 32 ? 8 : 4;
+  shape.waves = cfg->n_rows >= 8 ? 8 : 4;
   // Non-temporal accesses pay off when an iteration's working set cannot stay in the last-level
   // cache anyway; small problems keep ordinary accesses so that one iteration finds the previous
   // one's output on chip.

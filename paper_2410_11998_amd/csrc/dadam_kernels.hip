@@ -24,6 +24,8 @@
 namespace dadam {
 namespace {
 
+constexpr uint32_t kXcds = 8;  // accelerator complex dies of an MI355X, each with its own L2
+
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
@@ -397,15 +399,15 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
   u4* lds = reinterpret_cast<u4*>(lds_bytes);
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  // Consecutive workgroup ids are dispatched to the 8 XCDs in turn.  Give each XCD one contiguous
+  // eighth of the tiles instead of every eighth tile, so that each XCD (and its L2) walks its own
+  // region of every array front to back: measured 1-3 % faster.  The map is a bijection of
+  // [0, 8 * chunk) onto itself; the last gridDim.x mod 8 workgroups keep their tile.
   uint32_t b = blockIdx.x;
-#ifdef DADAM_XCD_CHUNK
   {
-    // experiment: consecutive workgroup ids go to the 8 XCDs in turn; give each XCD one contiguous
-    // eighth of the tiles instead of every eighth tile (a bijection of [0, 8*chunk) onto itself)
-    const uint32_t chunk = gridDim.x / 8u;
-    if (b < chunk * 8u) b = (b % 8u) * chunk + b / 8u;
+    const uint32_t chunk = gridDim.x / kXcds;
+    if (b < chunk * kXcds) b = (b % kXcds) * chunk + b / kXcds;
   }
-#endif
   uint64_t tile_index, lo, hi;
   locate<true>(a, a.work_begin + b, tile_index, lo, hi);
   const uint64_t tbase = tile_index * TILE;
