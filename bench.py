@@ -238,10 +238,10 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32" if wl.param_dtype == "f32" else "bf16 params+grads, f32 moments and arithmetic",
+        "dtype": "f32",     # the arithmetic type; parameters and gradients are stored as config.param_dtype / grad_dtype
         "data": "synthetic",
         "config": {
-            "workload": wl.name, "n_rows": R, "n_sources": C, "d": d, "tensors": len(layout.names), "topology": wl.topology,
+            "workload": wl.name, "param_dtype": wl.param_dtype, "grad_dtype": wl.grad_dtype, "state_dtype": "f32", "n_rows": R, "n_sources": C, "d": d, "tensors": len(layout.names), "topology": wl.topology,
             "accum_s": wl.s, "kernel": ("k_tile" if tile_mode else "k_direct"), "x_buffers": "in-place" if inplace else "ping-pong",
             "hbm_layout": args.layout if span_gib is None else f"spread over {span_gib:.0f} GiB",
             "grad_pool": len(pool),
