@@ -65,6 +65,22 @@ def algorithmic_bytes_per_replica_param(wl, phase: str) -> float:
     raise ValueError(phase)
 
 
+def path_bytes_per_replica_param(wl, phase: str, path: str) -> float:
+    """Bytes the kernels of a non-default --path have to move per updated element (for the fused and
+    the bucketed path this is the algorithmic figure)."""
+    px = 2 if wl.param_dtype == "bf16" else 4
+    pg = 2 if wl.grad_dtype == "bf16" else 4
+    src = px * wl.n_cols / wl.n_rows
+    if path in ("fused", "buckets"):
+        return algorithmic_bytes_per_replica_param(wl, phase)
+    acc = {"alg1": pg + 8 + 8, "plain": pg + 4 + 4, "loopstart": pg + 4, "fold": pg + 4 + 4 + 8 + 8}[phase]
+    if path == "accumulate":
+        return acc
+    if path == "mix":
+        return src + px
+    return (src + px + pg + 8) + acc          # unfused: update-only pass, then the accumulate pass
+
+
 def cpu_baseline(wl, x0_sample, grad_samples, csrs, iters: int):
     """The CPU oracle as it stands, timed on this host on a bounded sample of the workload."""
     import numpy as np
@@ -93,6 +109,11 @@ def main() -> int:
     ap.add_argument("--mode", choices=["auto", "tile", "direct"], default="auto")
     ap.add_argument("--inplace", action="store_true", help="update parameters in place instead of ping-pong")
     ap.add_argument("--pool", type=int, default=2, help="number of pre-generated gradient sets cycled through")
+    ap.add_argument("--path", choices=["fused", "unfused", "mix", "accumulate", "buckets"], default="fused",
+                    help="fused: one dadam_gossip_step per iteration (the benchmark); unfused: dadam_gossip_step without "
+                         "accumulation followed by dadam_accumulate; mix: dadam_mix only; accumulate: dadam_accumulate only; "
+                         "buckets: the fused step issued tensor range by tensor range (--bucket-mb)")
+    ap.add_argument("--bucket-mb", type=float, default=25.0, help="target bucket size for --path buckets")
     ap.add_argument("--layout", choices=["spread", "packed"], default="spread",
                     help="spread: one arena over most of the free HBM, buffers at equal distances (faster, see "
                          "paper_2410_11998_amd/arena.py); packed: one ordinary allocation per buffer")
@@ -188,9 +209,35 @@ def main() -> int:
 
     stream = B.current_stream()
 
+    # tensor ranges of about --bucket-mb of parameters each, in layout order (the granularity at which
+    # the paper's implementation updates and communicates)
+    buckets = []
+    if args.path == "buckets":
+        per = int(args.bucket_mb * 1e6 / (2 if wl.param_dtype == "bf16" else 4))
+        start, cur = 0, 0
+        for k, n_k in enumerate(layout.numels):
+            cur += int(n_k)
+            if cur >= per or k == len(layout.numels) - 1:
+                buckets.append((start, k + 1))
+                start, cur = k + 1, 0
+    mode_flags = flags & ~B.DADAM_FUSE_ACCUM
+
     def one_step(t: int):
-        B.dadam_gossip_step(h, wl.slot_of_step(t), pool[t % len(pool)], t, flags, stream)
-        if not inplace:
+        g = pool[t % len(pool)]
+        slot = wl.slot_of_step(t)
+        if args.path == "fused":
+            B.dadam_gossip_step(h, slot, g, t, flags, stream)
+        elif args.path == "unfused":
+            B.dadam_gossip_step(h, slot, g, t, mode_flags, stream)
+            B.dadam_accumulate(h, g, t, stream)
+        elif args.path == "mix":
+            B.dadam_mix(h, slot, mode_flags, stream)
+        elif args.path == "accumulate":
+            B.dadam_accumulate(h, g, t, stream)
+        else:
+            for tb, te in buckets:
+                B.dadam_gossip_step_range(h, slot, g, t, flags, tb, te, stream)
+        if not inplace and args.path != "accumulate":
             B.dadam_swap_x(h)
 
     t = 0
@@ -217,11 +264,11 @@ def main() -> int:
     avg_kernel_s = sum(kernel_ms) / K / 1e3
     replica_params = R * d
     value = replica_params * K / elapsed
-    bytes_per_launch = replica_params * sum(algorithmic_bytes_per_replica_param(wl, p) for p in phases) / K
+    bytes_per_launch = replica_params * sum(path_bytes_per_replica_param(wl, p, args.path) for p in phases) / K
     achieved = bytes_per_launch / avg_kernel_s
     traffic = None
     table = MEASURED_TRAFFIC_BYTES.get(wl.name)
-    if table is not None and args.mode == "auto" and all(p in table for p in phases):
+    if table is not None and args.mode == "auto" and args.path == "fused" and all(p in table for p in phases):
         traffic = sum(table[p] for p in phases) / K
     by_phase = {}
     for p, ms in zip(phases, kernel_ms):
@@ -242,7 +289,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": wl.name, "param_dtype": wl.param_dtype, "grad_dtype": wl.grad_dtype, "state_dtype": "f32", "n_rows": R, "n_sources": C, "d": d, "tensors": len(layout.names), "topology": wl.topology,
-            "accum_s": wl.s, "kernel": ("k_tile" if tile_mode else "k_direct"), "x_buffers": "in-place" if inplace else "ping-pong",
+            "accum_s": wl.s, "kernel": ("k_tile" if tile_mode else "k_direct"), "path": args.path,
+            "launches_per_step": (len(buckets) if args.path == "buckets" else 2 if args.path == "unfused" else 1), "x_buffers": "in-place" if inplace else "ping-pong",
             "hbm_layout": args.layout if span_gib is None else f"spread over {span_gib:.0f} GiB",
             "grad_pool": len(pool),
         },

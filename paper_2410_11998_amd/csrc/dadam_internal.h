@@ -18,11 +18,14 @@ constexpr int kDirectThreads = 256;  // workgroup of the direct and accumulate k
 // buffers are; a tile that sticks out of [lo, hi) is clipped element by element.
 struct Segment {
   uint64_t lo, hi;
-  uint64_t first_tile_t;  // index of the first tile-mode tile that intersects the segment
-  uint64_t first_tile_d;  // same for direct-mode tiles
-  uint32_t work0_t;       // number of tile-mode work items in earlier segments
-  uint32_t work0_d;       // same for direct mode (per row)
+  uint64_t first_tile[3];  // per Grid: index of the first tile of that grid that intersects the segment
+  uint32_t work0[3];       // per Grid: number of work items (tiles; per row in direct mode) in earlier segments
+  uint32_t pad_;
 };
+
+// Which of the three tile grids a launch walks: the fused step's tiles, the direct/accumulate
+// kernels' tiles, or the wider tiles of the mixing-only launch.
+enum Grid : uint32_t { kGridTile = 0, kGridDirect = 1, kGridMix = 2 };
 
 // Scalars of one iteration, computed on the host in double and rounded once.
 struct Scalars {
@@ -58,6 +61,7 @@ struct StepArgs {
   const Segment* seg;  // device
   uint32_t n_seg;
   uint32_t n_rows, n_cols;
+  uint32_t grid;        // Grid: which tile numbering work items refer to
   uint32_t work_begin;  // first work item (in tiles) of this launch
   uint64_t clip_lo, clip_hi;  // element range of this launch (whole layout or a tensor range)
   Scalars s;

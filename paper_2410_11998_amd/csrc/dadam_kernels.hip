@@ -247,24 +247,25 @@ struct Needs {
   static constexpr bool moments_out = PHASE == kFold || PHASE == kAlg1;
 };
 
-// Which segment does work item `work` belong to, and which tile of the fixed grid is it?
-template <bool TILE_MODE>
+// Which segment does work item `work` belong to, and which tile of the launch's grid is it?
+// (Fields are read one by one through the pointer: copying the struct would put it in scratch.)
 __device__ __forceinline__ void locate(const StepArgs& a, uint32_t work, uint64_t& tile_index,
                                        uint64_t& lo, uint64_t& hi) {
+  const uint32_t grid = a.grid;
+  const Segment* seg = a.seg;
   uint32_t s = 0;
   if (a.n_seg > 1) {
     uint32_t l = 0, r = a.n_seg;
     while (r - l > 1) {
       uint32_t mid = (l + r) >> 1;
-      uint32_t w0 = TILE_MODE ? a.seg[mid].work0_t : a.seg[mid].work0_d;
-      if (w0 <= work) l = mid; else r = mid;
+      if (seg[mid].work0[grid] <= work) l = mid; else r = mid;
     }
     s = l;
   }
-  const Segment sg = a.seg[s];
-  tile_index = (TILE_MODE ? sg.first_tile_t : sg.first_tile_d) + (work - (TILE_MODE ? sg.work0_t : sg.work0_d));
-  lo = sg.lo > a.clip_lo ? sg.lo : a.clip_lo;
-  hi = sg.hi < a.clip_hi ? sg.hi : a.clip_hi;
+  tile_index = seg[s].first_tile[grid] + (work - seg[s].work0[grid]);
+  const uint64_t slo = seg[s].lo, shi = seg[s].hi;
+  lo = slo > a.clip_lo ? slo : a.clip_lo;
+  hi = shi < a.clip_hi ? shi : a.clip_hi;
 }
 
 // Row i's slice of the neighbour list, one entry per lane, and its bounds as wave-uniform values.
@@ -409,7 +410,7 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
     if (b < chunk * kXcds) b = (b % kXcds) * chunk + b / kXcds;
   }
   uint64_t tile_index, lo, hi;
-  locate<true>(a, a.work_begin + b, tile_index, lo, hi);
+  locate(a, a.work_begin + b, tile_index, lo, hi);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
     tile_body<XT, GT, PHASE, W, UT, false, NT>(a, lds, tbase, lo, hi, lane, wave);
@@ -557,7 +558,7 @@ __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
   const uint32_t t = blockIdx.x / n_rows;
   const int row = (int)(blockIdx.x - t * n_rows);
   uint64_t tile_index, lo, hi;
-  locate<false>(a, a.work_begin + t, tile_index, lo, hi);
+  locate(a, a.work_begin + t, tile_index, lo, hi);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
     direct_body<XT, GT, PHASE, false, NT>(a, row, tbase, lo, hi, lane);
@@ -632,7 +633,7 @@ __global__ __launch_bounds__(kDirectThreads) void k_acc(const StepArgs a) {
   const uint32_t t = blockIdx.x / n_rows;
   const int row = (int)(blockIdx.x - t * n_rows);
   uint64_t tile_index, lo, hi;
-  locate<false>(a, a.work_begin + t, tile_index, lo, hi);
+  locate(a, a.work_begin + t, tile_index, lo, hi);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
     acc_body<GT, VEC, PHASE, false, NT>(a, row, tbase, lo, hi);

@@ -163,6 +163,42 @@ def one_peer_slots(n: int) -> int:
     return max(k, 1)
 
 
+def one_peer_ring(n: int, slot: int):
+    """One-peer ring (appendix figure of the same name): two alternating perfect matchings of
+    the ring.  Even slots pair (0,1), (2,3), ...; odd slots pair (1,2), (3,4), ..., (n-1,0).
+    Weights 1/2."""
+    assert n % 2 == 0
+    shift = slot % 2
+    neigh = [None] * n
+    for a in range(shift, n + shift, 2):
+        i, j = a % n, (a + 1) % n
+        neigh[i] = [i, j]
+        neigh[j] = [j, i]
+    return _uniform_rows(neigh)
+
+
+def aer_groups(per_node: int, phase: int):
+    """Alternating Exponential Ring for four nodes (appendix figure of that name).  Every drawn
+    loop is an All-Reduce (a plain average) over its members.  In each of the four phases one pair
+    of nodes forms a common loop and the other two nodes average internally; the pairs are, in
+    order, nodes (2,3), (0,1), (0,2), (1,3) - ring hops 1, 1, 2, 2."""
+    pair = [(2, 3), (0, 1), (0, 2), (1, 3)][phase % 4]
+    node = lambda a: list(range(a * per_node, (a + 1) * per_node))
+    groups = [node(pair[0]) + node(pair[1])]
+    groups += [node(a) for a in range(4) if a not in pair]
+    return groups
+
+
+def aer(per_node: int, phase: int):
+    """Rows of the mixing matrix of one AER phase: uniform weights over the row's loop."""
+    n = 4 * per_node
+    neigh = [None] * n
+    for grp in aer_groups(per_node, phase):
+        for i in grp:
+            neigh[i] = [i] + [j for j in grp if j != i]
+    return _uniform_rows(neigh)
+
+
 def complete(n: int):
     return _uniform_rows([list(range(n)) for _ in range(n)])
 

@@ -431,3 +431,17 @@ def test_spread_arena_layout_matches_oracle():
             H.assert_within(H.compare_step(prev, ref_x, ref_state, sim.outputs(), g64, csr, t, ohp, dtype, mask), f"arena {dtype} t={t}")
             sim.swap()
         sim.close()
+
+
+def test_time_varying_loops_alternating_exponential_ring():
+    """16 replicas cycling through the four AER phases (rows of degree 4 and 8) and, on a second
+    handle, through the two one-peer-ring matchings."""
+    n = 16
+    layout = WL.pack([("a", (70001,)), ("b", (333,))])
+    hp = H.HyperF32(s=2)
+    aer = [WL.aer(4, ph) for ph in range(4)]
+    w = H.run_parity("aer", n, n, layout, hp, aer, lambda t: (t - 1) % 4, 6, seed=55, grad_std=1e-2)
+    say("aer worst error / tolerance:", w)
+    opr = [WL.one_peer_ring(n, k) for k in range(2)]
+    w = H.run_parity("one-peer-ring", n, n, layout, hp, opr, lambda t: (t - 1) % 2, 5, seed=56, grad_std=1e-2)
+    say("one-peer ring worst error / tolerance:", w)

@@ -235,3 +235,22 @@ def test_spread_offsets_properties():
     with pytest.raises(B.DadamError):
         B.dadam_spread_offsets([5 << 20, 5 << 20], 8 << 20)
     assert B.lib.dadam_spread_offsets(None, 1, 100, None) == B.DADAM_EINVAL
+
+
+def test_kernels_use_no_scratch_memory(tmp_path):
+    """Every kernel must keep its state in registers: a struct copied to private memory once cost
+    8 % of the step's bandwidth without any test noticing.  Compiles the device code with the
+    compiler's resource-usage remarks and checks the scratch size of every kernel."""
+    import shutil
+    import subprocess
+    from paper_2410_11998_amd import build as bld
+    if shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"):
+        pytest.skip("hipcc not available")
+    flags = [f for f in bld.FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [bld.hipcc()] + flags + ["--cuda-device-only", "-c", os.path.join(bld.CSRC, "dadam_kernels.hip"),
+                                  "-o", str(tmp_path / "k.o"), "-Rpass-analysis=kernel-resource-usage"]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stderr[-2000:]
+    sizes = [int(x) for x in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", r.stderr)]
+    assert len(sizes) > 100, "no resource remarks found"
+    assert max(sizes) == 0, f"{sum(1 for s in sizes if s)} kernels spill or copy to scratch"

@@ -497,3 +497,45 @@ def test_mixing_pins_catch_planted_mistakes(monkeypatch):
                 except AssertionError:
                     caught += 1
             assert caught >= 1, f"planted mistake {fn.__name__} went unnoticed"
+
+
+# ---------------------------------------------------------------------------------------
+# the other topologies the paper draws
+# ---------------------------------------------------------------------------------------
+
+def test_one_peer_ring_matchings():
+    n = 16
+    a, b = csr_of(WL.one_peer_ring(n, 0)).dense(n), csr_of(WL.one_peer_ring(n, 1)).dense(n)
+    for W in (a, b):
+        assert np.array_equal(W, W.T) and np.all(W.sum(0) == 1) and np.all(W.sum(1) == 1)
+        assert np.all((W == 0) | (W == 0.5))
+    assert a[0, 1] == 0.5 and a[14, 15] == 0.5 and a[1, 2] == 0       # (0,1), ..., (14,15)
+    assert b[1, 2] == 0.5 and b[15, 0] == 0.5 and b[0, 1] == 0        # (1,2), ..., (15,0)
+    # the union of the two matchings is the ring: every replica reaches every other one
+    reach = np.linalg.matrix_power(((a + b) > 0).astype(float), n)
+    assert np.all(reach > 0)
+
+
+def test_alternating_exponential_ring_phases_and_exact_averaging():
+    """Loops as drawn for 16 workers on four nodes; the four phases in a row average all
+    replicas exactly (each phase is a group average; pairs (2,3), (0,1), (0,2), (1,3))."""
+    m, n = 4, 16
+    want_big = [set(range(8, 16)), set(range(0, 8)), {0, 1, 2, 3, 8, 9, 10, 11}, {4, 5, 6, 7, 12, 13, 14, 15}]
+    prod = np.eye(n)
+    rng = np.random.default_rng(17)
+    x0 = [rng.standard_normal(6) for _ in range(n)]
+    xs = [x.copy() for x in x0]
+    for ph in range(4):
+        groups = WL.aer_groups(m, ph)
+        assert set(groups[0]) == want_big[ph] and sorted(len(g) for g in groups) == [4, 4, 8]
+        assert sorted(i for g in groups for i in g) == list(range(n))
+        csr = csr_of(WL.aer(m, ph), w64=True)
+        W = csr.dense(n)
+        assert np.allclose(W, W.T) and np.allclose(W.sum(0), 1) and np.allclose(W.sum(1), 1)
+        for g in groups:
+            for i in g:
+                assert np.allclose(W[i, g], 1.0 / len(g)) and np.isclose(W[i].sum(), 1.0)
+        prod = W @ prod
+        xs = O.mix_only(xs, csr, mode="O64")
+    np.testing.assert_allclose(prod, np.full((n, n), 1.0 / n), atol=1e-15)
+    np.testing.assert_allclose(np.stack(xs), np.tile(np.mean(x0, axis=0), (n, 1)), atol=1e-14)
