@@ -41,6 +41,9 @@ Readings of the paper taken here (each is also listed in the design document):
 * all rows are updated from the previous iterate at once (Jacobi), which is what
   "x_j^(t-1)" in eq. (2) says.
 
+* the AdamW-style variant (weight_decay argument) is not written out in the paper; the
+  reading taken is stated at dadam_step.
+
 Pins: tests/test_oracle_pins.py checks every function below against closed forms,
 library routines (torch.optim.Adam), brute force with a dense mixing matrix, and
 the invariants the paper states.  No function here is "parity unpinned".
@@ -207,13 +210,23 @@ class State:
 
 def dadam_step(state: State, grads: Sequence[np.ndarray], csr: Csr, t: int, hp: Hyper,
                mode: str = "O32m", param_dtype: str = "f32",
-               do_update: bool = True, do_accumulate: bool = True) -> List[np.ndarray]:
+               do_update: bool = True, do_accumulate: bool = True,
+               weight_decay=None) -> List[np.ndarray]:
     """Iteration t (1-based) of Algorithm 3 for every row; returns x^(t) per row and
     updates m_hat, v_hat, b in ``state`` (x_src is left alone: all rows read the
     previous iterate, the caller decides what the next iteration's sources are).
 
     do_update=False skips lines 6-8 (returns None), do_accumulate=False skips lines
     9-13: the two halves of the unfused call sequence.
+
+    weight_decay (None, a number, or an array with one entry per coordinate) selects the
+    AdamW-style variant the appendix mentions without writing it out.  Reading taken:
+    decoupled weight decay is part of the search direction of eq. (2), which by the
+    paper's construction depends on worker i's own quantities only, so the direction
+    becomes  u_i + lambda * x_i^(t-1)  with x_i^(t-1) the worker's OWN previous model
+    (source buffer i), applied at every model update:
+        x_i^(t) = sum_j w_ij x_j^(t-1) - lr * (u_i + lambda * x_i^(t-1)).
+    With W = I and s = 1 this is the library's AdamW.
     """
     assert t >= 1 and hp.s >= 1
     th = t_hat(t, hp.s)
@@ -225,6 +238,8 @@ def dadam_step(state: State, grads: Sequence[np.ndarray], csr: Csr, t: int, hp: 
             g = np.asarray(grads[i], dtype=np.float64)
             m, v = temporary_moments(state.m_hat[i], state.v_hat[i], g, hp)
             u = search_direction(m, v, th, hp)
+            if weight_decay is not None:
+                u = u + np.asarray(weight_decay, dtype=np.float64) * np.asarray(state.x_src[i], dtype=np.float64)
             x_new.append(_store_x(mixes[i] - hp.lr * u, mode, param_dtype))
     if do_accumulate:
         for i in range(csr.n_rows):
@@ -244,7 +259,7 @@ def mix_only(x_src: Sequence[np.ndarray], csr: Csr, mode: str = "O32m",
 
 def run_simulation(x0: Sequence[np.ndarray], grads_of_t, csr_of_t, T: int, hp: Hyper,
                    mode: str = "O32m", param_dtype: str = "f32", t_start: int = 1,
-                   state: Optional[State] = None) -> State:
+                   state: Optional[State] = None, weight_decay=None) -> State:
     """All n replicas of a decentralized run held side by side (rows = sources):
     iterations t_start..T.  grads_of_t(t) -> list of n gradient arrays,
     csr_of_t(t) -> Csr for that iteration (time-varying topologies)."""
@@ -253,7 +268,7 @@ def run_simulation(x0: Sequence[np.ndarray], grads_of_t, csr_of_t, T: int, hp: H
         z = lambda: [np.zeros_like(np.asarray(x0[0], dtype=np.float64)) for _ in range(n)]
         state = State([np.asarray(x, dtype=np.float64).copy() for x in x0], z(), z(), z())
     for t in range(t_start, T + 1):
-        x_new = dadam_step(state, grads_of_t(t), csr_of_t(t), t, hp, mode, param_dtype)
+        x_new = dadam_step(state, grads_of_t(t), csr_of_t(t), t, hp, mode, param_dtype, weight_decay=weight_decay)
         state.x_src = x_new
     return state
 
@@ -282,7 +297,7 @@ def allreduce_adam(x0: np.ndarray, grads_of_t, n: int, T: int, hp: Hyper) -> np.
 # error scale used by the parity tests (not part of the method)
 # --------------------------------------------------------------------------------------
 
-def magnitude_scale(state: State, grads: Sequence[np.ndarray], csr: Csr, t: int, hp: Hyper):
+def magnitude_scale(state: State, grads: Sequence[np.ndarray], csr: Csr, t: int, hp: Hyper, weight_decay=None):
     """Per row, the sum of the magnitudes of the terms that make up x^(t):
     sum_j |w_ij x_j| + lr * (beta1 |m_hat| + (1-beta1)|g|) / c1 / (sqrt(v/c2) + eps).
     A float32 evaluation of the iteration is off by a small multiple of 2^-24 times
@@ -299,5 +314,8 @@ def magnitude_scale(state: State, grads: Sequence[np.ndarray], csr: Csr, t: int,
         g = np.asarray(grads[i], dtype=np.float64)
         v = hp.beta2 * state.v_hat[i] + (1.0 - hp.beta2) * g * g
         mag_m = hp.beta1 * np.abs(state.m_hat[i]) + (1.0 - hp.beta1) * np.abs(g)
-        out.append(acc + hp.lr * (mag_m / c1) / (np.sqrt(v / c2) + hp.eps))
+        scale = acc + hp.lr * (mag_m / c1) / (np.sqrt(v / c2) + hp.eps)
+        if weight_decay is not None:
+            scale = scale + hp.lr * np.abs(np.asarray(weight_decay, dtype=np.float64) * state.x_src[i])
+        out.append(scale)
     return out

@@ -539,3 +539,62 @@ def test_alternating_exponential_ring_phases_and_exact_averaging():
         xs = O.mix_only(xs, csr, mode="O64")
     np.testing.assert_allclose(prod, np.full((n, n), 1.0 / n), atol=1e-15)
     np.testing.assert_allclose(np.stack(xs), np.tile(np.mean(x0, axis=0), (n, 1)), atol=1e-14)
+
+
+# ---------------------------------------------------------------------------------------
+# decoupled weight decay (the AdamW-style variant)
+# ---------------------------------------------------------------------------------------
+
+def test_weight_decay_identity_s1_equals_torch_adamw():
+    n, d, T, lam = 2, 101, 8, 3e-2
+    hp = O.Hyper(lr=2e-3, s=1)
+    rng = np.random.default_rng(71)
+    x0 = [rng.standard_normal(d) for _ in range(n)]
+    G = rand_grads(72, n, d, T)
+    st = O.run_simulation(x0, lambda t: G[t], lambda t: csr_of(WL.identity(n)), T, hp, mode="O64", weight_decay=lam)
+    for i in range(n):
+        p = torch.tensor(x0[i], dtype=torch.float64, requires_grad=True)
+        opt = torch.optim.AdamW([p], lr=hp.lr, betas=(hp.beta1, hp.beta2), eps=hp.eps, weight_decay=lam)
+        for t in range(1, T + 1):
+            p.grad = torch.tensor(G[t][i], dtype=torch.float64)
+            opt.step()
+        np.testing.assert_allclose(st.x_src[i], p.detach().numpy(), rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("s", [1, 4])
+def test_weight_decay_constant_gradient_closed_form(s):
+    """W = I, g = c: x_t = q^t x_0 - lr * c/(|c|+eps) * (1 - q^t)/(1 - q) with q = 1 - lr*lambda,
+    for every accumulation length (the decay acts at every model update)."""
+    hp = O.Hyper(lr=1e-2, eps=1e-3, s=s)
+    lam = 0.5
+    c = np.array([0.5, -0.25, 2.0, 0.0])
+    x0 = [np.array([1.0, -2.0, 0.5, 3.0])]
+    st = zeros_state(x0)
+    q = 1.0 - hp.lr * lam
+    for t in range(1, 10):
+        st.x_src = O.dadam_step(st, [c], csr_of(WL.identity(1)), t, hp, mode="O64", weight_decay=lam)
+        want = q ** t * x0[0] - hp.lr * c / (np.abs(c) + hp.eps) * (1 - q ** t) / (1 - q)
+        np.testing.assert_allclose(st.x_src[0], want, rtol=1e-12, atol=1e-15)
+
+
+def test_weight_decay_acts_on_own_previous_model_per_coordinate():
+    """Ring, different replicas: x_new - mix + lr*u = -lr * lambda * x_own, coordinate by coordinate,
+    with lambda zero on some coordinates (the recipe that exempts normalisation parameters)."""
+    n, d = 4, 12
+    hp = O.Hyper(lr=1e-2, s=2)
+    rng = np.random.default_rng(73)
+    x0 = [rng.standard_normal(d) for _ in range(n)]
+    lam = np.where(np.arange(d) % 3 == 0, 0.0, 0.1)
+    G = rand_grads(74, n, d, 3, std=1.0)
+    csr = csr_of(WL.ring(n), w64=True)
+    st = zeros_state(x0)
+    for t in (1, 2, 3):
+        prev = [x.copy() for x in st.x_src]
+        mixes = O.mix_rows(prev, csr)
+        U = [O.search_direction(*O.temporary_moments(st.m_hat[i], st.v_hat[i], G[t][i], hp), O.t_hat(t, hp.s), hp) for i in range(n)]
+        st.x_src = O.dadam_step(st, G[t], csr, t, hp, mode="O64", weight_decay=lam)
+        for i in range(n):
+            np.testing.assert_allclose(st.x_src[i] - mixes[i] + hp.lr * U[i], -hp.lr * lam * prev[i], atol=1e-15)
+        # averaged over workers the decay pulls the mean model (doubly stochastic W)
+        np.testing.assert_allclose(np.mean(st.x_src, axis=0),
+                                   np.mean(prev, axis=0) - hp.lr * np.mean([U[i] + lam * prev[i] for i in range(n)], axis=0), atol=1e-14)
