@@ -15,6 +15,12 @@
  *                       v_hat_i[e] = beta_vhat * v_hat_i[e] + (1 - beta_vhat) * b_i[e]^2
  *                       b_i[e] = 0
  *
+ * A tensor with weight_decay lambda > 0 uses the AdamW-style variant the appendix mentions without
+ * writing it out; the reading taken is decoupled decay of the replica's OWN previous parameters
+ * inside the search direction (which, as the paper stresses, depends on the worker's own quantities
+ * only):   x_dst_i[e] = mixing term - lr * (direction + lambda * x_src[i][e]),  at every iteration.
+ * Source buffer i must then be row i's own previous parameters (n_rows <= n_cols).
+ *
  * k runs over row i of a CSR neighbour list (row_ptr, col, w); the replica itself is an ordinary
  * entry of its row.  Every row reads the previous iterate x^(t-1) (the sources), never a value
  * written by the same call.  m and v are temporaries and are not stored.
@@ -73,8 +79,9 @@ typedef struct dadam_handle dadam_handle; /* opaque, owned by the library */
 
 /* One tensor of the packed layout: elements [offset_elems, offset_elems + numel) of every
  * per-replica buffer.  Tensors must be listed in increasing offset order and must not overlap;
- * elements between tensors (padding) are never read or written.  weight_decay and flags are
- * reserved for per-tensor hyper-parameters and must be 0. */
+ * elements between tensors (padding) are never read or written.  weight_decay >= 0 is the decoupled
+ * weight decay of this tensor (0 = plain Adam; e.g. 3e-5 on all but the normalisation parameters in
+ * the paper's ResNet-50 recipe).  flags is reserved and must be 0. */
 typedef struct {
   uint64_t offset_elems;
   uint64_t numel;
@@ -127,7 +134,8 @@ typedef struct {
 /* Create a handle.  Validates the configuration, builds the segment table from the tensor list
  * and (unless device == DADAM_DEVICE_NONE) uploads it.  *out is set only on success.
  * Errors: DADAM_EINVAL (null, n_rows/n_cols 0 or above DADAM_MAX_ROWS, d == 0, s == 0, dtype,
- * tensors unordered / overlapping / beyond d / non-zero reserved fields, hyper-parameters out of
+ * tensors unordered / overlapping / beyond d / negative weight decay / non-zero flags / weight decay with
+ * n_rows > n_cols, hyper-parameters out of
  * range: lr finite, 0 <= beta < 1, eps >= 0), DADAM_EHIP. */
 int dadam_init(const dadam_config* cfg, dadam_handle** out);
 

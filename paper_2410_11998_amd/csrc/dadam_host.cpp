@@ -116,12 +116,13 @@ int plan(dadam_handle* h) {
   for (size_t k = 0; k < h->tensors.size(); ++k) {
     const dadam_tensor_desc& t = h->tensors[k];
     if (t.numel == 0) continue;
-    if (!h->segs.empty() && h->segs.back().hi == t.offset_elems) {
+    if (!h->segs.empty() && h->segs.back().hi == t.offset_elems && h->segs.back().weight_decay == t.weight_decay) {
       h->segs.back().hi = t.offset_elems + t.numel;
     } else {
       Segment s{};
       s.lo = t.offset_elems;
       s.hi = t.offset_elems + t.numel;
+      s.weight_decay = t.weight_decay;
       h->segs.push_back(s);
     }
     h->tensor_seg[k] = (uint32_t)(h->segs.size() - 1);
@@ -382,8 +383,11 @@ int dadam_init(const dadam_config* cfg, dadam_handle** out) {
       return fail(nullptr, DADAM_EINVAL, "tensor %u starts before tensor %u ends (list must be ordered and disjoint)", k, k ? k - 1 : 0);
     if (t.numel > cfg->d || t.offset_elems > cfg->d - t.numel)
       return fail(nullptr, DADAM_EINVAL, "tensor %u reaches beyond d", k);
-    if (t.weight_decay != 0.f || t.flags != 0)
-      return fail(nullptr, DADAM_EINVAL, "tensor %u: weight_decay and flags are reserved and must be 0", k);
+    if (!(t.weight_decay >= 0.f) || !std::isfinite(t.weight_decay))
+      return fail(nullptr, DADAM_EINVAL, "tensor %u: weight_decay must be finite and >= 0", k);
+    if (t.flags != 0) return fail(nullptr, DADAM_EINVAL, "tensor %u: flags is reserved and must be 0", k);
+    if (t.weight_decay > 0.f && cfg->n_rows > cfg->n_cols)
+      return fail(nullptr, DADAM_EINVAL, "weight decay needs source buffer i to be row i's own parameters (n_rows <= n_cols)");
     prev_end = t.offset_elems + t.numel;
   }
   dadam_handle* h = new (std::nothrow) dadam_handle();

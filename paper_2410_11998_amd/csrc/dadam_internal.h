@@ -13,14 +13,14 @@ constexpr int kMaxRows = DADAM_MAX_ROWS;
 constexpr int kWave = 64;            // gfx950 wavefront
 constexpr int kDirectThreads = 256;  // workgroup of the direct and accumulate kernels
 
-// A maximal run of contiguous tensors: elements [lo, hi) of every buffer.  Work items are tiles of a
+// A maximal run of contiguous tensors with the same hyper-parameters: elements [lo, hi) of every buffer.  Work items are tiles of a
 // fixed grid anchored at element 0, so that vector accesses are 16-byte aligned whenever the
 // buffers are; a tile that sticks out of [lo, hi) is clipped element by element.
 struct Segment {
   uint64_t lo, hi;
   uint64_t first_tile[3];  // per Grid: index of the first tile of that grid that intersects the segment
   uint32_t work0[3];       // per Grid: number of work items (tiles; per row in direct mode) in earlier segments
-  uint32_t pad_;
+  float weight_decay;      // decoupled weight decay of the tensors in this segment
 };
 
 // Which of the three tile grids a launch walks: the fused step's tiles, the direct/accumulate

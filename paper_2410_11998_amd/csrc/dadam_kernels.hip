@@ -215,16 +215,17 @@ __device__ __forceinline__ void unpack_raw(u4 r, float (&out)[XT::vec]) {
 // Algorithm 3, lines 6-13, for one element.  mix is the finished neighbour sum of line 8.
 // Returns x^(t); updates mh, vh, b in registers according to the phase.
 // ---------------------------------------------------------------------------------------------
+// decay = lambda * x_own (0 where there is no weight decay): the AdamW-style part of the direction.
 template <int PHASE>
 __device__ __forceinline__ float element_step(const Scalars& s, float mix, float g, float& mh,
-                                              float& vh, float& b) {
+                                              float& vh, float& b, float decay) {
   if constexpr (PHASE == kMixOnly) return mix;
   // lines 6-7: temporary moments from the persistent ones and the fresh gradient
   float m = fmaf(s.beta1, mh, s.omb1 * g);
   float v = fmaf(s.beta2, vh, s.omb2 * (g * g));
   // line 8: bias correction with exponent t_hat, epsilon outside the root
   float denom = sqrtf(v * s.inv_c2) + s.eps;
-  float u = (m * s.inv_c1) / denom;
+  float u = (m * s.inv_c1) / denom + decay;
   float x = fmaf(-s.lr, u, mix);
   // line 9
   if constexpr (PHASE == kPlain || PHASE == kFold) b = fmaf(g, s.inv_s, b);
@@ -250,7 +251,7 @@ struct Needs {
 // Which segment does work item `work` belong to, and which tile of the launch's grid is it?
 // (Fields are read one by one through the pointer: copying the struct would put it in scratch.)
 __device__ __forceinline__ void locate(const StepArgs& a, uint32_t work, uint64_t& tile_index,
-                                       uint64_t& lo, uint64_t& hi) {
+                                       uint64_t& lo, uint64_t& hi, float& weight_decay) {
   const uint32_t grid = a.grid;
   const Segment* seg = a.seg;
   uint32_t s = 0;
@@ -266,6 +267,7 @@ __device__ __forceinline__ void locate(const StepArgs& a, uint32_t work, uint64_
   const uint64_t slo = seg[s].lo, shi = seg[s].hi;
   lo = slo > a.clip_lo ? slo : a.clip_lo;
   hi = shi < a.clip_hi ? shi : a.clip_hi;
+  weight_decay = seg[s].weight_decay;
 }
 
 // Row i's slice of the neighbour list, one entry per lane, and its bounds as wave-uniform values.
@@ -299,7 +301,7 @@ __device__ __forceinline__ float list_w(const RowList& r, int k) {
 // ---------------------------------------------------------------------------------------------
 template <typename XT, typename GT, int PHASE, int W, int UT, bool MASKED, bool NT>
 __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t tbase, uint64_t lo,
-                                          uint64_t hi, int lane, int wave) {
+                                          uint64_t hi, float wd, int lane, int wave) {
   constexpr int VEC = XT::vec;
   uint64_t e[UT];
 #pragma unroll
@@ -366,12 +368,28 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
       }
     }
 
+    // decoupled weight decay acts on the row's own previous parameters: source buffer i
+    float decay[UT][VEC];
+#pragma unroll
+    for (int u = 0; u < UT; ++u)
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) decay[u][j] = 0.0f;
+    if (PHASE != kMixOnly && wd != 0.0f) {
+#pragma unroll
+      for (int u = 0; u < UT; ++u) {
+        float xs[VEC];
+        unpack_raw<XT>(lds[(i * UT + u) * kWave + lane], xs);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) decay[u][j] = wd * xs[j];
+      }
+    }
+
     float xo[UT][VEC];
 #pragma unroll
     for (int u = 0; u < UT; ++u)
 #pragma unroll
       for (int j = 0; j < VEC; ++j)
-        xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j]);
+        xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j], decay[u][j]);
 
     void* xd = a.x_dst[i];
 #pragma unroll
@@ -410,12 +428,13 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
     if (b < chunk * kXcds) b = (b % kXcds) * chunk + b / kXcds;
   }
   uint64_t tile_index, lo, hi;
-  locate(a, a.work_begin + b, tile_index, lo, hi);
+  float wd;
+  locate(a, a.work_begin + b, tile_index, lo, hi, wd);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
-    tile_body<XT, GT, PHASE, W, UT, false, NT>(a, lds, tbase, lo, hi, lane, wave);
+    tile_body<XT, GT, PHASE, W, UT, false, NT>(a, lds, tbase, lo, hi, wd, lane, wave);
   } else {
-    tile_body<XT, GT, PHASE, W, UT, true, NT>(a, lds, tbase, lo, hi, lane, wave);
+    tile_body<XT, GT, PHASE, W, UT, true, NT>(a, lds, tbase, lo, hi, wd, lane, wave);
   }
 }
 
@@ -480,7 +499,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
 
 template <typename XT, typename GT, int PHASE, bool MASKED, bool NT>
 __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t tbase, uint64_t lo,
-                                            uint64_t hi, int lane) {
+                                            uint64_t hi, float wd, int lane) {
   constexpr int VEC = XT::vec;
   uint64_t e[kUD];
 #pragma unroll
@@ -523,12 +542,29 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
     case 5: mix_direct<XT, 5, MASKED, NT>(a, rl, e, lo, hi, mix); break;
     default: mix_direct<XT, 0, MASKED, NT>(a, rl, e, lo, hi, mix); break;
   }
+  // decoupled weight decay acts on the row's own previous parameters: source buffer `row` (the
+  // load repeats one the mixing sum has just made, so it is served by the cache)
+  float decay[kUD][VEC];
+#pragma unroll
+  for (int u = 0; u < kUD; ++u)
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) decay[u][j] = 0.0f;
+  if (PHASE != kMixOnly && wd != 0.0f) {
+    const void* own = a.x_src[row];
+#pragma unroll
+    for (int u = 0; u < kUD; ++u) {
+      float xs[VEC];
+      unpack_raw<XT>(load_raw<XT, MASKED, false>(own, e[u], lo, hi), xs);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) decay[u][j] = wd * xs[j];
+    }
+  }
   float xo[kUD][VEC];
 #pragma unroll
   for (int u = 0; u < kUD; ++u)
 #pragma unroll
     for (int j = 0; j < VEC; ++j)
-      xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j]);
+      xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j], decay[u][j]);
   void* xd = a.x_dst[row];
 #pragma unroll
   for (int u = 0; u < kUD; ++u) store_vals<XT, VEC, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
@@ -558,12 +594,13 @@ __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
   const uint32_t t = blockIdx.x / n_rows;
   const int row = (int)(blockIdx.x - t * n_rows);
   uint64_t tile_index, lo, hi;
-  locate(a, a.work_begin + t, tile_index, lo, hi);
+  float wd;
+  locate(a, a.work_begin + t, tile_index, lo, hi, wd);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
-    direct_body<XT, GT, PHASE, false, NT>(a, row, tbase, lo, hi, lane);
+    direct_body<XT, GT, PHASE, false, NT>(a, row, tbase, lo, hi, wd, lane);
   } else {
-    direct_body<XT, GT, PHASE, true, NT>(a, row, tbase, lo, hi, lane);
+    direct_body<XT, GT, PHASE, true, NT>(a, row, tbase, lo, hi, wd, lane);
   }
 }
 
@@ -633,7 +670,8 @@ __global__ __launch_bounds__(kDirectThreads) void k_acc(const StepArgs a) {
   const uint32_t t = blockIdx.x / n_rows;
   const int row = (int)(blockIdx.x - t * n_rows);
   uint64_t tile_index, lo, hi;
-  locate(a, a.work_begin + t, tile_index, lo, hi);
+  float wd_unused;
+  locate(a, a.work_begin + t, tile_index, lo, hi, wd_unused);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
     acc_body<GT, VEC, PHASE, false, NT>(a, row, tbase, lo, hi);

@@ -55,7 +55,7 @@ class GpuSim:
 
     def __init__(self, n_rows: int, n_cols: int, layout: WL.PackedLayout, hp: HyperF32, csrs: Sequence,
                  param_dtype: str = "f32", grad_dtype: str = "f32", inplace: bool = False,
-                 pad_fill: Optional[float] = None, device: str = "cuda:0"):
+                 pad_fill: Optional[float] = None, device: str = "cuda:0", weight_decay=None):
         self.R, self.C, self.layout, self.hp = n_rows, n_cols, layout, hp
         self.pd, self.gd = param_dtype, grad_dtype
         self.dev = torch.device(device)
@@ -78,7 +78,8 @@ class GpuSim:
             for t in ([] if inplace else self.x_dst) + self.m + self.v + (self.b or []):
                 t[inv] = pad_fill
         self.h = B.dadam_init(n_rows, n_cols, d, layout.offsets, layout.numels, ABI_DT[param_dtype], ABI_DT[grad_dtype],
-                              hp.lr, hp.beta1, hp.beta2, hp.eps, hp.s, hp.beta_vhat, device=self.dev.index or 0)
+                              hp.lr, hp.beta1, hp.beta2, hp.eps, hp.s, hp.beta_vhat, device=self.dev.index or 0,
+                              weight_decay=weight_decay)
         self.csrs = list(csrs)
         for k, (rp, col, w) in enumerate(self.csrs):
             B.dadam_set_topology(self.h, k, rp, col, w)
@@ -162,13 +163,23 @@ def state_scales(prev: O.State, grads64, t: int, hp: O.Hyper):
     return sb, sm, sv
 
 
+def per_coordinate_decay(layout: WL.PackedLayout, weight_decay) -> Optional[np.ndarray]:
+    """Per-tensor weight decay (as float32, the way the library receives it) spread over coordinates."""
+    if weight_decay is None:
+        return None
+    out = np.zeros(layout.d)
+    for o, n, w in zip(layout.offsets, layout.numels, weight_decay):
+        out[int(o):int(o) + int(n)] = float(np.float32(w))
+    return out
+
+
 def compare_step(prev: O.State, ref_x, ref_state: O.State, got, grads64, csr: O.Csr, t: int, hp: O.Hyper,
-                 param_dtype: str, mask: Optional[np.ndarray] = None, what: str = "") -> dict:
+                 param_dtype: str, mask: Optional[np.ndarray] = None, what: str = "", wd=None) -> dict:
     """Element-by-element comparison of one iteration's outputs.  ``prev`` is the state both
     sides started the iteration from (teacher forcing) or the oracle's own previous state
     (free running).  Returns the worst ratios error / bound (all must be <= 1)."""
     gx, gm, gv, gb = got
-    xs = O.magnitude_scale(prev, grads64, csr, t, hp)
+    xs = O.magnitude_scale(prev, grads64, csr, t, hp, weight_decay=wd)
     sb, sm, sv = state_scales(prev, grads64, t, hp)
     rt = RTOL[param_dtype]
     worst = {"x": 0.0, "m": 0.0, "v": 0.0, "b": 0.0}
@@ -207,12 +218,12 @@ class FreeBounds:
         self.av = [np.zeros(n) for _ in range(n_rows)]
         self.ab = [np.zeros(n) for _ in range(n_rows)]
 
-    def advance(self, prev: O.State, grads64, csr: O.Csr, t: int, hp: O.Hyper, x_ratio: float):
+    def advance(self, prev: O.State, grads64, csr: O.Csr, t: int, hp: O.Hyper, x_ratio: float, wd=None):
         """prev: the oracle's state before iteration t.  x_ratio = tolerance of the moments divided by
         the tolerance of x (1 for float32 parameters, 1e-4 for bfloat16)."""
         th = O.t_hat(t, hp.s)
         c1, c2 = 1.0 - hp.beta1 ** th, 1.0 - hp.beta2 ** th
-        xs = O.magnitude_scale(prev, grads64, csr, t, hp)
+        xs = O.magnitude_scale(prev, grads64, csr, t, hp, weight_decay=wd)
         sb, sm, sv = state_scales(prev, grads64, t, hp)
         new_ax = []
         for i in range(csr.n_rows):
@@ -224,7 +235,8 @@ class FreeBounds:
             u = np.abs(m / c1) / denom
             from_m = hp.lr * hp.beta1 * self.am[i] / c1 / denom
             from_v = hp.lr * u * 0.5 * hp.beta2 * self.av[i] / np.maximum(v, 1e-300) * (np.sqrt(v / c2) / denom)
-            new_ax.append(inh + xs[i] + x_ratio * (from_m + from_v))
+            from_decay = 0.0 if wd is None else hp.lr * np.abs(wd) * self.ax[i]
+            new_ax.append(inh + xs[i] + from_decay + x_ratio * (from_m + from_v))
         for i in range(csr.n_rows):
             self.ax[i] = new_ax[i]
             loop_start = (t - 1) % hp.s == 0
@@ -256,12 +268,14 @@ def to_device(arr: np.ndarray, dtype: str, dev) -> torch.Tensor:
 def run_parity(wl_name: str, n_rows: int, n_cols: int, layout: WL.PackedLayout, hp: HyperF32, csrs, slot_of_t,
                T: int, seed: int, param_dtype="f32", grad_dtype="f32", grad_std=1e-2, flags=B.DADAM_FUSE_ACCUM,
                inplace=False, shared_init=False, refresh_extra_sources=False, unfused=False, free_running=True,
-               pad_fill: Optional[float] = 777.0):
+               pad_fill: Optional[float] = 777.0, weight_decay=None):
     """Whole-vector parity over T iterations.  Each iteration is checked teacher-forced (the
     oracle restarts from the device's previous state) and, with free_running, a second oracle
     that never sees device state is compared at the end."""
     dev = torch.device("cuda:0")
-    sim = GpuSim(n_rows, n_cols, layout, hp, csrs, param_dtype, grad_dtype, inplace=inplace, pad_fill=pad_fill)
+    sim = GpuSim(n_rows, n_cols, layout, hp, csrs, param_dtype, grad_dtype, inplace=inplace, pad_fill=pad_fill,
+                 weight_decay=weight_decay)
+    wd = per_coordinate_decay(layout, weight_decay)
     ohp = hp.oracle()
     mask = valid_mask(layout)
     d = layout.d
@@ -293,15 +307,15 @@ def run_parity(wl_name: str, n_rows: int, n_cols: int, layout: WL.PackedLayout, 
         torch.cuda.synchronize()
         got = sim.outputs()
         ref_state = O.State(prev.x_src, list(prev.m_hat), list(prev.v_hat), list(prev.b))
-        ref_x = O.dadam_step(ref_state, g64, csr, t, ohp, "O32m", param_dtype)
-        w = compare_step(prev, ref_x, ref_state, got, g64, csr, t, ohp, param_dtype, mask, f"{wl_name} t={t}")
+        ref_x = O.dadam_step(ref_state, g64, csr, t, ohp, "O32m", param_dtype, weight_decay=wd)
+        w = compare_step(prev, ref_x, ref_state, got, g64, csr, t, ohp, param_dtype, mask, f"{wl_name} t={t}", wd=wd)
         assert_within(w, f"{wl_name} teacher-forced t={t}")
         for k in worst_all:
             worst_all[k] = max(worst_all[k], w[k])
         if free is not None:
             fprev = O.State(list(free.x_src), list(free.m_hat), list(free.v_hat), list(free.b))
-            fx = O.dadam_step(free, g64, csr, t, ohp, "O32m", param_dtype)
-            bounds.advance(fprev, g64, csr, t, ohp, 1e-6 / H_RTOL(param_dtype))
+            fx = O.dadam_step(free, g64, csr, t, ohp, "O32m", param_dtype, weight_decay=wd)
+            bounds.advance(fprev, g64, csr, t, ohp, 1e-6 / H_RTOL(param_dtype), wd=wd)
             bounds.check(got, fx, free, H_RTOL(param_dtype), mask, f"{wl_name} free-running t={t}")
             for i in range(n_rows):
                 free.x_src[i] = fx[i]

@@ -445,3 +445,28 @@ def test_time_varying_loops_alternating_exponential_ring():
     opr = [WL.one_peer_ring(n, k) for k in range(2)]
     w = H.run_parity("one-peer-ring", n, n, layout, hp, opr, lambda t: (t - 1) % 2, 5, seed=56, grad_std=1e-2)
     say("one-peer ring worst error / tolerance:", w)
+
+
+@pytest.mark.parametrize("mode", ["tile", "direct"])
+@pytest.mark.parametrize("dtype,s", [("f32", 1), ("f32", 2), ("bf16", 2)])
+def test_per_tensor_weight_decay(mode, dtype, s):
+    """AdamW-style decoupled decay on some tensors only (as in the paper's ResNet-50 recipe, which
+    exempts normalisation parameters), ragged layout, both kernels, including the unfused sequence."""
+    say("case", mode, dtype, s)
+    n = 4
+    layout = WL.pack(WL.odd_shapes() + [("big", (50001,))])
+    wds = [0.0 if k % 3 == 0 else (3e-2 if k % 3 == 1 else 0.5) for k in range(len(layout.names))]
+    hp = H.HyperF32(lr=1e-2, s=s)
+    for unfused in (False, True):
+        w = H.run_parity("decay", n, n, layout, hp, [WL.ring(n)], lambda t: 0, 2 * s + 1, seed=88, param_dtype=dtype,
+                         grad_dtype=dtype, grad_std=1e-2, flags=B.DADAM_FUSE_ACCUM | MODES[mode], weight_decay=wds,
+                         unfused=unfused)
+        say("worst error / tolerance:", w)
+
+
+def test_weight_decay_node_share_in_place():
+    """One row with receive buffers, updated in place: the decay uses source buffer 0, the row's own."""
+    layout = WL.pack([("w", (30000,)), ("norm", (257,))])
+    w = H.run_parity("decay-node", 1, 3, layout, H.HyperF32(lr=1e-2, s=2), [WL.node_share_ring()], lambda t: 0, 4, seed=89,
+                     inplace=True, refresh_extra_sources=True, weight_decay=[0.1, 0.0], pad_fill=None)
+    say("worst error / tolerance:", w)

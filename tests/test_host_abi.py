@@ -61,9 +61,10 @@ def test_init_rejects_bad_configurations():
                 dict(param_dtype=2), dict(grad_dtype=7), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=-1.0),
                 dict(lr=float("inf")), dict(abi_version=99), dict(beta_vhat=1.5), dict(device=-3),
                 dict(offsets=[0, 50]), dict(offsets=[104, 0]), dict(d=120), dict(offsets=[], numels=[]),
-                dict(weight_decay=[0.0, 0.1]), dict(tensor_flags=[1, 0])):
+                dict(weight_decay=[0.0, -0.1]), dict(weight_decay=[float("nan"), 0.0]), dict(tensor_flags=[1, 0]),
+                dict(n_rows=2, n_cols=1, weight_decay=[0.0, 0.1])):
         expect(B.DADAM_EINVAL, B.dadam_init, **{**ok, **bad})
-    assert "tensor" in B.dadam_last_error(None)
+    assert "weight decay" in B.dadam_last_error(None)      # the text of the last failure of this thread
 
 
 def test_planner_segments_and_tiles():
@@ -78,6 +79,11 @@ def test_planner_segments_and_tiles():
     assert info.n_tiles_tile == want
     D = info.direct_elems
     assert info.n_tiles_direct == sum((hi - 1) // D - lo // D + 1 for lo, hi in ((0, 310), (1000, 5000)))
+    B.dadam_destroy(h)
+    # tensors with different weight decay do not merge even when contiguous
+    h = B.dadam_init(2, 2, 5000, [0, 100, 300, 1000], [100, 200, 700, 4000], device=B.DADAM_DEVICE_NONE,
+                     weight_decay=[0.0, 0.0, 0.1, 0.1])
+    assert B.dadam_get_plan_info(h).n_segments == 2       # [0,300) and [300,5000)
     B.dadam_destroy(h)
     for cfg, segs in ((2, 1), (3, 1), (4, 1), (5, 1)):
         wl = WL.workload(cfg)
