@@ -257,6 +257,16 @@ def mix_only(x_src: Sequence[np.ndarray], csr: Csr, mode: str = "O32m",
     return [_store_x(m, mode, param_dtype) for m in mix_rows(x_src, csr)]
 
 
+def consensus_error(x: Sequence[np.ndarray]) -> float:
+    """Squared distance of the replicas from their average, sum_i ||x_i - x_bar||^2 with
+    x_bar = (1/N) sum_i x_i: the quantity whose decay per communication round the paper plots
+    to compare topologies (section on heterogeneous communication), and the left-hand side of
+    the consensus lemma."""
+    X = np.stack([np.asarray(a, dtype=np.float64) for a in x])
+    xbar = X.mean(axis=0)
+    return float(np.sum((X - xbar) ** 2))
+
+
 def run_simulation(x0: Sequence[np.ndarray], grads_of_t, csr_of_t, T: int, hp: Hyper,
                    mode: str = "O32m", param_dtype: str = "f32", t_start: int = 1,
                    state: Optional[State] = None, weight_decay=None) -> State:

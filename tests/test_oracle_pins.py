@@ -598,3 +598,31 @@ def test_weight_decay_acts_on_own_previous_model_per_coordinate():
         # averaged over workers the decay pulls the mean model (doubly stochastic W)
         np.testing.assert_allclose(np.mean(st.x_src, axis=0),
                                    np.mean(prev, axis=0) - hp.lr * np.mean([U[i] + lam * prev[i] for i in range(n)], axis=0), atol=1e-14)
+
+
+# ---------------------------------------------------------------------------------------
+# consensus error
+# ---------------------------------------------------------------------------------------
+
+def test_consensus_error_definition_and_decay():
+    """Brute-force double loop on a tiny case; zero for equal replicas; invariant under a common
+    shift; and with pure gossip on the 4-ring (all non-consensus eigenvalues +-1/3) it shrinks by
+    exactly 1/9 per round, the lambda^2 rate of the consensus lemma."""
+    rng = np.random.default_rng(91)
+    n, d = 4, 7
+    x = [rng.standard_normal(d) for _ in range(n)]
+    want = 0.0
+    for e in range(d):
+        mean = sum(x[i][e] for i in range(n)) / n
+        for i in range(n):
+            want += (x[i][e] - mean) ** 2
+    assert abs(O.consensus_error(x) - want) < 1e-13
+    assert O.consensus_error([x[0]] * n) == 0.0
+    assert abs(O.consensus_error([a + 5.0 for a in x]) - want) < 1e-12
+    csr = csr_of(WL.ring(n), w64=True)
+    err = O.consensus_error(x)
+    for _ in range(6):
+        x = O.mix_only(x, csr, mode="O64")
+        new = O.consensus_error(x)
+        np.testing.assert_allclose(new, err / 9.0, rtol=1e-12)
+        err = new
