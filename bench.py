@@ -76,7 +76,7 @@ def path_bytes_per_replica_param(wl, phase: str, path: str) -> float:
     acc = {"alg1": pg + 8 + 8, "plain": pg + 4 + 4, "loopstart": pg + 4, "fold": pg + 4 + 4 + 8 + 8}[phase]
     if path == "accumulate":
         return acc
-    if path == "mix":
+    if path in ("mix", "mix_consensus"):
         return src + px
     return (src + px + pg + 8) + acc          # unfused: update-only pass, then the accumulate pass
 
@@ -109,7 +109,7 @@ def main() -> int:
     ap.add_argument("--mode", choices=["auto", "tile", "direct"], default="auto")
     ap.add_argument("--inplace", action="store_true", help="update parameters in place instead of ping-pong")
     ap.add_argument("--pool", type=int, default=2, help="number of pre-generated gradient sets cycled through")
-    ap.add_argument("--path", choices=["fused", "unfused", "mix", "accumulate", "buckets"], default="fused",
+    ap.add_argument("--path", choices=["fused", "unfused", "mix", "mix_consensus", "accumulate", "buckets"], default="fused",
                     help="fused: one dadam_gossip_step per iteration (the benchmark); unfused: dadam_gossip_step without "
                          "accumulation followed by dadam_accumulate; mix: dadam_mix only; accumulate: dadam_accumulate only; "
                          "buckets: the fused step issued tensor range by tensor range (--bucket-mb)")
@@ -221,6 +221,7 @@ def main() -> int:
                 buckets.append((start, k + 1))
                 start, cur = k + 1, 0
     mode_flags = flags & ~B.DADAM_FUSE_ACCUM
+    consensus_out = torch.zeros(1, dtype=torch.float64, device=dev)
 
     def one_step(t: int):
         g = pool[t % len(pool)]
@@ -232,6 +233,8 @@ def main() -> int:
             B.dadam_accumulate(h, g, t, stream)
         elif args.path == "mix":
             B.dadam_mix(h, slot, mode_flags, stream)
+        elif args.path == "mix_consensus":
+            B.dadam_mix_consensus(h, slot, consensus_out, mode_flags, stream)
         elif args.path == "accumulate":
             B.dadam_accumulate(h, g, t, stream)
         else:

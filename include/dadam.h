@@ -185,6 +185,17 @@ int dadam_accumulate(dadam_handle* h, const void* const* grads, uint64_t t, void
  * of DADAM_FORCE_DIRECT / DADAM_FORCE_TILE. */
 int dadam_mix(dadam_handle* h, uint32_t slot, uint32_t flags, void* hip_stream);
 
+/* dadam_mix plus, at no extra HBM traffic, the consensus error of the SOURCES,
+ *     *consensus_out = sum over source buffers c and elements e of (x_src[c][e] - mean_c x_src[.][e])^2,
+ * the squared distance of the replicas from their average whose decay per gossip round the paper
+ * plots to compare topologies (section "Important aspects ...", heterogeneous communication; the
+ * consensus lemma bounds the same quantity).  consensus_out is a DEVICE pointer to one double,
+ * written by work enqueued on the stream; per-element arithmetic is float32, the sum double.
+ * Available in tile mode only (the sources of a tile are then on chip together); DADAM_ESTATE
+ * otherwise.  Calls on one handle must not overlap in time: they share the handle's partial sums. */
+int dadam_mix_consensus(dadam_handle* h, uint32_t slot, uint32_t flags, double* consensus_out,
+                        void* hip_stream);
+
 /* Change the step size used by later calls (learning-rate schedules). */
 int dadam_set_lr(dadam_handle* h, float lr);
 

@@ -31,7 +31,7 @@ DADAM_WARN_NOT_COLUMN_STOCHASTIC = 1
 
 EXPORTS = [
     "dadam_init", "dadam_set_topology", "dadam_bind", "dadam_swap_x", "dadam_gossip_step",
-    "dadam_gossip_step_range", "dadam_accumulate", "dadam_mix", "dadam_set_lr", "dadam_get_plan_info",
+    "dadam_gossip_step_range", "dadam_accumulate", "dadam_mix", "dadam_mix_consensus", "dadam_set_lr", "dadam_get_plan_info",
     "dadam_slot_uses_tile_mode", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_last_error", "dadam_destroy",
 ]
 
@@ -75,6 +75,7 @@ def _load() -> C.CDLL:
     lib.dadam_gossip_step_range.argtypes = [H, C.c_uint32, C.POINTER(C.c_void_p), C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
     lib.dadam_accumulate.argtypes = [H, C.POINTER(C.c_void_p), C.c_uint64, C.c_void_p]
     lib.dadam_mix.argtypes = [H, C.c_uint32, C.c_uint32, C.c_void_p]
+    lib.dadam_mix_consensus.argtypes = [H, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]
     lib.dadam_set_lr.argtypes = [H, C.c_float]
     lib.dadam_get_plan_info.argtypes = [H, C.POINTER(dadam_plan_info)]
     lib.dadam_slot_uses_tile_mode.argtypes = [H, C.c_uint32]
@@ -221,6 +222,15 @@ def dadam_accumulate(h, grads, t: int, stream: int = 0) -> None:
 
 def dadam_mix(h, slot: int, flags: int = 0, stream: int = 0) -> None:
     _check(h, lib.dadam_mix(h, slot, flags, C.c_void_p(stream)))
+
+
+def dadam_mix_consensus(h, slot: int, out, flags: int = 0, stream: int = 0) -> None:
+    """out: a device tensor holding one float64 (or an integer device address)."""
+    if not isinstance(out, int):
+        if out.numel() < 1 or out.element_size() != 8:
+            raise ValueError("consensus output must hold one float64")
+        out = out.data_ptr()
+    _check(h, lib.dadam_mix_consensus(h, slot, flags, C.c_void_p(out), C.c_void_p(stream)))
 
 
 def dadam_set_lr(h, lr: float) -> None:

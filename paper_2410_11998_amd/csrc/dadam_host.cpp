@@ -57,6 +57,7 @@ struct dadam_handle {
   std::vector<uint32_t> tensor_seg;  // segment of each non-empty tensor, UINT32_MAX for empty ones
   std::vector<Segment> segs;
   Segment* d_segs = nullptr;
+  double* d_partials = nullptr;  // kConsensusPartials doubles of scratch for the consensus error
   TileShape shape{4, 1, false};
   TileShape mix_shape{4, 1, false};  // shape of the mixing-only launch (more bytes in flight per wavefront)
   uint32_t mix_tile_elems = 0, mix_lds_bytes = 0;
@@ -290,7 +291,7 @@ int resolve_range(const dadam_handle* h, uint32_t tb, uint32_t te, bool whole, u
 }
 
 int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint64_t t, uint32_t flags,
-              bool whole, uint32_t tb, uint32_t te, bool mix_only, void* stream) {
+              bool whole, uint32_t tb, uint32_t te, bool mix_only, void* stream, double* consensus_out = nullptr) {
   if (!h) return DADAM_EINVAL;
   int rc = check_launchable(h);
   if (rc) return rc;
@@ -312,12 +313,26 @@ int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint6
   bool tile_mode = false;
   rc = choose_mode(h, slot, flags, &tile_mode);
   if (rc) return rc;
+  if (consensus_out) {
+    if (!tile_mode)
+      return fail(h, DADAM_ESTATE, "the consensus error is a by-product of tile mode (shared sources that fit in LDS)");
+    phase = kMixConsensus;
+  }
   uint64_t lo = 0, hi = 0;
   uint32_t s0 = 0, s1 = 0;
   bool empty = false;
   rc = resolve_range(h, tb, te, whole, &lo, &hi, &s0, &s1, &empty);
   if (rc) return rc;
-  if (empty) return DADAM_OK;
+  DeviceGuard guard(h->cfg.device);
+  if (guard.err != hipSuccess) return fail(h, DADAM_EHIP, "hipSetDevice: %s", hipGetErrorString(guard.err));
+  if (consensus_out) {
+    int e0 = launch_consensus_zero(h->d_partials, stream);
+    if (e0 != (int)hipSuccess) return fail(h, DADAM_EHIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)e0));
+  }
+  if (empty) {
+    if (consensus_out) (void)launch_consensus_sum(h->d_partials, consensus_out, stream);
+    return DADAM_OK;
+  }
   uint32_t w0 = 0, w1 = 0;
   const Grid grid = !tile_mode ? kGridDirect : mix_only ? kGridMix : kGridTile;
   work_range(h, grid, s0, s1, lo, hi, &w0, &w1);
@@ -327,13 +342,13 @@ int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint6
   a.work_begin = w0;
   a.clip_lo = lo;
   a.clip_hi = hi;
+  a.partials = h->d_partials;
   fill_scalars(h, mix_only ? 1 : t, &a.s);
-  DeviceGuard guard(h->cfg.device);
-  if (guard.err != hipSuccess) return fail(h, DADAM_EHIP, "hipSetDevice: %s", hipGetErrorString(guard.err));
   int e = tile_mode
               ? launch_tile((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase, mix_only ? h->mix_shape : h->shape, a, w1 - w0,
                             mix_only ? h->mix_lds_bytes : h->lds_bytes, stream)
               : launch_direct((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase, h->nontemporal, a, w1 - w0, stream);
+  if (e == (int)hipSuccess && consensus_out) e = launch_consensus_sum(h->d_partials, consensus_out, stream);
   if (e != (int)hipSuccess)
     return fail(h, DADAM_EHIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)e));
   return DADAM_OK;
@@ -444,8 +459,10 @@ int dadam_init(const dadam_config* cfg, dadam_handle** out) {
       if (e == hipSuccess)
         e = hipMemcpy(h->d_segs, h->segs.data(), h->segs.size() * sizeof(Segment), hipMemcpyHostToDevice);
     }
+    if (e == hipSuccess) e = hipMalloc((void**)&h->d_partials, kConsensusPartials * sizeof(double));
     if (e != hipSuccess) {
       if (h->d_segs) (void)hipFree(h->d_segs);
+      if (h->d_partials) (void)hipFree(h->d_partials);
       delete h;
       return fail(nullptr, DADAM_EHIP, "device set-up failed: %s", hipGetErrorString(e));
     }
@@ -598,6 +615,14 @@ int dadam_mix(dadam_handle* h, uint32_t slot, uint32_t flags, void* hip_stream) 
   return step_impl(h, slot, nullptr, 1, flags, true, 0, 0, true, hip_stream);
 }
 
+int dadam_mix_consensus(dadam_handle* h, uint32_t slot, uint32_t flags, double* consensus_out, void* hip_stream) {
+  if (!h) return DADAM_EINVAL;
+  if (flags & DADAM_FUSE_ACCUM) return fail(h, DADAM_EINVAL, "dadam_mix_consensus takes only the FORCE flags");
+  if (!consensus_out || (reinterpret_cast<uintptr_t>(consensus_out) & 7u))
+    return fail(h, DADAM_EINVAL, "consensus_out must be a non-null, 8-byte aligned device pointer");
+  return step_impl(h, slot, nullptr, 1, flags, true, 0, 0, true, hip_stream, consensus_out);
+}
+
 int dadam_accumulate(dadam_handle* h, const void* const* grads, uint64_t t, void* hip_stream) {
   if (!h) return DADAM_EINVAL;
   int rc = check_launchable(h);
@@ -692,6 +717,7 @@ void dadam_destroy(dadam_handle* h) {
     DeviceGuard guard(h->cfg.device);
     for (Slot& s : h->slots) free_slot(s);
     if (h->d_segs) (void)hipFree(h->d_segs);
+    if (h->d_partials) (void)hipFree(h->d_partials);
   }
   delete h;
 }

@@ -44,8 +44,11 @@ enum Phase : int {
   kLoopStart = 3,   // lines 6-9, first iteration of a loop: b is known to be zero and not read
   kFold = 4,        // lines 6-13, last iteration of a loop (s > 1)
   kAlg1 = 5,        // s == 1: Algorithm 1, moments updated every iteration, no accumulator
-  kNumPhases = 6
+  kMixConsensus = 6,  // x_dst = W x_src and, on the side, sum_c ||x_src[c] - mean||^2 (tile mode only)
+  kNumPhases = 7
 };
+
+constexpr uint32_t kConsensusPartials = 1024;  // partial sums the tiles scatter their contributions over
 
 // Kernel argument block (passed by value; about 3.2 KB of the 4 KB kernarg segment).
 struct StepArgs {
@@ -64,6 +67,7 @@ struct StepArgs {
   uint32_t grid;        // Grid: which tile numbering work items refer to
   uint32_t work_begin;  // first work item (in tiles) of this launch
   uint64_t clip_lo, clip_hi;  // element range of this launch (whole layout or a tensor range)
+  double* partials;           // kConsensusPartials doubles (device), used by kMixConsensus only
   Scalars s;
 };
 
@@ -82,6 +86,10 @@ int launch_direct(int xdt, int gdt, Phase phase, bool nontemporal, const StepArg
 // vec = elements per direct-mode parameter vector of the handle (fixes the tile grid).
 int launch_accumulate(int gdt, Phase phase, bool nontemporal, const StepArgs& a, uint32_t n_work_tiles,
                       void* stream, int vec);
+
+// Consensus error: clear the partial sums / add them up in a fixed order into *out (device).
+int launch_consensus_zero(double* partials, void* stream);
+int launch_consensus_sum(const double* partials, double* out, void* stream);
 
 // Geometry the host planner needs.
 int vec_elems(int xdt);              // elements per 16-byte parameter vector: 4 (f32) or 8 (bf16)

@@ -219,7 +219,7 @@ __device__ __forceinline__ void unpack_raw(u4 r, float (&out)[XT::vec]) {
 template <int PHASE>
 __device__ __forceinline__ float element_step(const Scalars& s, float mix, float g, float& mh,
                                               float& vh, float& b, float decay) {
-  if constexpr (PHASE == kMixOnly) return mix;
+  if constexpr (PHASE == kMixOnly || PHASE == kMixConsensus) return mix;
   // lines 6-7: temporary moments from the persistent ones and the fresh gradient
   float m = fmaf(s.beta1, mh, s.omb1 * g);
   float v = fmaf(s.beta2, vh, s.omb2 * (g * g));
@@ -241,8 +241,9 @@ __device__ __forceinline__ float element_step(const Scalars& s, float mix, float
 
 template <int PHASE>
 struct Needs {
-  static constexpr bool grad = PHASE != kMixOnly;
-  static constexpr bool moments_in = PHASE != kMixOnly;
+  static constexpr bool mixing_only = PHASE == kMixOnly || PHASE == kMixConsensus;
+  static constexpr bool grad = !mixing_only;
+  static constexpr bool moments_in = !mixing_only;
   static constexpr bool acc_in = PHASE == kPlain || PHASE == kFold;
   static constexpr bool acc_out = PHASE == kPlain || PHASE == kLoopStart || PHASE == kFold;
   static constexpr bool moments_out = PHASE == kFold || PHASE == kAlg1;
@@ -301,7 +302,7 @@ __device__ __forceinline__ float list_w(const RowList& r, int k) {
 // ---------------------------------------------------------------------------------------------
 template <typename XT, typename GT, int PHASE, int W, int UT, bool MASKED, bool NT>
 __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t tbase, uint64_t lo,
-                                          uint64_t hi, float wd, int lane, int wave) {
+                                          uint64_t hi, float wd, uint32_t tile_id, int lane, int wave) {
   constexpr int VEC = XT::vec;
   uint64_t e[UT];
 #pragma unroll
@@ -318,6 +319,39 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
     for (int u = 0; u < UT; ++u) lds[(c * UT + u) * kWave + lane] = r[u];
   }
   __syncthreads();
+
+  if constexpr (PHASE == kMixConsensus) {
+    // Consensus error of the sources, sum_c (x_c - mean)^2 per element, as a by-product: the whole
+    // tile is in LDS anyway.  One wavefront per tile (taking turns) does it in one pass on values
+    // shifted by source 0, y_c = x_c - x_0, so that sum y^2 - (sum y)^2 / C does not cancel.
+    // Elements outside the segment were staged as zeros in every source and add nothing.
+    if (wave == (int)(tile_id % (uint32_t)W)) {
+      const float inv_c = 1.0f / (float)n_cols;
+      float acc = 0.0f;
+#pragma unroll
+      for (int u = 0; u < UT; ++u) {
+        float ref[VEC], s1[VEC], s2[VEC];
+        unpack_raw<XT>(lds[u * kWave + lane], ref);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
+        for (int c = 1; c < n_cols; ++c) {
+          float xs[VEC];
+          unpack_raw<XT>(lds[(c * UT + u) * kWave + lane], xs);
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) {
+            const float y = xs[j] - ref[j];
+            s1[j] += y;
+            s2[j] = fmaf(y, y, s2[j]);
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc += s2[j] - s1[j] * s1[j] * inv_c;
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+      if (lane == 0) atomicAdd(a.partials + (tile_id % kConsensusPartials), (double)acc);
+    }
+  }
 
   const int n_rows = (int)a.n_rows;
   for (int i = wave; i < n_rows; i += W) {
@@ -374,7 +408,7 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
     for (int u = 0; u < UT; ++u)
 #pragma unroll
       for (int j = 0; j < VEC; ++j) decay[u][j] = 0.0f;
-    if (PHASE != kMixOnly && wd != 0.0f) {
+    if (!Needs<PHASE>::mixing_only && wd != 0.0f) {
 #pragma unroll
       for (int u = 0; u < UT; ++u) {
         float xs[VEC];
@@ -432,9 +466,9 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
   locate(a, a.work_begin + b, tile_index, lo, hi, wd);
   const uint64_t tbase = tile_index * TILE;
   if (tbase >= lo && tbase + TILE <= hi) {
-    tile_body<XT, GT, PHASE, W, UT, false, NT>(a, lds, tbase, lo, hi, wd, lane, wave);
+    tile_body<XT, GT, PHASE, W, UT, false, NT>(a, lds, tbase, lo, hi, wd, b, lane, wave);
   } else {
-    tile_body<XT, GT, PHASE, W, UT, true, NT>(a, lds, tbase, lo, hi, wd, lane, wave);
+    tile_body<XT, GT, PHASE, W, UT, true, NT>(a, lds, tbase, lo, hi, wd, b, lane, wave);
   }
 }
 
@@ -549,7 +583,7 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
   for (int u = 0; u < kUD; ++u)
 #pragma unroll
     for (int j = 0; j < VEC; ++j) decay[u][j] = 0.0f;
-  if (PHASE != kMixOnly && wd != 0.0f) {
+  if (!Needs<PHASE>::mixing_only && wd != 0.0f) {
     const void* own = a.x_src[row];
 #pragma unroll
     for (int u = 0; u < kUD; ++u) {
@@ -681,6 +715,27 @@ __global__ __launch_bounds__(kDirectThreads) void k_acc(const StepArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// consensus error: partial sums are cleared by a kernel (not a memset, so that the sequence can be
+// captured in a graph) and added up by one workgroup in a fixed order
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_consensus_zero(double* partials) {
+  for (uint32_t i = threadIdx.x; i < kConsensusPartials; i += 256) partials[i] = 0.0;
+}
+
+__global__ __launch_bounds__(256) void k_consensus_sum(const double* partials, double* out) {
+  __shared__ double red[256];
+  double s = 0.0;
+  for (uint32_t i = threadIdx.x; i < kConsensusPartials; i += 256) s += partials[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[0] = red[0] < 0.0 ? 0.0 : red[0];
+}
+
+// ---------------------------------------------------------------------------------------------
 // dispatch tables
 // ---------------------------------------------------------------------------------------------
 typedef void (*KernelFn)(const StepArgs);
@@ -689,6 +744,7 @@ template <typename XT, typename GT, int W, int UT, bool NT>
 KernelFn tile_kernel_for_phase(int phase) {
   switch (phase) {
     case kMixOnly: return k_tile<XT, GT, kMixOnly, W, UT, NT>;
+    case kMixConsensus: return k_tile<XT, GT, kMixConsensus, W, UT, NT>;
     case kUpdateOnly: return k_tile<XT, GT, kUpdateOnly, W, UT, NT>;
     case kPlain: return k_tile<XT, GT, kPlain, W, UT, NT>;
     case kLoopStart: return k_tile<XT, GT, kLoopStart, W, UT, NT>;
@@ -753,6 +809,16 @@ int launch(KernelFn fn, uint32_t grid, uint32_t block, uint32_t lds, const StepA
 static_assert(sizeof(StepArgs) <= 4096, "kernel argument block must fit the kernarg segment");
 
 }  // namespace
+
+int launch_consensus_zero(double* partials, void* stream) {
+  hipLaunchKernelGGL(k_consensus_zero, dim3(1), dim3(256), 0, reinterpret_cast<hipStream_t>(stream), partials);
+  return (int)hipGetLastError();
+}
+
+int launch_consensus_sum(const double* partials, double* out, void* stream) {
+  hipLaunchKernelGGL(k_consensus_sum, dim3(1), dim3(256), 0, reinterpret_cast<hipStream_t>(stream), partials, out);
+  return (int)hipGetLastError();
+}
 
 int vec_elems(int xdt) { return xdt == DADAM_BF16 ? TBF16::vec : TF32::vec; }
 int direct_unroll() { return kUD; }

@@ -108,6 +108,9 @@ class GpuSim:
     def mix(self, slot: int = 0, flags: int = 0):
         B.dadam_mix(self.h, slot, flags, self.stream())
 
+    def mix_consensus(self, out, slot: int = 0, flags: int = 0):
+        B.dadam_mix_consensus(self.h, slot, out, flags, self.stream())
+
     def swap(self):
         """Ping-pong: the outputs of this iteration are the sources of the next."""
         if self.inplace:

@@ -470,3 +470,42 @@ def test_weight_decay_node_share_in_place():
     w = H.run_parity("decay-node", 1, 3, layout, H.HyperF32(lr=1e-2, s=2), [WL.node_share_ring()], lambda t: 0, 4, seed=89,
                      inplace=True, refresh_extra_sources=True, weight_decay=[0.1, 0.0], pad_fill=None)
     say("worst error / tolerance:", w)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("topo", ["ring4", "exp16", "onepeer64"])
+def test_consensus_error_by_product_of_mixing(dtype, topo):
+    """dadam_mix_consensus writes the same x_dst bits as dadam_mix and reports the squared distance
+    of the sources from their mean; over repeated gossip rounds on the 4-ring it shrinks by 1/9 per
+    round (the lambda^2 rate of the consensus lemma)."""
+    say("case", dtype, topo)
+    n, csr3 = {"ring4": (4, WL.ring(4)), "exp16": (16, WL.static_exponential(16)), "onepeer64": (64, WL.one_peer_exponential(64, 3))}[topo]
+    layout = WL.pack(WL.odd_shapes() + [("big", (40003,))])
+    d = layout.d
+    sim = H.GpuSim(n, n, layout, H.HyperF32(s=1), [csr3], dtype, dtype, pad_fill=None)
+    for c in range(n):
+        sim.x_src[c].copy_(H.to_device(WL.normal_np(2000 + c, d, 0.02) + 0.5, dtype, DEV))   # deviations << values
+    mask = H.valid_mask(layout)
+    out = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+    prev_err = None
+    for rnd in range(4):
+        xs = [x[mask] for x in sim._get(sim.x_src, None)]
+        want = O.consensus_error(xs)
+        sim.mix()
+        torch.cuda.synchronize()
+        plain = [x.clone() for x in sim.x_dst]
+        sim.mix_consensus(out)
+        torch.cuda.synchronize()
+        got = float(out.item())
+        for a_, b_ in zip(plain, sim.x_dst):
+            assert torch.equal(a_, b_)
+        assert abs(got - want) <= 2e-5 * want + 1e-30, (rnd, got, want)
+        if topo == "ring4" and dtype == "f32" and prev_err is not None:
+            assert abs(got / prev_err - 1.0 / 9.0) < 1e-4
+        prev_err = got
+        sim.swap()
+    # the by-product needs the tile kernel
+    with pytest.raises(B.DadamError) as e:
+        sim.mix_consensus(out, 0, B.DADAM_FORCE_DIRECT)
+    assert e.value.code == B.DADAM_ESTATE
+    sim.close()

@@ -168,6 +168,9 @@ def test_bind_alignment_and_aliasing_rules():
     expect(B.DADAM_ESTATE, B.dadam_gossip_step, h, 0, [P(11), P(12)], 1)
     expect(B.DADAM_ESTATE, B.dadam_accumulate, h, [P(11), P(12)], 1)
     expect(B.DADAM_ESTATE, B.dadam_mix, h, 0)
+    expect(B.DADAM_ESTATE, B.dadam_mix_consensus, h, 0, P(13))
+    expect(B.DADAM_EINVAL, B.dadam_mix_consensus, h, 0, 0)
+    expect(B.DADAM_EINVAL, B.dadam_mix_consensus, h, 0, P(13) + 4)
     B.dadam_destroy(h)
 
 
