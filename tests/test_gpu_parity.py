@@ -509,3 +509,93 @@ def test_consensus_error_by_product_of_mixing(dtype, topo):
         sim.mix_consensus(out, 0, B.DADAM_FORCE_DIRECT)
     assert e.value.code == B.DADAM_ESTATE
     sim.close()
+
+
+def test_empty_layouts_and_single_replica():
+    """Degenerate shapes: a layout whose tensors are all empty launches nothing and touches nothing;
+    a single replica (n = 1, W = [1]) is plain Adam in either kernel."""
+    layout = WL.PackedLayout(["e0", "e1"], np.array([0, 8], np.uint64), np.array([0, 0], np.uint64), 16)
+    sim = H.GpuSim(2, 2, layout, H.HyperF32(s=2), [WL.ring(2)], pad_fill=None)
+    for t_ in sim.x_src + sim.x_dst + sim.m + sim.v + sim.b:
+        t_.fill_(3.0)
+    g = [torch.ones(16, device=DEV) for _ in range(2)]
+    for flags in (B.DADAM_FUSE_ACCUM, B.DADAM_FUSE_ACCUM | B.DADAM_FORCE_DIRECT, 0):
+        sim.step(g, 2, 0, flags)
+    sim.accumulate(g, 2)
+    sim.mix()
+    out = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+    sim.mix_consensus(out)
+    torch.cuda.synchronize()
+    assert float(out.item()) == 0.0
+    for t_ in sim.x_src + sim.x_dst + sim.m + sim.v + sim.b:
+        assert bool(torch.all(t_ == 3.0))
+    sim.close()
+    for mode in ("tile", "direct"):
+        H.run_parity("single", 1, 1, flat_layout(5003), H.HyperF32(s=3), [WL.ring(1)], lambda t: 0, 7, seed=93,
+                     flags=B.DADAM_FUSE_ACCUM | MODES[mode])
+
+
+def test_late_iteration_bias_correction():
+    """t = 10^6 + k: the bias corrections are 1 to float32 precision; iteration numbers are 64-bit."""
+    n, d = 2, 4099
+    layout = flat_layout(d)
+    hp = H.HyperF32(s=4)
+    sim = H.GpuSim(n, n, layout, hp, [WL.ring(n)], pad_fill=None)
+    ohp = hp.oracle()
+    csr = H.csr_oracle(WL.ring(n))
+    mask = H.valid_mask(layout)
+    for c in range(n):
+        sim.x_src[c].copy_(H.to_device(WL.normal_np(940 + c, layout.d, 0.02), "f32", DEV))
+        sim.m[c].copy_(H.to_device(WL.normal_np(950 + c, layout.d, 1e-3), "f32", DEV))
+        sim.v[c].copy_(H.to_device(np.abs(WL.normal_np(960 + c, layout.d, 1e-6)), "f32", DEV))
+        sim.b[c].copy_(H.to_device(WL.normal_np(970 + c, layout.d, 1e-3), "f32", DEV))
+    for t in (10 ** 6 + 2, 10 ** 6 + 3, 10 ** 6 + 4, (1 << 33) + 4):
+        grads = [H.to_device(WL.normal_np(980 + (t % 97) * 4 + i, layout.d, 1e-2), "f32", DEV) for i in range(n)]
+        g64 = [g.to(torch.float64).cpu().numpy() for g in grads]
+        prev = sim.snapshot()
+        sim.step(grads, t)
+        torch.cuda.synchronize()
+        ref_state = O.State(prev.x_src, list(prev.m_hat), list(prev.v_hat), list(prev.b))
+        ref_x = O.dadam_step(ref_state, g64, csr, t, ohp, "O32m", "f32")
+        H.assert_within(H.compare_step(prev, ref_x, ref_state, sim.outputs(), g64, csr, t, ohp, "f32", mask), f"late t={t}")
+        sim.swap()
+    sim.close()
+
+
+@pytest.mark.parametrize("mode", ["tile", "direct"])
+def test_buffers_beyond_4_gib_use_64_bit_offsets(mode):
+    """1.34 G elements per buffer (5.4 GB of float32): byte offsets pass 2^32; checked on sampled
+    coordinates including the last elements."""
+    say("case", mode)
+    d_real = (1 << 30) + (1 << 28) + 1001
+    layout = WL.pack([("a", (1 << 30,)), ("b", ((1 << 28) + 1001,))])
+    assert layout.d >= d_real
+    n = 2
+    hp = H.HyperF32(s=2)
+    sim = H.GpuSim(n, n, layout, hp, [WL.ring(n)], pad_fill=None)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(4242)
+    for c in range(n):
+        sim.x_src[c].normal_(0.0, 0.02, generator=gen)
+        sim.x_src[c][d_real:] = 0.0          # padding after the last tensor: must stay as it is
+    grads = [torch.empty(layout.d, device=DEV).normal_(0.0, 1e-2, generator=gen) for _ in range(n)]
+    rng = np.random.default_rng(5)
+    idx_np = np.unique(np.concatenate([np.arange(0, 2048), np.arange(d_real - 4096, d_real), np.arange((1 << 30) - 512, (1 << 30) + 512),
+                                       rng.integers(0, d_real, size=1 << 15), rng.integers((1 << 30), d_real, size=1 << 14)]))
+    idx = torch.from_numpy(idx_np).to(DEV)
+    ohp = hp.oracle()
+    csr = H.csr_oracle(WL.ring(n))
+    for t in (1, 2):
+        prev = sim.snapshot(idx)
+        g64 = [g[idx].to(torch.float64).cpu().numpy() for g in grads]
+        sim.step(grads, t, 0, B.DADAM_FUSE_ACCUM | MODES[mode])
+        torch.cuda.synchronize()
+        ref_state = O.State(prev.x_src, list(prev.m_hat), list(prev.v_hat), list(prev.b))
+        ref_x = O.dadam_step(ref_state, g64, csr, t, ohp, "O32m", "f32")
+        H.assert_within(H.compare_step(prev, ref_x, ref_state, sim.outputs(idx), g64, csr, t, ohp, "f32", None), f"big t={t}")
+        # nothing beyond the last tensor was written
+        assert bool(torch.all(sim.x_dst[0][d_real:] == 0)) and bool(torch.all(sim.m[1][d_real:] == 0))
+        sim.swap()
+    sim.close()
+    del sim, grads
+    torch.cuda.empty_cache()
