@@ -300,6 +300,104 @@ __device__ __forceinline__ float list_w(const RowList& r, int k) {
 // ---------------------------------------------------------------------------------------------
 // tile mode
 // ---------------------------------------------------------------------------------------------
+// The stream inputs of one row of a tile: gradient, moments, accumulator (whatever the phase needs).
+template <typename GT, int PHASE, int VEC, int UT, bool MASKED, bool NT>
+__device__ __forceinline__ void load_row_inputs(const StepArgs& a, int i, const uint64_t (&e)[UT], uint64_t lo,
+                                                uint64_t hi, float (&g)[UT][VEC], float (&mh)[UT][VEC],
+                                                float (&vh)[UT][VEC], float (&b)[UT][VEC]) {
+  if constexpr (Needs<PHASE>::grad) {
+    const void* gp = a.grad[i];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) load_vals<GT, VEC, MASKED, NT>(gp, e[u], lo, hi, g[u]);
+  }
+  if constexpr (Needs<PHASE>::moments_in) {
+    const float* mp = a.m_hat[i];
+    const float* vp = a.v_hat[i];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
+#pragma unroll
+    for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
+  }
+  if constexpr (Needs<PHASE>::acc_in) {
+    const float* bp = a.acc[i];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
+  }
+}
+
+// Mixing from LDS, the update of Algorithm 3 and the stores of one row of a tile.
+template <typename XT, int PHASE, int VEC, int UT, bool MASKED, bool NT>
+__device__ __forceinline__ void finish_row(const StepArgs& a, const u4* lds, int i, const RowList& rl,
+                                           const uint64_t (&e)[UT], uint64_t lo, uint64_t hi, float wd, int lane,
+                                           float (&g)[UT][VEC], float (&mh)[UT][VEC], float (&vh)[UT][VEC],
+                                           float (&b)[UT][VEC]) {
+  // neighbour sum in the order the row lists its entries: first a product, then fused
+  // multiply-adds
+  float mix[UT][VEC];
+  {
+    const int c0 = list_col(rl, 0);
+    const float w0 = list_w(rl, 0);
+#pragma unroll
+    for (int u = 0; u < UT; ++u) {
+      float xs[VEC];
+      unpack_raw<XT>(lds[(c0 * UT + u) * kWave + lane], xs);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) mix[u][j] = w0 * xs[j];
+    }
+  }
+  for (int k = 1; k < rl.deg; ++k) {
+    const int c = list_col(rl, k);
+    const float wk = list_w(rl, k);
+#pragma unroll
+    for (int u = 0; u < UT; ++u) {
+      float xs[VEC];
+      unpack_raw<XT>(lds[(c * UT + u) * kWave + lane], xs);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) mix[u][j] = fmaf(wk, xs[j], mix[u][j]);
+    }
+  }
+
+  // decoupled weight decay acts on the row's own previous parameters: source buffer i
+  float decay[UT][VEC];
+#pragma unroll
+  for (int u = 0; u < UT; ++u)
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) decay[u][j] = 0.0f;
+  if (!Needs<PHASE>::mixing_only && wd != 0.0f) {
+#pragma unroll
+    for (int u = 0; u < UT; ++u) {
+      float xs[VEC];
+      unpack_raw<XT>(lds[(i * UT + u) * kWave + lane], xs);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) decay[u][j] = wd * xs[j];
+    }
+  }
+
+  float xo[UT][VEC];
+#pragma unroll
+  for (int u = 0; u < UT; ++u)
+#pragma unroll
+    for (int j = 0; j < VEC; ++j)
+      xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j], decay[u][j]);
+
+  void* xd = a.x_dst[i];
+#pragma unroll
+  for (int u = 0; u < UT; ++u) store_vals<XT, VEC, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
+  if constexpr (Needs<PHASE>::acc_out) {
+    float* bp = a.acc[i];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
+  }
+  if constexpr (Needs<PHASE>::moments_out) {
+    float* mp = a.m_hat[i];
+    float* vp = a.v_hat[i];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
+#pragma unroll
+    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
+  }
+}
+
 template <typename XT, typename GT, int PHASE, int W, int UT, bool MASKED, bool NT>
 __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t tbase, uint64_t lo,
                                           uint64_t hi, float wd, uint32_t tile_id, int lane, int wave) {
@@ -354,93 +452,13 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
   }
 
   const int n_rows = (int)a.n_rows;
+  // (Issuing the next row's loads before the current row is finished was measured and changes
+  // nothing: with 8-32 wavefronts per CU in flight the memory system, not latency, is the limit.)
   for (int i = wave; i < n_rows; i += W) {
     RowList rl = load_row_list(a, i, lane);
     float g[UT][VEC], mh[UT][VEC], vh[UT][VEC], b[UT][VEC];
-    if constexpr (Needs<PHASE>::grad) {
-      const void* gp = a.grad[i];
-#pragma unroll
-      for (int u = 0; u < UT; ++u) load_vals<GT, VEC, MASKED, NT>(gp, e[u], lo, hi, g[u]);
-    }
-    if constexpr (Needs<PHASE>::moments_in) {
-      const float* mp = a.m_hat[i];
-      const float* vp = a.v_hat[i];
-#pragma unroll
-      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
-#pragma unroll
-      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
-    }
-    if constexpr (Needs<PHASE>::acc_in) {
-      const float* bp = a.acc[i];
-#pragma unroll
-      for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
-    }
-
-    // neighbour sum in the order the row lists its entries: first a product, then fused
-    // multiply-adds
-    float mix[UT][VEC];
-    {
-      const int c0 = list_col(rl, 0);
-      const float w0 = list_w(rl, 0);
-#pragma unroll
-      for (int u = 0; u < UT; ++u) {
-        float xs[VEC];
-        unpack_raw<XT>(lds[(c0 * UT + u) * kWave + lane], xs);
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) mix[u][j] = w0 * xs[j];
-      }
-    }
-    for (int k = 1; k < rl.deg; ++k) {
-      const int c = list_col(rl, k);
-      const float wk = list_w(rl, k);
-#pragma unroll
-      for (int u = 0; u < UT; ++u) {
-        float xs[VEC];
-        unpack_raw<XT>(lds[(c * UT + u) * kWave + lane], xs);
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) mix[u][j] = fmaf(wk, xs[j], mix[u][j]);
-      }
-    }
-
-    // decoupled weight decay acts on the row's own previous parameters: source buffer i
-    float decay[UT][VEC];
-#pragma unroll
-    for (int u = 0; u < UT; ++u)
-#pragma unroll
-      for (int j = 0; j < VEC; ++j) decay[u][j] = 0.0f;
-    if (!Needs<PHASE>::mixing_only && wd != 0.0f) {
-#pragma unroll
-      for (int u = 0; u < UT; ++u) {
-        float xs[VEC];
-        unpack_raw<XT>(lds[(i * UT + u) * kWave + lane], xs);
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) decay[u][j] = wd * xs[j];
-      }
-    }
-
-    float xo[UT][VEC];
-#pragma unroll
-    for (int u = 0; u < UT; ++u)
-#pragma unroll
-      for (int j = 0; j < VEC; ++j)
-        xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j], decay[u][j]);
-
-    void* xd = a.x_dst[i];
-#pragma unroll
-    for (int u = 0; u < UT; ++u) store_vals<XT, VEC, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
-    if constexpr (Needs<PHASE>::acc_out) {
-      float* bp = a.acc[i];
-#pragma unroll
-      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
-    }
-    if constexpr (Needs<PHASE>::moments_out) {
-      float* mp = a.m_hat[i];
-      float* vp = a.v_hat[i];
-#pragma unroll
-      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
-#pragma unroll
-      for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
-    }
+    load_row_inputs<GT, PHASE, VEC, UT, MASKED, NT>(a, i, e, lo, hi, g, mh, vh, b);
+    finish_row<XT, PHASE, VEC, UT, MASKED, NT>(a, lds, i, rl, e, lo, hi, wd, lane, g, mh, vh, b);
   }
 }
 
