@@ -7,7 +7,7 @@ workload: one call of dadam_gossip_step (all rows, all elements) followed by the
 ping-pong parameter buffers.  Inputs (parameters, a small pool of pre-generated gradient sets,
 zero moments) are resident in HBM before the timed region starts.  Prints ONE JSON line.
 
-The default workload is BASELINE configuration 2 (16 replicas, static exponential graph,
+The default workload is the benchmark's configuration 2 (16 replicas, static exponential graph,
 GPT-2-small tensor shapes, float32, s = 4); --config selects 1..5.
 """
 

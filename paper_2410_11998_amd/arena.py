@@ -1,9 +1,9 @@
 """Device buffers spread over HBM.
 
 On MI355X a streaming step that touches ~100 arrays at once sustains about 0.65 of peak HBM
-bandwidth when those arrays are packed into one contiguous piece of physical memory and about 0.75
-when they are spread over most of the device's memory (measured; the gain appears once the set
-spans roughly 128 GB).  ``SpreadArena`` makes one allocation and carves the buffers out of it at the
+bandwidth when those arrays all lie inside one 96 GiB third of the device's physical memory (where
+a fresh process's consecutive allocations land) and 0.75-0.77 when they straddle the boundaries
+between thirds (measured).  ``SpreadArena`` makes one allocation and carves the buffers out of it at the
 offsets ``dadam_spread_offsets`` computes; the space between buffers stays untouched and can be used
 for anything else.  Memory management only - nothing of the method is computed here.
 """
