@@ -55,23 +55,37 @@ class GpuSim:
 
     def __init__(self, n_rows: int, n_cols: int, layout: WL.PackedLayout, hp: HyperF32, csrs: Sequence,
                  param_dtype: str = "f32", grad_dtype: str = "f32", inplace: bool = False,
-                 pad_fill: Optional[float] = None, device: str = "cuda:0", weight_decay=None):
+                 pad_fill: Optional[float] = None, device: str = "cuda:0", weight_decay=None, spread: bool = False):
         self.R, self.C, self.layout, self.hp = n_rows, n_cols, layout, hp
         self.pd, self.gd = param_dtype, grad_dtype
         self.dev = torch.device(device)
         d = layout.d
         self.d = d
-        z = lambda dt: torch.zeros(d, dtype=dt, device=self.dev)
-        self.x_src = [z(TORCH_DT[param_dtype]) for _ in range(n_cols)]
         self.inplace = inplace
         if inplace:
             assert n_rows <= n_cols
+        pdt = TORCH_DT[param_dtype]
+        dts = [pdt] * n_cols + ([] if inplace else [pdt] * n_rows) + [torch.float32] * (n_rows * (3 if hp.s > 1 else 2))
+        if spread:
+            # the benchmark's layout: one arena over most of the free memory, buffers at equal distances
+            from paper_2410_11998_amd.arena import SpreadArena
+            self.arena = SpreadArena([d * (2 if dt == torch.bfloat16 else 4) for dt in dts], self.dev,
+                                     keep_free_bytes=48 << 30)      # room for the gradients and temporaries of the test
+            bufs = self.arena.views(dts)
+            for t in bufs:
+                t.zero_()
+        else:
+            bufs = [torch.zeros(d, dtype=dt, device=self.dev) for dt in dts]
+        self.x_src = bufs[:n_cols]
+        k = n_cols
+        if inplace:
             self.x_dst = [self.x_src[i] for i in range(n_rows)]
         else:
-            self.x_dst = [z(TORCH_DT[param_dtype]) for _ in range(n_rows)]
-        self.m = [z(torch.float32) for _ in range(n_rows)]
-        self.v = [z(torch.float32) for _ in range(n_rows)]
-        self.b = [z(torch.float32) for _ in range(n_rows)] if hp.s > 1 else None
+            self.x_dst = bufs[k:k + n_rows]
+            k += n_rows
+        self.m = bufs[k:k + n_rows]
+        self.v = bufs[k + n_rows:k + 2 * n_rows]
+        self.b = bufs[k + 2 * n_rows:k + 3 * n_rows] if hp.s > 1 else None
         if pad_fill is not None:
             # sentinel in the padding between tensors only; it must still be there afterwards
             inv = torch.from_numpy(~valid_mask(layout)).to(self.dev)

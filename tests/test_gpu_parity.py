@@ -344,7 +344,8 @@ def test_full_size_configs_sampled(cfg):
     ohp = hp.oracle()
     csrs = [wl.csr(k) for k in range(wl.n_slots())]
     dev = torch.device(DEV)
-    sim = H.GpuSim(wl.n_rows, wl.n_cols, layout, hp, csrs, wl.param_dtype, wl.grad_dtype, inplace=(cfg == 3), pad_fill=None)
+    sim = H.GpuSim(wl.n_rows, wl.n_cols, layout, hp, csrs, wl.param_dtype, wl.grad_dtype, inplace=(cfg == 3), pad_fill=None,
+                   spread=True)     # the layout bench.py times
     rng = np.random.default_rng(cfg)
     idx_np = sample_coordinates(layout, rng, 1 << (16 if wl.n_rows >= 16 else 18))
     idx = torch.from_numpy(idx_np).to(dev)

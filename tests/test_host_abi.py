@@ -263,3 +263,29 @@ def test_kernels_use_no_scratch_memory(tmp_path):
     sizes = [int(x) for x in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", r.stderr)]
     assert len(sizes) > 100, "no resource remarks found"
     assert max(sizes) == 0, f"{sum(1 for s in sizes if s)} kernels spill or copy to scratch"
+
+
+def test_bench_byte_accounting_matches_the_workload_table():
+    """bench.py's per-phase algorithmic bytes, averaged over one accumulation loop, are the
+    per-element figures of the workload module (28 + 4/s, 36 + 4/s, 22 + 4/s)."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    want = {1: 30.0, 2: 29.0, 3: 36.5, 4: 30.0, 5: 23.0}
+    for cfg in range(1, 6):
+        wl = WL.workload(cfg)
+        loop = [bench.phase_of(t, wl.s) for t in range(1, wl.s + 1)]
+        avg = sum(bench.algorithmic_bytes_per_replica_param(wl, p) for p in loop) / wl.s
+        assert abs(avg - want[cfg]) < 1e-12 and abs(wl.bytes_per_replica_param() - want[cfg]) < 1e-12
+        assert loop[0] == "loopstart" and loop[-1] == "fold"
+        for p in loop:
+            assert bench.path_bytes_per_replica_param(wl, p, "fused") == bench.algorithmic_bytes_per_replica_param(wl, p)
+            assert bench.path_bytes_per_replica_param(wl, p, "unfused") > bench.algorithmic_bytes_per_replica_param(wl, p)
+    # the quoted traffic table agrees with the algorithmic bytes to a tenth of a percent
+    for name, table in bench.MEASURED_TRAFFIC_BYTES.items():
+        cfg = int(name[3])
+        wl = WL.workload(cfg)
+        n = wl.n_rows * wl.layout().d
+        for phase, measured in table.items():
+            assert abs(measured / (n * bench.algorithmic_bytes_per_replica_param(wl, phase)) - 1.0) < 1e-3
