@@ -39,6 +39,9 @@
  *   - All validation happens on the host before anything is launched; a failed call launches
  *     nothing.
  *   - At most DADAM_MAX_ROWS rows and DADAM_MAX_ROWS source buffers per handle.
+ *   - A handle is not thread-safe: calls on one handle must come from one thread at a time.  Launches
+ *     on different streams may be in flight together (every launch carries its own copy of the pointer
+ *     tables and scalars), except dadam_mix_consensus, whose calls share scratch memory of the handle.
  */
 #ifndef DADAM_H_
 #define DADAM_H_

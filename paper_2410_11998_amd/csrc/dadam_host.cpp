@@ -347,7 +347,9 @@ int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint6
   int e = tile_mode
               ? launch_tile((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase, mix_only ? h->mix_shape : h->shape, a, w1 - w0,
                             mix_only ? h->mix_lds_bytes : h->lds_bytes, stream)
-              : launch_direct((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase, h->nontemporal, a, w1 - w0, stream);
+              : launch_direct((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase,
+                              // where rows share sources the re-reads must find them in the cache
+                              h->nontemporal && !slot.reuse, a, w1 - w0, stream);
   if (e == (int)hipSuccess && consensus_out) e = launch_consensus_sum(h->d_partials, consensus_out, stream);
   if (e != (int)hipSuccess)
     return fail(h, DADAM_EHIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)e));

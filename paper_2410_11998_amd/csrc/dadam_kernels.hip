@@ -30,19 +30,17 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 
-// Elements per lane and vector.  float32 parameters: 4 (one 128-bit access).  bfloat16 parameters:
-// 8 (one 128-bit access of x and g, two of each float32 state vector, the lane's 32 bytes
-// contiguous) or 4 (64-bit accesses of x and g, one fully coalesced 128-bit access of state).
-#ifndef DADAM_BF16_VEC
-#define DADAM_BF16_VEC 8
-#endif
+// Element types, with the elements per lane and vector of a handle whose parameters have that type:
+// float32 4 (one 128-bit access); bfloat16 8 (one 128-bit access of x and g, two of each float32 state
+// vector, the lane's 32 bytes contiguous).  A 4-element bfloat16 variant with fully coalesced state
+// accesses was measured at +0.3 % and not kept.
 struct TF32 {
   static constexpr int bytes = 4;
   static constexpr int vec = 4;
 };
 struct TBF16 {
   static constexpr int bytes = 2;
-  static constexpr int vec = DADAM_BF16_VEC;
+  static constexpr int vec = 8;
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
@@ -77,12 +75,10 @@ __device__ __forceinline__ void store_elem(void* base, uint64_t e, float v) {
 // touch only the elements that are; the others read as zero.
 // Streaming accesses: every global datum of a step is touched exactly once, so full-vector
 // accesses may carry the non-temporal hint (NT) and leave the caches to nobody in particular.
-#ifndef DADAM_NT_BITS
-#define DADAM_NT_BITS 5
-#endif
-constexpr bool kNtSource = (DADAM_NT_BITS & 1) != 0;  // parameter (source) loads
-constexpr bool kNtStream = (DADAM_NT_BITS & 2) != 0;  // gradient / moment / accumulator loads
-constexpr bool kNtStore = (DADAM_NT_BITS & 4) != 0;   // all stores
+// Which classes of access carry the hint when a handle streams (all eight combinations measured):
+constexpr bool kNtSource = true;   // parameter (source) loads
+constexpr bool kNtStream = false;  // gradient / moment / accumulator loads: costs the bf16 variant 5 %
+constexpr bool kNtStore = true;    // all stores
 
 template <bool NT, typename V>
 __device__ __forceinline__ V vload(const V* p) {
@@ -160,28 +156,15 @@ __device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, 
   }
 }
 
-// The 16 bytes a parameter vector occupies in LDS: 4 float32, 8 bfloat16 as stored, or 4 bfloat16
-// already widened to float32.
+// The 16 raw bytes of a parameter vector (4 float32 or 8 bfloat16), as they are parked in LDS.
 template <typename XT, bool MASKED, bool NT>
 __device__ __forceinline__ u4 load_raw(const void* base, uint64_t e, uint64_t lo, uint64_t hi) {
   constexpr int VEC = XT::vec;
   if (!MASKED || (e >= lo && e + VEC <= hi)) {
-    if constexpr (XT::bytes == 2 && VEC == 4) {
-      u2 h = vload<NT && kNtSource>(reinterpret_cast<const u2*>(reinterpret_cast<const uint16_t*>(base) + e));
-      u4 w = {h.x << 16, h.x & 0xFFFF0000u, h.y << 16, h.y & 0xFFFF0000u};  // exact widening
-      return w;
-    } else {
-      return vload<NT && kNtSource>(reinterpret_cast<const u4*>(reinterpret_cast<const char*>(base) + e * XT::bytes));
-    }
+    return vload<NT && kNtSource>(reinterpret_cast<const u4*>(reinterpret_cast<const char*>(base) + e * XT::bytes));
   }
   u4 r = {0u, 0u, 0u, 0u};
-  if constexpr (XT::bytes == 2 && VEC == 4) {
-    const uint16_t* p = reinterpret_cast<const uint16_t*>(base);
-    if (e + 0 >= lo && e + 0 < hi) r.x = (uint32_t)p[e + 0] << 16;
-    if (e + 1 >= lo && e + 1 < hi) r.y = (uint32_t)p[e + 1] << 16;
-    if (e + 2 >= lo && e + 2 < hi) r.z = (uint32_t)p[e + 2] << 16;
-    if (e + 3 >= lo && e + 3 < hi) r.w = (uint32_t)p[e + 3] << 16;
-  } else if constexpr (XT::bytes == 4) {
+  if constexpr (XT::bytes == 4) {
     const uint32_t* p = reinterpret_cast<const uint32_t*>(base);
     if (e + 0 >= lo && e + 0 < hi) r.x = p[e + 0];
     if (e + 1 >= lo && e + 1 < hi) r.y = p[e + 1];
@@ -200,7 +183,7 @@ __device__ __forceinline__ u4 load_raw(const void* base, uint64_t e, uint64_t lo
 
 template <typename XT>
 __device__ __forceinline__ void unpack_raw(u4 r, float (&out)[XT::vec]) {
-  if constexpr (XT::bytes == 4 || XT::vec == 4) {
+  if constexpr (XT::bytes == 4) {
     out[0] = __uint_as_float(r.x); out[1] = __uint_as_float(r.y);
     out[2] = __uint_as_float(r.z); out[3] = __uint_as_float(r.w);
   } else {
@@ -493,10 +476,7 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
 // ---------------------------------------------------------------------------------------------
 // direct mode
 // ---------------------------------------------------------------------------------------------
-#ifndef DADAM_DIRECT_UNROLL
-#define DADAM_DIRECT_UNROLL 2
-#endif
-constexpr int kUD = DADAM_DIRECT_UNROLL;  // 16-byte parameter vectors per thread
+constexpr int kUD = 2;  // 16-byte parameter vectors per thread (1 and 4 measured slower)
 
 // Neighbour sum with all loads of DEG sources issued before the first use.  DEG == 0: any degree.
 template <typename XT, int DEG, bool MASKED, bool NT>
@@ -657,8 +637,8 @@ __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// accumulate / fold only (Algorithm 3 lines 9-13).  Tiles have the direct-mode size of a float32
-// layout: 4 elements per 16-byte state vector.
+// accumulate / fold only (Algorithm 3 lines 9-13).  Walks the direct kernel's tile grid, so a lane
+// vector has as many elements as a parameter vector of the handle (4 or 8).
 // ---------------------------------------------------------------------------------------------
 template <int PHASE>
 __device__ __forceinline__ void acc_step(const Scalars& s, float g, float& mh, float& vh, float& b) {
@@ -778,14 +758,6 @@ KernelFn tile_kernel_for_shape_nt(int phase, TileShape s) {
   if (s.waves == 4 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 4, 2, NT>(phase);
   if (s.waves == 8 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 8, 1, NT>(phase);
   if (s.waves == 8 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 8, 2, NT>(phase);
-#ifdef DADAM_ALL_SHAPES
-  if (s.waves == 1 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 1, 1, NT>(phase);
-  if (s.waves == 2 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 2, 1, NT>(phase);
-  if (s.waves == 2 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 2, 2, NT>(phase);
-  if (s.waves == 16 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 16, 1, NT>(phase);
-  if (s.waves == 4 && s.ut == 4) return tile_kernel_for_phase<XT, GT, 4, 4, NT>(phase);
-  if (s.waves == 8 && s.ut == 4) return tile_kernel_for_phase<XT, GT, 8, 4, NT>(phase);
-#endif
   return nullptr;
 }
 template <typename XT, typename GT>
@@ -841,9 +813,6 @@ int launch_consensus_sum(const double* partials, double* out, void* stream) {
 int vec_elems(int xdt) { return xdt == DADAM_BF16 ? TBF16::vec : TF32::vec; }
 int direct_unroll() { return kUD; }
 bool tile_shape_supported(TileShape s) {
-#ifdef DADAM_ALL_SHAPES
-  return true;
-#endif
   return (s.waves == 4 || s.waves == 8) && (s.ut == 1 || s.ut == 2);
 }
 
