@@ -130,14 +130,19 @@ def test_config1_every_element_every_step(mode):
     say("worst error / tolerance:", worst)
 
 
-@pytest.mark.parametrize("cfg,div,mode", [(2, 16, "auto"), (2, 16, "direct"), (3, 16, "auto"), (3, 16, "tile"),
-                                         (4, 4, "auto"), (4, 4, "direct"), (5, 16, "auto"), (5, 16, "direct")])
-def test_scaled_configs_every_element(cfg, div, mode):
-    say("case", cfg, div, mode)
+@pytest.mark.parametrize("cfg,div,mode,full", [(2, 16, "auto", True), (2, 16, "direct", False), (3, 16, "auto", True),
+                                              (3, 16, "tile", False), (4, 16, "auto", True), (4, 8, "auto", False),
+                                              (4, 8, "direct", False), (5, 32, "auto", True), (5, 16, "auto", False),
+                                              (5, 16, "direct", False)])
+def test_scaled_configs_every_element(cfg, div, mode, full):
+    """Small copies of configurations 2-5 (same tensor lists, dimensions divided), every element checked
+    at every iteration, teacher-forced and against a free-running oracle; `full` runs the configuration's
+    whole step count (20, 50, 30, 10 iterations), the others two accumulation loops and a step."""
+    say("case", cfg, div, mode, full)
     wl = WL.workload(cfg, scale_div=div)
     hp = H.HyperF32(wl.lr, wl.beta1, wl.beta2, wl.eps, wl.s)
     csrs = [wl.csr(k) for k in range(wl.n_slots())]
-    T = min(wl.steps, 2 * wl.s + 1)
+    T = wl.steps if full else min(wl.steps, 2 * wl.s + 1)
     worst = H.run_parity(wl.name, wl.n_rows, wl.n_cols, wl.layout(), hp, csrs, lambda t: wl.slot_of_step(t), T,
                          seed=10 + cfg, param_dtype=wl.param_dtype, grad_dtype=wl.grad_dtype, grad_std=wl.grad_std,
                          flags=B.DADAM_FUSE_ACCUM | MODES[mode], refresh_extra_sources=(cfg == 3),
@@ -332,6 +337,9 @@ def sample_coordinates(layout, rng, n_random):
         for edge in (int(o), int(o) + int(n)):
             pick.append(np.arange(max(0, edge - 64), min(d, edge + 64)))
     pick.append(rng.integers(0, d, size=n_random))
+    # both sides of randomly chosen tile boundaries of the kernels (multiples of 256 elements)
+    tiles = rng.integers(1, max(2, d // 256), size=2048) * 256
+    pick.append(np.concatenate([tiles + k for k in (-2, -1, 0, 1)]).clip(0, d - 1))
     return np.unique(np.concatenate(pick))
 
 
