@@ -1,0 +1,84 @@
+// Host-side fuzz driver for the C ABI, meant to be built with AddressSanitizer and
+// UndefinedBehaviorSanitizer (tests/test_host_abi.py does that).  The kernel launchers are replaced by
+// stubs, so only host logic runs: validation, the tile planner, neighbour-list checks, aliasing rules,
+// the layout helpers.  Random, partly malformed inputs; every call must return a status, never crash.
+#include "dadam.h"
+#include "dadam_internal.h"
+#include <cstdio>
+#include <vector>
+#include <cmath>
+#include <random>
+namespace dadam {
+int launch_tile(int, int, Phase, TileShape, const StepArgs&, uint32_t, uint32_t, void*) { return 0; }
+int launch_direct(int, int, Phase, bool, const StepArgs&, uint32_t, void*) { return 0; }
+int launch_accumulate(int, Phase, bool, const StepArgs&, uint32_t, void*, int) { return 0; }
+int launch_consensus_zero(double*, void*) { return 0; }
+int launch_consensus_sum(const double*, double*, void*) { return 0; }
+int vec_elems(int xdt) { return xdt == DADAM_BF16 ? 8 : 4; }
+int direct_unroll() { return 2; }
+bool tile_shape_supported(TileShape s) { return (s.waves == 4 || s.waves == 8) && (s.ut == 1 || s.ut == 2); }
+}
+int main() {
+  std::mt19937_64 rng(1);
+  int n_ok = 0, n_err = 0;
+  for (int iter = 0; iter < 3000; ++iter) {
+    uint32_t R = 1 + rng() % 64, C = 1 + rng() % 64;
+    uint32_t nt = 1 + rng() % 40;
+    std::vector<dadam_tensor_desc> ts(nt);
+    uint64_t cur = 0;
+    for (auto& t : ts) {
+      cur += (rng() % 3 == 0) ? rng() % 17 : 0;
+      t.offset_elems = cur; t.numel = rng() % 5000; t.weight_decay = (rng() % 4 == 0 && R <= C) ? 0.01f : 0.f; t.flags = 0;
+      cur += t.numel;
+    }
+    dadam_config cfg{};
+    cfg.abi_version = DADAM_ABI_VERSION; cfg.n_rows = R; cfg.n_cols = C; cfg.d = cur + rng() % 9 + 1; cfg.n_tensors = nt; cfg.tensors = ts.data();
+    cfg.param_dtype = rng() % 2; cfg.grad_dtype = rng() % 2; cfg.lr = 1e-3f; cfg.beta1 = 0.9f; cfg.beta2 = 0.999f; cfg.eps = 1e-8f;
+    cfg.accum_s = 1 + rng() % 4; cfg.beta_vhat = -1.f; cfg.device = DADAM_DEVICE_NONE;
+    dadam_handle* h = nullptr;
+    int rc = dadam_init(&cfg, &h);
+    if (rc != 0) { ++n_err; continue; }
+    // random topology, sometimes broken
+    std::vector<int32_t> rp(R + 1, 0), col; std::vector<float> w;
+    for (uint32_t i = 0; i < R; ++i) {
+      uint32_t deg = 1 + rng() % C;
+      std::vector<int32_t> perm(C); for (uint32_t c = 0; c < C; ++c) perm[c] = c;
+      for (uint32_t c = 0; c < deg; ++c) std::swap(perm[c], perm[c + rng() % (C - c)]);
+      for (uint32_t c = 0; c < deg; ++c) { col.push_back(perm[c]); w.push_back(1.0f / deg); }
+      rp[i + 1] = (int32_t)col.size();
+    }
+    if (rng() % 5 == 0 && !col.empty()) col[rng() % col.size()] = (int32_t)(rng() % 200) - 50;
+    if (rng() % 7 == 0 && !w.empty()) w[rng() % w.size()] = -1.f;
+    uint32_t warn = 0;
+    rc = dadam_set_topology(h, rng() % 18, rp.data(), col.data(), w.data(), &warn);
+    rc == 0 ? ++n_ok : ++n_err;
+    // bind with fake addresses
+    size_t stride = cfg.d * 4 + 4096;
+    std::vector<const void*> xs(C); std::vector<void*> xd(R); std::vector<float*> m(R), v(R), b(R);
+    uintptr_t base = 1 << 20; size_t k = 0;
+    for (auto& p : xs) p = (const void*)(base + stride * k++);
+    bool inplace = rng() % 3 == 0 && R <= C;
+    for (uint32_t i = 0; i < R; ++i) xd[i] = inplace ? const_cast<void*>(xs[i]) : (void*)(base + stride * k++);
+    for (auto& p : m) p = (float*)(base + stride * k++);
+    for (auto& p : v) p = (float*)(base + stride * k++);
+    for (auto& p : b) p = (float*)(base + stride * k++);
+    if (rng() % 6 == 0) m[rng() % R] = (float*)xs[rng() % C];
+    dadam_buffers bufs{xs.data(), xd.data(), m.data(), v.data(), b.data()};
+    rc = dadam_bind(h, &bufs);
+    rc == 0 ? ++n_ok : ++n_err;
+    dadam_plan_info info; dadam_get_plan_info(h, &info);
+    for (uint32_t s = 0; s < DADAM_MAX_SLOTS; ++s) (void)dadam_slot_uses_tile_mode(h, s);
+    (void)dadam_swap_x(h);
+    std::vector<const void*> g(R); for (auto& p : g) p = (const void*)(base + stride * k++);
+    (void)dadam_gossip_step(h, 0, g.data(), 1 + rng() % 9, DADAM_FUSE_ACCUM, nullptr);
+    (void)dadam_gossip_step_range(h, 0, g.data(), 3, DADAM_FUSE_ACCUM, rng() % (nt + 2), rng() % (nt + 2), nullptr);
+    (void)dadam_accumulate(h, g.data(), 2, nullptr);
+    (void)dadam_mix(h, 0, 0, nullptr);
+    (void)dadam_last_error(h);
+    dadam_destroy(h);
+  }
+  std::vector<uint64_t> nb = {5, 1u << 21, 77, 3u << 20}; std::vector<uint64_t> off(4);
+  (void)dadam_spread_offsets(nb.data(), 4, 1ull << 30, off.data());
+  printf("sanitizer driver finished: %d ok, %d rejected\n", n_ok, n_err);
+  return 0;
+}

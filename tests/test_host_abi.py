@@ -289,3 +289,24 @@ def test_bench_byte_accounting_matches_the_workload_table():
         n = wl.n_rows * wl.layout().d
         for phase, measured in table.items():
             assert abs(measured / (n * bench.algorithmic_bytes_per_replica_param(wl, phase)) - 1.0) < 1e-3
+
+
+def test_host_code_under_address_and_ub_sanitizers(tmp_path):
+    """Builds the host side of the library with ASan + UBSan (kernel launchers stubbed out) together
+    with tests/host_sanitizer_driver.cpp and runs a few thousand random, partly malformed call
+    sequences through init / set_topology / bind / step validation / planner."""
+    import subprocess
+    clang = "/opt/rocm/lib/llvm/bin/clang++"
+    if not os.path.exists(clang):
+        pytest.skip("clang++ of the ROCm toolchain not available")
+    exe = str(tmp_path / "san_driver")
+    cmd = [clang, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2410_11998_amd", "csrc"),
+           "-I", "/opt/rocm/include", os.path.join(ROOT, "tests", "host_sanitizer_driver.cpp"),
+           os.path.join(ROOT, "paper_2410_11998_amd", "csrc", "dadam_host.cpp"),
+           "-L/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib", "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and "sanitizer driver finished" in r.stdout, (r.stdout[-500:], r.stderr[-3000:])
+    assert "ERROR" not in r.stderr and "runtime error" not in r.stderr, r.stderr[-3000:]
