@@ -120,6 +120,9 @@ def main() -> int:
     ap.add_argument("--span-gib", type=int, default=0, help="arena size for --layout spread (default: free memory minus 12 GiB)")
     ap.add_argument("--scale-div", type=int, default=1, help="divide tensor dimensions (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--repeats", type=int, default=1,
+                    help="after the timed region, time that many minus one further regions of the same length and "
+                         "report all of them (median and minimum) next to the first, which stays the reported value")
     ap.add_argument("--cpu-sample", type=int, default=None, help="coordinates per row given to the CPU oracle")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of a known size (1 GiB read + 1 GiB written each), so that "
@@ -263,6 +266,16 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
 
+    region_ms = [elapsed / K * 1e3]
+    for _ in range(max(0, args.repeats - 1)):
+        torch.cuda.synchronize()
+        r0 = time.perf_counter()
+        for k in range(K):
+            t += 1
+            one_step(t)
+        torch.cuda.synchronize()
+        region_ms.append((time.perf_counter() - r0) / K * 1e3)
+
     kernel_ms = [ev0[k].elapsed_time(ev1[k]) for k in range(K)]
     avg_kernel_s = sum(kernel_ms) / K / 1e3
     replica_params = R * d
@@ -285,6 +298,7 @@ def main() -> int:
         "steps": K,
         "warmup": W,
         "ms_per_step": elapsed / K * 1e3,
+        "ms_per_step_regions": {"all": region_ms, "median": sorted(region_ms)[len(region_ms) // 2], "min": min(region_ms)},
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
