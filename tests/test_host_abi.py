@@ -310,3 +310,43 @@ def test_host_code_under_address_and_ub_sanitizers(tmp_path):
     r = subprocess.run([exe], capture_output=True, text=True, timeout=600)
     assert r.returncode == 0 and "sanitizer driver finished" in r.stdout, (r.stdout[-500:], r.stderr[-3000:])
     assert "ERROR" not in r.stderr and "runtime error" not in r.stderr, r.stderr[-3000:]
+
+
+def _model_plan(offsets, numels, wds, tile, direct):
+    """Python model of the planner: maximal runs of contiguous tensors with equal weight decay, and the
+    number of tiles of a grid anchored at element 0 that each run touches."""
+    segs = []
+    for o, n, w in zip(offsets, numels, wds):
+        if n == 0:
+            continue
+        if segs and segs[-1][1] == o and segs[-1][2] == w:
+            segs[-1][1] = o + n
+        else:
+            segs.append([o, o + n, w])
+    count = lambda T: sum((hi - 1) // T - lo // T + 1 for lo, hi, _ in segs)
+    return len(segs), count(tile), count(direct)
+
+
+def test_planner_against_python_model_random_layouts():
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=150, deadline=None)
+    @given(st.lists(st.tuples(st.integers(0, 40), st.integers(0, 5000), st.sampled_from([0.0, 0.0, 0.01])), min_size=1, max_size=30),
+           st.sampled_from([B.DADAM_F32, B.DADAM_BF16]), st.integers(1, 64))
+    def check(items, dtype, n):
+        offsets, numels, wds, cur = [], [], [], 0
+        for gap, numel, wd in items:
+            cur += gap
+            offsets.append(cur); numels.append(numel); wds.append(wd)
+            cur += numel
+        d = cur + 1
+        h = B.dadam_init(n, n, d, offsets, numels, dtype, dtype, accum_s=2, device=B.DADAM_DEVICE_NONE, weight_decay=wds)
+        info = B.dadam_get_plan_info(h)
+        vec = 8 if dtype == B.DADAM_BF16 else 4
+        assert info.tile_elems == 64 * vec and info.direct_elems == 256 * vec * 2
+        want = _model_plan(offsets, numels, [float(np.float32(w)) for w in wds], info.tile_elems, info.direct_elems)
+        assert (info.n_segments, info.n_tiles_tile, info.n_tiles_direct) == want
+        assert info.lds_bytes_tile == n * 64 * 16 and info.tile_mode_possible == 1
+        B.dadam_destroy(h)
+
+    check()

@@ -626,3 +626,42 @@ def test_consensus_error_definition_and_decay():
         new = O.consensus_error(x)
         np.testing.assert_allclose(new, err / 9.0, rtol=1e-12)
         err = new
+
+
+def test_random_doubly_stochastic_matrices_properties():
+    """Random doubly stochastic W (convex combinations of permutation matrices), random s, random
+    degree: the replica mean follows the averaged-direction recursion, pure mixing never increases
+    the consensus error, and s = 1 with any W leaves the accumulator empty."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=40, deadline=None)
+    @given(st.integers(2, 9), st.integers(1, 4), st.integers(1, 5), st.integers(0, 10 ** 6))
+    def check(n, n_perm, s, seed):
+        rng = np.random.default_rng(seed)
+        W = np.zeros((n, n))
+        coef = rng.random(n_perm) + 0.05
+        coef /= coef.sum()
+        for c in coef:
+            W[np.arange(n), rng.permutation(n)] += c
+        row_ptr, col, w = [0], [], []
+        for i in range(n):
+            nz = np.nonzero(W[i])[0]
+            nz = rng.permutation(nz)                       # rows list their entries in any order
+            col += list(nz); w += list(W[i, nz]); row_ptr.append(len(col))
+        csr = O.Csr(np.array(row_ptr), np.array(col), np.array(w))
+        d, T = 5, 2 * s + 1
+        hp = O.Hyper(lr=1e-2, s=s)
+        x = [rng.standard_normal(d) for _ in range(n)]
+        st_ = zeros_state(x)
+        G = [[rng.standard_normal(d) for _ in range(n)] for _ in range(T + 1)]
+        e0 = O.consensus_error(x)
+        assert O.consensus_error(O.mix_only(x, csr, mode="O64")) <= e0 * (1 + 1e-12)
+        for t in range(1, T + 1):
+            mean_prev = np.mean(st_.x_src, axis=0)
+            U = [O.search_direction(*O.temporary_moments(st_.m_hat[i], st_.v_hat[i], G[t][i], hp), O.t_hat(t, s), hp) for i in range(n)]
+            st_.x_src = O.dadam_step(st_, G[t], csr, t, hp, mode="O64")
+            np.testing.assert_allclose(np.mean(st_.x_src, axis=0), mean_prev - hp.lr * np.mean(U, axis=0), atol=1e-13)
+            if s == 1 or t % s == 0:
+                assert all(np.all(b == 0) for b in st_.b)
+
+    check()
