@@ -608,3 +608,29 @@ def test_buffers_beyond_4_gib_use_64_bit_offsets(mode):
     sim.close()
     del sim, grads
     torch.cuda.empty_cache()
+
+
+def test_random_rectangular_topologies_and_layouts():
+    """Seeded random cases: rows and sources of different counts, random degrees and weights in
+    shuffled order, ragged tensor lists with gaps, every dtype pair, s in 1..3, both kernels."""
+    rng = np.random.default_rng(20241011)
+    for case in range(14):
+        R = int(rng.integers(1, 13))
+        C = int(rng.integers(R, R + 8))
+        row_ptr, col, w = [0], [], []
+        for i in range(R):
+            deg = int(rng.integers(1, min(C, 9) + 1))
+            cols = rng.permutation(C)[:deg]
+            ww = (rng.random(deg) + 0.05).astype(np.float32)
+            ww = (ww / ww.sum(dtype=np.float32)).astype(np.float32)
+            col += list(cols); w += list(ww); row_ptr.append(len(col))
+        t3 = (np.array(row_ptr, np.int32), np.array(col, np.int32), np.array(w, np.float32))
+        shapes = [(f"t{k}", (int(rng.choice([1, 7, 64, 255, 256, 257, 1000, 3333, 5000])),)) for k in range(int(rng.integers(1, 9)))]
+        layout = WL.pack(shapes, align_elems=int(rng.choice([8, 16, 24])))
+        pd, gd = [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32"), ("f32", "bf16")][case % 4]
+        s = int(rng.integers(1, 4))
+        mode = ["tile", "direct"][case % 2]
+        say("case", case, "R", R, "C", C, "nnz", len(col), "d", layout.d, pd, gd, "s", s, mode)
+        H.run_parity(f"random{case}", R, C, layout, H.HyperF32(lr=3e-3, s=s), [t3], lambda t: 0, s + 2, seed=300 + case,
+                     param_dtype=pd, grad_dtype=gd, grad_std=1e-2, flags=B.DADAM_FUSE_ACCUM | MODES[mode],
+                     refresh_extra_sources=True)
