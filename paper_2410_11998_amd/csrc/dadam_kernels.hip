@@ -389,49 +389,83 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
 #pragma unroll
   for (int u = 0; u < UT; ++u) e[u] = tbase + (uint64_t)(u * kWave + lane) * VEC;
 
-  // stage every source buffer's slice of the tile: HBM -> registers -> LDS, once
+  // stage every source buffer's slice of the tile: HBM -> registers -> LDS, once.  With more than
+  // two sources per wavefront, a wavefront issues the loads of up to KB of them before it parks
+  // the first, so that their latencies overlap (+3 % with 64 sources); with one or two, taking
+  // them in turn is faster (3 % in the bfloat16 ring of 8), so both forms are here.
   const int n_cols = (int)a.n_cols;
-  for (int c = wave; c < n_cols; c += W) {
-    const void* src = a.x_src[c];
-    u4 r[UT];
+  if (n_cols > 2 * W) {
+    constexpr int KB = 8 / UT;
+    for (int c0 = wave; c0 < n_cols; c0 += KB * W) {
+      u4 r[KB][UT];
 #pragma unroll
-    for (int u = 0; u < UT; ++u) r[u] = load_raw<XT, MASKED, NT>(src, e[u], lo, hi);
+      for (int k = 0; k < KB; ++k) {
+        const int c = c0 + k * W;
+        if (c < n_cols) {
+          const void* src = a.x_src[c];
 #pragma unroll
-    for (int u = 0; u < UT; ++u) lds[(c * UT + u) * kWave + lane] = r[u];
+          for (int u = 0; u < UT; ++u) r[k][u] = load_raw<XT, MASKED, NT>(src, e[u], lo, hi);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < KB; ++k) {
+        const int c = c0 + k * W;
+        if (c < n_cols) {
+#pragma unroll
+          for (int u = 0; u < UT; ++u) lds[(c * UT + u) * kWave + lane] = r[k][u];
+        }
+      }
+    }
+  } else {
+    for (int c = wave; c < n_cols; c += W) {
+      const void* src = a.x_src[c];
+      u4 r[UT];
+#pragma unroll
+      for (int u = 0; u < UT; ++u) r[u] = load_raw<XT, MASKED, NT>(src, e[u], lo, hi);
+#pragma unroll
+      for (int u = 0; u < UT; ++u) lds[(c * UT + u) * kWave + lane] = r[u];
+    }
   }
   __syncthreads();
 
   if constexpr (PHASE == kMixConsensus) {
     // Consensus error of the sources, sum_c (x_c - mean)^2 per element, as a by-product: the whole
-    // tile is in LDS anyway.  One wavefront per tile (taking turns) does it in one pass on values
-    // shifted by source 0, y_c = x_c - x_0, so that sum y^2 - (sum y)^2 / C does not cancel.
+    // tile is in LDS anyway.  One pass on values shifted by source 0, y_c = x_c - x_0, so that
+    // sum y^2 - (sum y)^2 / C does not cancel.  The work is dealt evenly: each wavefront takes
+    // PER of the tile's 16-byte slots, and its G = 64 / PER lane groups take every G-th source;
+    // the groups' sums of y meet through lane exchanges before they are squared.
     // Elements outside the segment were staged as zeros in every source and add nothing.
-    if (wave == (int)(tile_id % (uint32_t)W)) {
-      const float inv_c = 1.0f / (float)n_cols;
-      float acc = 0.0f;
+    constexpr int PER = UT * kWave / W;
+    constexpr int G = kWave / PER;
+    static_assert(PER >= 1 && PER * W == UT * kWave && G * PER == kWave, "tile does not divide");
+    const int q = wave * PER + (lane % PER);
+    const int grp = lane / PER;
+    float ref[VEC], s1[VEC], s2[VEC];
+    unpack_raw<XT>(lds[q], ref);
 #pragma unroll
-      for (int u = 0; u < UT; ++u) {
-        float ref[VEC], s1[VEC], s2[VEC];
-        unpack_raw<XT>(lds[u * kWave + lane], ref);
+    for (int j = 0; j < VEC; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
+    for (int c = 1 + grp; c < n_cols; c += G) {
+      float xs[VEC];
+      unpack_raw<XT>(lds[c * (UT * kWave) + q], xs);
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
-        for (int c = 1; c < n_cols; ++c) {
-          float xs[VEC];
-          unpack_raw<XT>(lds[(c * UT + u) * kWave + lane], xs);
-#pragma unroll
-          for (int j = 0; j < VEC; ++j) {
-            const float y = xs[j] - ref[j];
-            s1[j] += y;
-            s2[j] = fmaf(y, y, s2[j]);
-          }
-        }
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) acc += s2[j] - s1[j] * s1[j] * inv_c;
+      for (int j = 0; j < VEC; ++j) {
+        const float y = xs[j] - ref[j];
+        s1[j] += y;
+        s2[j] = fmaf(y, y, s2[j]);
       }
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-      if (lane == 0) atomicAdd(a.partials + (tile_id % kConsensusPartials), (double)acc);
     }
+#pragma unroll
+    for (int off = PER; off < kWave; off <<= 1)
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) s1[j] += __shfl_xor(s1[j], off);
+    const float inv_c = grp == 0 ? 1.0f / (float)n_cols : 0.0f;
+    float acc = 0.0f;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc += s2[j] - s1[j] * s1[j] * inv_c;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if (lane == 0)
+      atomicAdd(a.partials + ((tile_id * (uint32_t)W + (uint32_t)wave) % kConsensusPartials), (double)acc);
   }
 
   const int n_rows = (int)a.n_rows;
