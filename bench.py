@@ -81,23 +81,56 @@ def path_bytes_per_replica_param(wl, phase: str, path: str) -> float:
     return (src + px + pg + 8) + acc          # unfused: update-only pass, then the accumulate pass
 
 
-def cpu_baseline(wl, x0_sample, grad_samples, csrs, iters: int):
-    """The CPU oracle as it stands, timed on this host on a bounded sample of the workload."""
+def cpu_baseline(wl, x0_sample, grad_samples, csrs, iters: int, threads: int = 1):
+    """The CPU oracle as it stands, timed on this host on a bounded sample of the workload.
+
+    threads > 1: the sample's coordinates are cut into that many slices and each thread runs the same
+    oracle on its slice (coordinates never interact, so the slices are independent runs)."""
     import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import dadam_oracle as O
     hp = O.Hyper(float(np.float32(wl.lr)), float(np.float32(wl.beta1)), float(np.float32(wl.beta2)),
                  float(np.float32(wl.eps)), wl.s)
     n = x0_sample[0].shape[0]
-    z = lambda: [np.zeros(n) for _ in range(wl.n_rows)]
-    st = O.State([x.copy() for x in x0_sample], z(), z(), z())
     ocsr = [O.Csr(np.asarray(rp), np.asarray(col), np.asarray(w, dtype=np.float64)) for rp, col, w in csrs]
+    cuts = [n * k // threads for k in range(threads + 1)]
+
+    def run_slice(k: int):
+        lo, hi = cuts[k], cuts[k + 1]
+        z = lambda: [np.zeros(hi - lo) for _ in range(wl.n_rows)]
+        st = O.State([x[lo:hi].copy() for x in x0_sample], z(), z(), z())
+        for t in range(1, iters + 1):
+            g = [gi[lo:hi] for gi in grad_samples[(t - 1) % len(grad_samples)]]
+            xn = O.dadam_step(st, g, ocsr[wl.slot_of_step(t)], t, hp, "O32m", wl.param_dtype)
+            for i in range(wl.n_rows):
+                st.x_src[i] = xn[i]
+
     t0 = time.perf_counter()
-    for t in range(1, iters + 1):
-        xn = O.dadam_step(st, grad_samples[(t - 1) % len(grad_samples)], ocsr[wl.slot_of_step(t)], t, hp, "O32m", wl.param_dtype)
-        for i in range(wl.n_rows):
-            st.x_src[i] = xn[i]
+    if threads == 1:
+        run_slice(0)
+    else:
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(run_slice, range(threads)))
     dt = time.perf_counter() - t0
     return wl.n_rows * n * iters / dt, dt
+
+
+def host_cpu():
+    """(model name, logical CPUs this process may run on) of the machine the baseline is timed on."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return model, n
 
 
 def main() -> int:
@@ -120,7 +153,7 @@ def main() -> int:
     ap.add_argument("--span-gib", type=int, default=0, help="arena size for --layout spread (default: free memory minus 12 GiB)")
     ap.add_argument("--scale-div", type=int, default=1, help="divide tensor dimensions (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--repeats", type=int, default=1,
+    ap.add_argument("--repeats", type=int, default=5,
                     help="after the timed region, time that many minus one further regions of the same length and "
                          "report all of them (median and minimum) next to the first, which stays the reported value")
     ap.add_argument("--cpu-sample", type=int, default=None, help="coordinates per row given to the CPU oracle")
@@ -336,10 +369,17 @@ def main() -> int:
         torch.cuda.empty_cache()
         iters = min(wl.steps, max(wl.s + 1, int(1.2e9 // (R * ns))))
         v, dt = cpu_baseline(wl, x0_sample, g_samples, csrs, iters)
+        model, logical = host_cpu()
+        # worker pools on this machine are sized to its share of the host: 16 threads at most
+        threads = max(1, min(16, logical, int(os.environ.get("OMP_NUM_THREADS", "16") or 16)))
+        vp, dtp = cpu_baseline(wl, x0_sample, g_samples, csrs, iters, threads=threads)
         out["cpu_baseline"] = {
             "value": v, "unit": "replica-params/s", "cores": 1, "kind": "oracle",
             "sample": f"first {ns} coordinates of all {R} rows, {iters} iterations of the same workload "
                       f"({dt:.1f} s of single-threaded NumPy float64)",
+            "all_cores": {"value": vp, "unit": "replica-params/s", "cores": threads,
+                          "how": f"the same sample cut into {threads} coordinate slices, one thread each ({dtp:.1f} s)"},
+            "host_cpu": model, "host_logical_cpus": logical,
         }
     print(json.dumps(out), flush=True)
     return 0
