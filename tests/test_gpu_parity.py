@@ -634,3 +634,46 @@ def test_random_rectangular_topologies_and_layouts():
         H.run_parity(f"random{case}", R, C, layout, H.HyperF32(lr=3e-3, s=s), [t3], lambda t: 0, s + 2, seed=300 + case,
                      param_dtype=pd, grad_dtype=gd, grad_std=1e-2, flags=B.DADAM_FUSE_ACCUM | MODES[mode],
                      refresh_extra_sources=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_free_running_distance_from_the_unrounded_iteration(dtype):
+    """The device run against the iteration carried in double precision with nothing rounded (not the
+    oracle convention that rounds stored state): after T iterations the distance is reported and must
+    stay below T times the per-iteration tolerance times the largest magnitude the element's terms
+    have had so far - rounding differences add up at most linearly, the mixing never amplifies
+    them, and what was committed while an element was large stays when it shrinks."""
+    say("case", dtype)
+    n, d, s, T = 8, 1 << 15, 2, 40
+    layout = flat_layout(d)
+    hp = H.HyperF32(lr=1e-3, s=s)
+    ohp = hp.oracle()
+    t3 = WL.ring(n)
+    csr = H.csr_oracle(t3)
+    sim = H.GpuSim(n, n, layout, hp, [t3], dtype, "f32")
+    dev = torch.device(DEV)
+    for c in range(n):
+        sim.x_src[c].copy_(H.to_device(WL.normal_np(9100 + c, layout.d, 0.02), dtype, dev))
+    exact = sim.snapshot()                      # starts from the stored (rounded) initial parameters
+    worst = 0.0
+    smax = [np.zeros(layout.d) for _ in range(n)]
+    for t in range(1, T + 1):
+        g64 = [WL.normal_np(9200 + t * 16 + i, layout.d, 1e-2).astype(np.float32).astype(np.float64) for i in range(n)]
+        grads = [H.to_device(g, "f32", dev) for g in g64]
+        prev = O.State(list(exact.x_src), list(exact.m_hat), list(exact.v_hat), list(exact.b))
+        scale = O.magnitude_scale(prev, g64, csr, t, ohp)
+        ex = O.dadam_step(exact, g64, csr, t, ohp, "O64", dtype)
+        for i in range(n):
+            exact.x_src[i] = ex[i]
+        sim.step(grads, t)
+        torch.cuda.synchronize()
+        gx = sim.outputs()[0]
+        for i in range(n):            # a mixed element inherits from its neighbours: take the rows' common maximum
+            smax[i] = np.maximum(smax[i], scale[i])
+        common = np.max(np.stack(smax), axis=0)
+        ratio = max(float((np.abs(gx[i] - ex[i]) / common).max()) for i in range(n))
+        worst = max(worst, ratio / (t * H.H_RTOL(dtype)))
+        sim.swap()
+    say(f"{dtype}: after {T} iterations max |x - exact| = {ratio:.3e} x largest term magnitude so far; worst ratio to t x tolerance {worst:.3f}")
+    assert worst <= 1.0
+    sim.close()
