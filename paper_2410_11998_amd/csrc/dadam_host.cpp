@@ -448,6 +448,10 @@ int dadam_init(const dadam_config* cfg, dadam_handle** out) {
     h->mix_shape.ut = 2;
     h->mix_shape.waves = 4;
   }
+  h->mix_shape.ut = env_int("DADAM_MIX_UT", h->mix_shape.ut);
+  h->mix_shape.waves = env_int("DADAM_MIX_WAVES", h->mix_shape.waves);
+  if (!tile_shape_supported(h->mix_shape) || cfg->n_cols * (uint32_t)h->mix_shape.ut * kWave * 16u > 65536u)
+    h->mix_shape = shape;
   h->mix_tile_elems = (uint32_t)(kWave * h->vec * h->mix_shape.ut);
   h->mix_lds_bytes = cfg->n_cols * (uint32_t)h->mix_shape.ut * kWave * 16u;
   int rc = plan(h);

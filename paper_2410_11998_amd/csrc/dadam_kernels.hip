@@ -273,6 +273,32 @@ __device__ __forceinline__ RowList load_row_list(const StepArgs& a, int row, int
   return r;
 }
 
+// All of row_ptr in two registers per lane (lane l holds row_ptr[l] and row_ptr[l + 1]; at most 64
+// rows), so that a wavefront that walks several rows finds each row's bounds with two lane reads
+// instead of a load it would have to wait for behind its own earlier stores.
+struct RowPtrs {
+  int32_t lo, hi;
+};
+
+__device__ __forceinline__ RowPtrs load_row_ptrs(const StepArgs& a, int lane) {
+  const int r = lane < (int)a.n_rows ? lane : 0;
+  RowPtrs p;
+  p.lo = a.row_ptr[r];
+  p.hi = a.row_ptr[r + 1];
+  return p;
+}
+
+__device__ __forceinline__ RowList load_row_list(const StepArgs& a, const RowPtrs& p, int row, int lane) {
+  const int k0 = __builtin_amdgcn_readlane(p.lo, row);
+  const int k1 = __builtin_amdgcn_readlane(p.hi, row);
+  RowList r;
+  r.deg = k1 - k0;  // host guarantees 1 <= deg <= n_cols <= 64
+  const int idx = k0 + (lane < r.deg ? lane : 0);
+  r.col_v = a.col[idx];
+  r.w_v = a.w[idx];
+  return r;
+}
+
 __device__ __forceinline__ int list_col(const RowList& r, int k) {
   return __builtin_amdgcn_readlane(r.col_v, k);
 }
@@ -389,6 +415,9 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
 #pragma unroll
   for (int u = 0; u < UT; ++u) e[u] = tbase + (uint64_t)(u * kWave + lane) * VEC;
 
+  const int n_rows = (int)a.n_rows;
+  const RowPtrs rp = load_row_ptrs(a, lane);
+
   // stage every source buffer's slice of the tile: HBM -> registers -> LDS, once.  With more than
   // two sources per wavefront, a wavefront issues the loads of up to KB of them before it parks
   // the first, so that their latencies overlap (+3 % with 64 sources); with one or two, taking
@@ -426,6 +455,8 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
       for (int u = 0; u < UT; ++u) lds[(c * UT + u) * kWave + lane] = r[u];
     }
   }
+  // the first row's neighbour list travels while the group meets at the barrier
+  RowList rl_next = load_row_list(a, rp, wave < n_rows ? wave : 0, lane);
   __syncthreads();
 
   if constexpr (PHASE == kMixConsensus) {
@@ -468,11 +499,13 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
       atomicAdd(a.partials + ((tile_id * (uint32_t)W + (uint32_t)wave) % kConsensusPartials), (double)acc);
   }
 
-  const int n_rows = (int)a.n_rows;
-  // (Issuing the next row's loads before the current row is finished was measured and changes
+  // Each row's list is fetched one row ahead, so that no row waits for a load issued behind the
+  // previous row's stores (memory operations of a wavefront retire in order).
+  // (Issuing the next row's gradient and state loads early as well was measured and changes
   // nothing: with 8-32 wavefronts per CU in flight the memory system, not latency, is the limit.)
   for (int i = wave; i < n_rows; i += W) {
-    RowList rl = load_row_list(a, i, lane);
+    const RowList rl = rl_next;
+    rl_next = load_row_list(a, rp, i + W < n_rows ? i + W : i, lane);
     float g[UT][VEC], mh[UT][VEC], vh[UT][VEC], b[UT][VEC];
     load_row_inputs<GT, PHASE, VEC, UT, MASKED, NT>(a, i, e, lo, hi, g, mh, vh, b);
     finish_row<XT, PHASE, VEC, UT, MASKED, NT>(a, lds, i, rl, e, lo, hi, wd, lane, g, mh, vh, b);
