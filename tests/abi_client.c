@@ -1,0 +1,81 @@
+/* A client of the library written in C99: shows that the header is plain C and that the calls that
+ * need no GPU (host-only handle) behave the same from C as through the Python binding.
+ * Prints "key value" lines that the test compares with the binding's answers. */
+#include <stdio.h>
+#include <string.h>
+
+#include "dadam.h"
+
+int main(void) {
+  dadam_tensor_desc tensors[3];
+  uint64_t numel[3] = {1000, 24, 5001};
+  uint64_t offsets[3];
+  uint64_t d = 0;
+  dadam_config cfg;
+  dadam_handle* h = NULL;
+  dadam_plan_info info;
+  /* ring of 4, weights 1/3 */
+  int32_t row_ptr[5] = {0, 3, 6, 9, 12};
+  int32_t col[12] = {3, 0, 1, 0, 1, 2, 1, 2, 3, 2, 3, 0};
+  float w[12];
+  uint32_t warn = 77u;
+  int rc, i;
+
+  rc = dadam_pack_offsets(numel, 3u, 8u, offsets, &d);
+  printf("pack_rc %d\n", rc);
+  printf("d %llu\n", (unsigned long long)d);
+  for (i = 0; i < 3; ++i) {
+    tensors[i].offset_elems = offsets[i];
+    tensors[i].numel = numel[i];
+    tensors[i].weight_decay = 0.0f;
+    tensors[i].flags = 0u;
+    printf("offset%d %llu\n", i, (unsigned long long)offsets[i]);
+  }
+  memset(&cfg, 0, sizeof cfg);
+  cfg.abi_version = DADAM_ABI_VERSION;
+  cfg.n_rows = 4u;
+  cfg.n_cols = 4u;
+  cfg.d = d;
+  cfg.n_tensors = 3u;
+  cfg.tensors = tensors;
+  cfg.param_dtype = DADAM_F32;
+  cfg.grad_dtype = DADAM_F32;
+  cfg.lr = 1e-3f;
+  cfg.beta1 = 0.9f;
+  cfg.beta2 = 0.999f;
+  cfg.eps = 1e-8f;
+  cfg.accum_s = 2u;
+  cfg.beta_vhat = -1.0f;
+  cfg.device = DADAM_DEVICE_NONE;
+  rc = dadam_init(&cfg, &h);
+  printf("init_rc %d\n", rc);
+  if (rc != DADAM_OK || h == NULL) return 1;
+
+  for (i = 0; i < 12; ++i) w[i] = 1.0f / 3.0f;
+  rc = dadam_set_topology(h, 0u, row_ptr, col, w, &warn);
+  printf("topology_rc %d\n", rc);
+  printf("warn %u\n", warn);
+
+  col[1] = 9; /* out of range */
+  rc = dadam_set_topology(h, 1u, row_ptr, col, w, &warn);
+  printf("bad_topology_rc %d\n", rc);
+  printf("bad_topology_has_message %d\n", dadam_last_error(h) != NULL && dadam_last_error(h)[0] != '\0');
+
+  rc = dadam_get_plan_info(h, &info);
+  printf("plan_rc %d\n", rc);
+  printf("n_segments %u\n", info.n_segments);
+  printf("tile_elems %u\n", info.tile_elems);
+  printf("n_tiles_tile %llu\n", (unsigned long long)info.n_tiles_tile);
+  printf("n_tiles_direct %llu\n", (unsigned long long)info.n_tiles_direct);
+  printf("lds_bytes_tile %u\n", info.lds_bytes_tile);
+
+  /* a host-only handle cannot launch: an error code, not a crash */
+  rc = dadam_mix(h, 0u, 0u, NULL);
+  printf("mix_on_host_only_handle_rc %d\n", rc);
+  rc = dadam_set_lr(h, 5e-4f);
+  printf("set_lr_rc %d\n", rc);
+  dadam_destroy(h);
+  dadam_destroy(NULL);
+  printf("done 1\n");
+  return 0;
+}

@@ -350,3 +350,37 @@ def test_planner_against_python_model_random_layouts():
         B.dadam_destroy(h)
 
     check()
+
+
+def test_c99_client_compiles_links_and_agrees_with_the_binding(tmp_path):
+    """The header is plain C (gcc -std=c99 -pedantic -Werror), a C program links against the library,
+    and what it is told (packing, plan, status codes) is what the Python binding is told."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    libdir = os.path.dirname(B.LIB_PATH)
+    exe = str(tmp_path / "abi_client")
+    rocm_lib = "/opt/rocm/lib"
+    cmd = [gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "abi_client.c"), "-o", exe, "-L", libdir, "-ldadam",
+           f"-Wl,-rpath,{libdir}", f"-Wl,-rpath,{rocm_lib}", f"-Wl,-rpath-link,{rocm_lib}"]
+    subprocess.run(cmd, check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
+    got = dict(line.split(" ", 1) for line in out.strip().splitlines())
+
+    numel = [1000, 24, 5001]
+    offsets, d = B.dadam_pack_offsets(numel, 8)
+    assert int(got["pack_rc"]) == 0 and int(got["d"]) == d
+    assert [int(got[f"offset{i}"]) for i in range(3)] == [int(o) for o in offsets]
+    h = B.dadam_init(4, 4, d, offsets, numel, accum_s=2, device=B.DADAM_DEVICE_NONE)
+    info = B.dadam_get_plan_info(h)
+    B.dadam_destroy(h)
+    assert int(got["init_rc"]) == 0 and int(got["topology_rc"]) == 0 and int(got["warn"]) == 0
+    assert int(got["bad_topology_rc"]) == B.DADAM_ETOPO and int(got["bad_topology_has_message"]) == 1
+    assert int(got["plan_rc"]) == 0
+    for key in ("n_segments", "tile_elems", "n_tiles_tile", "n_tiles_direct", "lds_bytes_tile"):
+        assert int(got[key]) == int(getattr(info, key)), key
+    assert int(got["mix_on_host_only_handle_rc"]) == B.DADAM_ESTATE
+    assert int(got["set_lr_rc"]) == 0 and int(got["done"]) == 1
