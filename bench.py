@@ -147,12 +147,17 @@ def main() -> int:
                          "accumulation followed by dadam_accumulate; mix: dadam_mix only; accumulate: dadam_accumulate only; "
                          "buckets: the fused step issued tensor range by tensor range (--bucket-mb)")
     ap.add_argument("--bucket-mb", type=float, default=25.0, help="target bucket size for --path buckets")
+    ap.add_argument("--bucket-streams", type=int, default=1,
+                    help="--path buckets: deal the buckets of a step over that many streams (1: the step's own stream)")
     ap.add_argument("--layout", choices=["spread", "packed"], default="spread",
                     help="spread: one arena over most of the free HBM, buffers at equal distances (faster, see "
                          "paper_2410_11998_amd/arena.py); packed: one ordinary allocation per buffer")
     ap.add_argument("--span-gib", type=int, default=0, help="arena size for --layout spread (default: free memory minus 12 GiB)")
     ap.add_argument("--scale-div", type=int, default=1, help="divide tensor dimensions (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="record a whole number of accumulation loops in a HIP graph once and time its replays "
+                         "(launch gaps of --path buckets); per-launch times then are replay averages")
     ap.add_argument("--repeats", type=int, default=5,
                     help="after the timed region, time that many minus one further regions of the same length and "
                          "report all of them (median and minimum) next to the first, which stays the reported value")
@@ -243,7 +248,7 @@ def main() -> int:
         x0_sample = [x[:ns].to(torch.float64).cpu().numpy() for x in x_src]
         g_samples = [[g[:ns].to(torch.float64).cpu().numpy() for g in gs] for gs in pool]
 
-    stream = B.current_stream()
+    stream = None      # read at call time: a graph capture changes torch's current stream
 
     # tensor ranges of about --bucket-mb of parameters each, in layout order (the granularity at which
     # the paper's implementation updates and communicates)
@@ -258,8 +263,10 @@ def main() -> int:
                 start, cur = k + 1, 0
     mode_flags = flags & ~B.DADAM_FUSE_ACCUM
     consensus_out = torch.zeros(1, dtype=torch.float64, device=dev)
+    side = [torch.cuda.Stream(device=dev) for _ in range(args.bucket_streams)] if args.bucket_streams > 1 else []
 
     def one_step(t: int):
+        stream = B.current_stream()
         g = pool[t % len(pool)]
         slot = wl.slot_of_step(t)
         if args.path == "fused":
@@ -273,9 +280,23 @@ def main() -> int:
             B.dadam_mix_consensus(h, slot, consensus_out, mode_flags, stream)
         elif args.path == "accumulate":
             B.dadam_accumulate(h, g, t, stream)
-        else:
+        elif len(side) <= 1:
             for tb, te in buckets:
                 B.dadam_gossip_step_range(h, slot, g, t, flags, tb, te, stream)
+        else:
+            # buckets dealt over side streams (default priority) so that one bucket's drain overlaps the next
+            # one's ramp; the step's stream forks to them and joins them again
+            main = torch.cuda.current_stream()
+            fork = torch.cuda.Event()
+            fork.record(main)
+            for st in side:
+                st.wait_event(fork)
+            for k, (tb, te) in enumerate(buckets):
+                B.dadam_gossip_step_range(h, slot, g, t, flags, tb, te, side[k % len(side)].cuda_stream)
+            for st in side:
+                join = torch.cuda.Event()
+                join.record(st)
+                main.wait_event(join)
         if not inplace and args.path != "accumulate":
             B.dadam_swap_x(h)
 
@@ -285,17 +306,42 @@ def main() -> int:
         one_step(t)
     torch.cuda.synchronize()
 
+    graph, L = None, 1
+    if args.graph:
+        # One replayable graph of L consecutive iterations: a whole number of accumulation loops, of
+        # the topology schedule's periods and of buffer exchanges, so that a replay leaves the handle as
+        # it found it.  The iteration numbers (hence the bias corrections) are those of the capture.
+        L = wl.s
+        while (not inplace and L % 2) or L % wl.n_slots():
+            L += wl.s
+        K = max(L, K // L * L)
+        t_graph = t
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for j in range(L):
+                one_step(t_graph + 1 + j)
+        graph.replay()                      # one untimed replay
+        torch.cuda.synchronize()
+
     ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
     ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
     phases = []
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
-    for k in range(K):
-        t += 1
-        phases.append(phase_of(t, wl.s))
-        ev0[k].record()
-        one_step(t)
-        ev1[k].record()
+    if graph is None:
+        for k in range(K):
+            t += 1
+            phases.append(phase_of(t, wl.s))
+            ev0[k].record()
+            one_step(t)
+            ev1[k].record()
+    else:
+        for r in range(K // L):
+            phases += [phase_of(t_graph + 1 + j, wl.s) for j in range(L)]
+            ev0[r].record()
+            graph.replay()
+            ev1[r].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_begin
 
@@ -303,13 +349,21 @@ def main() -> int:
     for _ in range(max(0, args.repeats - 1)):
         torch.cuda.synchronize()
         r0 = time.perf_counter()
-        for k in range(K):
-            t += 1
-            one_step(t)
+        if graph is None:
+            for k in range(K):
+                t += 1
+                one_step(t)
+        else:
+            for r in range(K // L):
+                graph.replay()
         torch.cuda.synchronize()
         region_ms.append((time.perf_counter() - r0) / K * 1e3)
 
-    kernel_ms = [ev0[k].elapsed_time(ev1[k]) for k in range(K)]
+    if graph is None:
+        kernel_ms = [ev0[k].elapsed_time(ev1[k]) for k in range(K)]
+    else:
+        # inside a graph single launches cannot be bracketed: every iteration of a replay gets the replay's average
+        kernel_ms = [ev0[r].elapsed_time(ev1[r]) / L for r in range(K // L) for _ in range(L)]
     avg_kernel_s = sum(kernel_ms) / K / 1e3
     replica_params = R * d
     value = replica_params * K / elapsed
@@ -343,6 +397,8 @@ def main() -> int:
             "launches_per_step": (len(buckets) if args.path == "buckets" else 2 if args.path == "unfused" else 1), "x_buffers": "in-place" if inplace else "ping-pong",
             "hbm_layout": args.layout if span_gib is None else f"spread over {span_gib:.0f} GiB",
             "grad_pool": len(pool),
+            "issue": "eager" if graph is None else f"graph of {L} iterations, replayed",
+            "bucket_streams": max(1, len(side)) if args.path == "buckets" else None,
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK_BYTES_PER_S / 1e9, "unit": "GB/s",

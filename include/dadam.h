@@ -175,7 +175,11 @@ int dadam_gossip_step(dadam_handle* h, uint32_t slot, const void* const* grads, 
                       uint32_t flags, void* hip_stream);
 
 /* The same restricted to tensors [tensor_begin, tensor_end) of the layout (a "bucket" in the
- * sense of section 2.1, where parameters are updated and communicated bucket by bucket). */
+ * sense of section 2.1, where parameters are updated and communicated bucket by bucket).
+ * Disjoint ranges of one iteration touch disjoint elements, also where two ranges meet inside one
+ * tile and when parameters are updated in place, so they may run on different streams at the same
+ * time (issued from one host thread); a range of iteration t + 1 must be ordered after the same
+ * range of iteration t.  An empty range is a successful no-op. */
 int dadam_gossip_step_range(dadam_handle* h, uint32_t slot, const void* const* grads, uint64_t t,
                             uint32_t flags, uint32_t tensor_begin, uint32_t tensor_end,
                             void* hip_stream);

@@ -677,3 +677,93 @@ def test_free_running_distance_from_the_unrounded_iteration(dtype):
     say(f"{dtype}: after {T} iterations max |x - exact| = {ratio:.3e} x largest term magnitude so far; worst ratio to t x tolerance {worst:.3f}")
     assert worst <= 1.0
     sim.close()
+
+
+def test_step_sequence_can_be_captured_in_a_graph_and_replayed():
+    """Callers that capture their loop: the library's calls are kernel launches only (no allocation, no
+    synchronisation, no memset), so an accumulation loop and a mixing pass with the consensus error
+    can be recorded once and replayed.  Every replay (with eager work and synchronisations between
+    them) must reproduce the eager results bit for bit."""
+    n, s = 8, 2
+    layout = WL.pack(WL.odd_shapes())
+    d = layout.d
+    hp = H.HyperF32(lr=2e-3, s=s)
+    t3 = WL.ring(n)
+    sim = H.GpuSim(n, n, layout, hp, [t3], "f32", "f32")
+    dev = torch.device(DEV)
+    x0 = [H.to_device(WL.normal_np(7700 + c, d, 0.02), "f32", dev) for c in range(n)]
+    grads = [[H.to_device(WL.normal_np(7800 + t * 16 + i, d, 1e-2), "f32", dev) for i in range(n)] for t in range(s)]
+    cons = torch.zeros(1, dtype=torch.float64, device=dev)
+    state = sim.x_src + sim.x_dst + sim.m + sim.v + sim.b
+
+    def reset():
+        for t_ in state:
+            t_.zero_()
+        for c in range(n):
+            sim.x_src[c].copy_(x0[c])
+        cons.zero_()
+
+    def sequence():
+        for t in range(1, s + 1):
+            sim.step(grads[t - 1], t)
+            sim.swap()
+        sim.mix_consensus(cons)          # reads the loop's result, writes the other buffer set
+        # an even number of exchanges: the handle's tables are back where they were
+
+    def results():
+        torch.cuda.synchronize()
+        return [t_.clone() for t_ in state] + [cons.clone()]
+
+    assert s % 2 == 0
+    reset()
+    sequence()
+    eager = results()
+
+    reset()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sequence()
+    for replay in range(3):
+        reset()
+        junk = torch.randn(1 << 16, device=dev).sum()      # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        got = results()
+        for k, (a, b) in enumerate(zip(eager, got)):
+            assert torch.equal(a, b), f"replay {replay}: buffer {k} differs from the eager run"
+        del junk
+    say("consensus error after the captured sequence:", float(cons.item()))
+    sim.close()
+
+
+@pytest.mark.parametrize("mode,inplace", [("tile", False), ("tile", True), ("direct", False)])
+def test_buckets_on_concurrent_streams_give_the_bits_of_the_whole_step(mode, inplace):
+    """Tensor ranges are independent work: issued on two streams at once (ranges that share a tile at
+    their ragged edges included, and with the parameters updated in place) they give the whole step."""
+    say("case", mode, inplace)
+    n = 6
+    layout = WL.pack(WL.odd_shapes() + [("big", (70001,)), ("tail", (333,))])
+    hp = H.HyperF32(s=2)
+    nt = len(layout.names)
+    t3 = WL.ring(n)
+    a = H.GpuSim(n, n, layout, hp, [t3])
+    b = H.GpuSim(n, n, layout, hp, [t3], inplace=inplace)
+    for c in range(n):
+        x0 = H.to_device(WL.normal_np(8500 + c, layout.d, 0.02), "f32", DEV)
+        a.x_src[c].copy_(x0); b.x_src[c].copy_(x0)
+    side = [torch.cuda.Stream(device=DEV), torch.cuda.Stream(device=DEV)]
+    valid = torch.from_numpy(H.valid_mask(layout)).to(DEV)
+    cuts = [0, 1, 2, 5, nt - 2, nt - 1, nt]
+    for t in (1, 2, 3, 4):
+        grads = [H.to_device(WL.normal_np(8600 + t * 8 + i, layout.d, 1e-2), "f32", DEV) for i in range(n)]
+        a.step(grads, t, 0, B.DADAM_FUSE_ACCUM | MODES[mode])
+        torch.cuda.synchronize()                      # inputs are ready before the side streams start
+        for k in range(len(cuts) - 1):
+            B.dadam_gossip_step_range(b.h, 0, grads, t, B.DADAM_FUSE_ACCUM | MODES[mode], cuts[k], cuts[k + 1],
+                                      side[k % 2].cuda_stream)
+        torch.cuda.synchronize()
+        for u, v in zip(a.x_dst + a.m + a.v + a.b, b.x_dst + b.m + b.v + b.b):
+            assert torch.equal(u[valid], v[valid])     # (padding differs by construction when b works in place)
+        a.swap(); b.swap()
+    a.close(); b.close()
