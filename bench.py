@@ -149,6 +149,11 @@ def main() -> int:
     ap.add_argument("--bucket-mb", type=float, default=25.0, help="target bucket size for --path buckets")
     ap.add_argument("--bucket-streams", type=int, default=1,
                     help="--path buckets: deal the buckets of a step over that many streams (1: the step's own stream)")
+    ap.add_argument("--standin-backward", type=int, default=0,
+                    help="--path buckets: before each bucket's update run an N x N bfloat16 matmul on the step's stream as a "
+                         "stand-in for that bucket's backward pass; with --bucket-streams >= 2 the updates go to side "
+                         "streams and overlap the next stand-in (the value then is not the benchmark's metric)")
+    ap.add_argument("--standin-only", action="store_true", help="with --standin-backward: skip the updates (the stand-in alone)")
     ap.add_argument("--layout", choices=["spread", "packed"], default="spread",
                     help="spread: one arena over most of the free HBM, buffers at equal distances (faster, see "
                          "paper_2410_11998_amd/arena.py); packed: one ordinary allocation per buffer")
@@ -264,6 +269,10 @@ def main() -> int:
     mode_flags = flags & ~B.DADAM_FUSE_ACCUM
     consensus_out = torch.zeros(1, dtype=torch.float64, device=dev)
     side = [torch.cuda.Stream(device=dev) for _ in range(args.bucket_streams)] if args.bucket_streams > 1 else []
+    standin = standin_out = None
+    if args.standin_backward > 0 and args.path == "buckets":
+        standin = torch.randn(args.standin_backward, args.standin_backward, device=dev, dtype=torch.bfloat16)
+        standin_out = torch.empty_like(standin)
 
     def one_step(t: int):
         stream = B.current_stream()
@@ -280,6 +289,25 @@ def main() -> int:
             B.dadam_mix_consensus(h, slot, consensus_out, mode_flags, stream)
         elif args.path == "accumulate":
             B.dadam_accumulate(h, g, t, stream)
+        elif standin is not None:
+            # the single-GPU analogue of the paper's schedule: a stand-in "backward" of bucket k on the step's
+            # stream, the bucket's update behind it - on the same stream, or on a side stream so that it runs
+            # beside the stand-in of bucket k + 1
+            main = torch.cuda.current_stream()
+            for k, (tb, te) in enumerate(buckets):
+                torch.matmul(standin, standin, out=standin_out)
+                if args.standin_only:
+                    continue
+                if side:
+                    st = side[k % len(side)]
+                    ev = torch.cuda.Event()
+                    ev.record(main)
+                    st.wait_event(ev)
+                    B.dadam_gossip_step_range(h, slot, g, t, flags, tb, te, st.cuda_stream)
+                else:
+                    B.dadam_gossip_step_range(h, slot, g, t, flags, tb, te, stream)
+            for st in side:
+                main.wait_stream(st)
         elif len(side) <= 1:
             for tb, te in buckets:
                 B.dadam_gossip_step_range(h, slot, g, t, flags, tb, te, stream)
@@ -399,6 +427,7 @@ def main() -> int:
             "grad_pool": len(pool),
             "issue": "eager" if graph is None else f"graph of {L} iterations, replayed",
             "bucket_streams": max(1, len(side)) if args.path == "buckets" else None,
+            "standin_backward": (f"{args.standin_backward}^3 bf16 matmul per bucket" + (" only" if args.standin_only else "")) if standin is not None else None,
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK_BYTES_PER_S / 1e9, "unit": "GB/s",
