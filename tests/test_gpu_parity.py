@@ -767,3 +767,36 @@ def test_buckets_on_concurrent_streams_give_the_bits_of_the_whole_step(mode, inp
             assert torch.equal(u[valid], v[valid])     # (padding differs by construction when b works in place)
         a.swap(); b.swap()
     a.close(); b.close()
+
+
+def test_gossip_rounds_in_place_and_ring_contraction_on_the_device():
+    """Repeated mixing x <- W x (the gossip of the consensus lemma with zero direction) on a ring of
+    four with weights 1/3: in-place mixing gives the bits of ping-pong mixing, and the consensus error
+    the device reports falls by the square of the second eigenvalue, 1/9, every round."""
+    n = 4
+    layout = WL.pack(WL.odd_shapes() + [("big", (50001,))])
+    t3 = WL.ring(n)
+    hp = H.HyperF32(s=1)
+    a = H.GpuSim(n, n, layout, hp, [t3])
+    b = H.GpuSim(n, n, layout, hp, [t3], inplace=True)
+    valid = torch.from_numpy(H.valid_mask(layout)).to(DEV)
+    for c in range(n):
+        x0 = H.to_device(WL.normal_np(8800 + c, layout.d, 1.0), "f32", DEV)
+        x0[~valid] = 0.0                      # padding takes no part; keep it out of the device's sum
+        a.x_src[c].copy_(x0); b.x_src[c].copy_(x0)
+    ca = torch.zeros(1, dtype=torch.float64, device=DEV)
+    cb = torch.zeros(1, dtype=torch.float64, device=DEV)
+    errs = []
+    for r in range(6):
+        a.mix_consensus(ca, 0, B.DADAM_FORCE_TILE)
+        b.mix_consensus(cb, 0, B.DADAM_FORCE_TILE)
+        torch.cuda.synchronize()
+        assert float(ca.item()) == float(cb.item())
+        for u, v in zip(a.x_dst, b.x_dst):
+            assert torch.equal(u[valid], v[valid])
+        errs.append(float(ca.item()))          # consensus error of the round's sources
+        a.swap()
+    say("consensus errors:", errs)
+    for e0, e1 in zip(errs, errs[1:]):
+        assert abs(e1 / e0 - 1.0 / 9.0) < 1e-5 * (1.0 / 9.0) * 10
+    a.close(); b.close()
