@@ -9,6 +9,11 @@ zero moments) are resident in HBM before the timed region starts.  Prints ONE JS
 
 The default workload is the benchmark's configuration 2 (16 replicas, static exponential graph,
 GPT-2-small tensor shapes, float32, s = 4); --config selects 1..5.
+
+Other measurements share the set-up (none of them is the benchmark's value): --path selects another
+call sequence (unfused, mix, mix_consensus, accumulate, buckets), --bucket-streams and
+--standin-backward shape the bucket sequence, --graph replays a recorded HIP graph, --layout packed
+uses one ordinary allocation per buffer, --mode forces a kernel.  See --help.
 """
 
 from __future__ import annotations

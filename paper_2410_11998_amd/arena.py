@@ -29,7 +29,15 @@ class SpreadArena:
             free, _total = torch.cuda.mem_get_info(self.device)
             span_bytes = max(packed, free - keep_free_bytes)
         span_bytes = max(int(span_bytes), packed)
-        self.storage = torch.empty(span_bytes + unit, dtype=torch.uint8, device=self.device)
+        while True:
+            try:
+                self.storage = torch.empty(span_bytes + unit, dtype=torch.uint8, device=self.device)
+                break
+            except torch.OutOfMemoryError:
+                # free memory is not always one contiguous range: settle for a smaller span
+                if span_bytes == packed:
+                    raise
+                span_bytes = max(packed, span_bytes - (8 << 30))
         self.base_offset = (-self.storage.data_ptr()) % unit            # start on a 2 MiB boundary
         self.span_bytes = span_bytes
         self.offsets = B.dadam_spread_offsets(nbytes, span_bytes)
