@@ -159,10 +159,16 @@ def main() -> int:
                          "stand-in for that bucket's backward pass; with --bucket-streams >= 2 the updates go to side "
                          "streams and overlap the next stand-in (the value then is not the benchmark's metric)")
     ap.add_argument("--standin-only", action="store_true", help="with --standin-backward: skip the updates (the stand-in alone)")
-    ap.add_argument("--layout", choices=["spread", "packed"], default="spread",
-                    help="spread: one arena over most of the free HBM, buffers at equal distances (faster, see "
-                         "paper_2410_11998_amd/arena.py); packed: one ordinary allocation per buffer")
+    ap.add_argument("--layout", choices=["spread", "whole", "packed"], default="spread",
+                    help="spread: one arena over most of the free HBM, buffers dealt alternately over two regions either "
+                         "side of the boundary between the first two thirds of the memory (fastest, see "
+                         "paper_2410_11998_amd/arena.py); whole: the same arena, buffers at equal distances over all "
+                         "of it; packed: one ordinary allocation per buffer")
     ap.add_argument("--span-gib", type=int, default=0, help="arena size for --layout spread (default: free memory minus 12 GiB)")
+    ap.add_argument("--window-gib", type=int, nargs=2, default=None, metavar=("LO", "HI"),
+                    help="--layout spread: use only [LO, HI) GiB of the arena")
+    ap.add_argument("--regions-gib", type=int, nargs="+", default=None, metavar="LO HI",
+                    help="--layout spread: deal the buffers round-robin over the windows [LO, HI) GiB of the arena")
     ap.add_argument("--scale-div", type=int, default=1, help="divide tensor dimensions (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -209,15 +215,24 @@ def main() -> int:
     kinds = [("x_src", pdt)] * C + ([] if inplace else [("x_dst", pdt)] * R) + [("m", torch.float32)] * R + \
             [("v", torch.float32)] * R + ([("b", torch.float32)] * R if wl.s > 1 else []) + [("g", gdt)] * (R * n_pool)
     esize = {torch.float32: 4, torch.bfloat16: 2}
-    if args.layout == "spread":
+    if args.layout in ("spread", "whole"):
         from paper_2410_11998_amd.arena import SpreadArena
         arena = SpreadArena([d * esize[dt] for _, dt in kinds], dev,
-                            span_bytes=(args.span_gib << 30) if args.span_gib else None)
+                            span_bytes=(args.span_gib << 30) if args.span_gib else None,
+                            window=[g << 30 for g in args.window_gib] if args.window_gib else None,
+                            regions=[(args.regions_gib[2 * r] << 30, args.regions_gib[2 * r + 1] << 30)
+                                     for r in range(len(args.regions_gib) // 2)] if args.regions_gib else None,
+                            default_regions=(args.layout == "spread"))
         bufs = arena.views([dt for _, dt in kinds])
         span_gib = arena.span_bytes / 2 ** 30
+        gib = lambda v: f"{v / 2 ** 30:.0f}"
+        used = sorted({(lo, hi) for lo, hi in getattr(arena, "regions_used", [])})
+        hbm_layout = (f"{arena.policy}: " + " + ".join(f"[{gib(lo)}, {gib(hi)})" for lo, hi in used) +
+                      f" GiB of a {span_gib:.0f} GiB allocation")
     else:
         bufs = [torch.empty(d, dtype=dt, device=dev) for _, dt in kinds]
         span_gib = None
+        hbm_layout = "packed: one allocation per buffer"
     take = lambda name: [b for (k, _), b in zip(kinds, bufs) if k == name]
     x_src = take("x_src")
     x_dst = x_src[:R] if inplace else take("x_dst")
@@ -428,7 +443,7 @@ def main() -> int:
             "workload": wl.name, "param_dtype": wl.param_dtype, "grad_dtype": wl.grad_dtype, "state_dtype": "f32", "n_rows": R, "n_sources": C, "d": d, "tensors": len(layout.names), "topology": wl.topology,
             "accum_s": wl.s, "kernel": ("k_tile" if tile_mode else "k_direct"), "path": args.path,
             "launches_per_step": (len(buckets) if args.path == "buckets" else 2 if args.path == "unfused" else 1), "x_buffers": "in-place" if inplace else "ping-pong",
-            "hbm_layout": args.layout if span_gib is None else f"spread over {span_gib:.0f} GiB",
+            "hbm_layout": hbm_layout,
             "grad_pool": len(pool),
             "issue": "eager" if graph is None else f"graph of {L} iterations, replayed",
             "bucket_streams": max(1, len(side)) if args.path == "buckets" else None,
@@ -454,7 +469,7 @@ def main() -> int:
         del src, dst
     if not args.no_cpu_baseline:
         del x_src, x_dst, m_hat, v_hat, acc, pool, gflat, bufs
-        if args.layout == "spread":
+        if args.layout in ("spread", "whole"):
             del arena
         torch.cuda.empty_cache()
         iters = min(wl.steps, max(wl.s + 1, int(1.2e9 // (R * ns))))

@@ -39,5 +39,20 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return LIB
 
 
+PROBE = os.path.join(HERE, "stream_probe")
+
+
+def build_probe(verbose: bool = True) -> str:
+    """The stand-alone streaming-bandwidth probe (csrc/stream_probe.hip), an executable of its own."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
+           os.path.join(CSRC, "stream_probe.hip"), "-o", PROBE]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return PROBE
+
+
 if __name__ == "__main__":
     build(extra_flags=sys.argv[1:])
+    build_probe()

@@ -441,8 +441,9 @@ int dadam_init(const dadam_config* cfg, dadam_handle** out) {
   h->lds_bytes = cfg->n_cols * (uint32_t)shape.ut * kWave * 16u;
   h->tile_possible = h->lds_bytes <= 65536u;
   // The mixing-only launch moves few bytes per row, so it wants more of them in flight per
-  // wavefront: two vectors per lane and four wavefronts when that tile still fits (measured
-  // 0.70-0.74 of peak against 0.56-0.66 with the fused step's shape).
+  // wavefront: two vectors per lane and four wavefronts when that tile still fits (measured: up to
+  // a quarter faster than the fused step's shape when the buffers sit badly in memory, 3 % when
+  // they sit well).
   h->mix_shape = shape;
   if (cfg->n_cols * 2u * kWave * 16u <= 65536u && env_int("DADAM_TILE_UT", 0) == 0 && env_int("DADAM_TILE_WAVES", 0) == 0) {
     h->mix_shape.ut = 2;

@@ -1,0 +1,196 @@
+// Streaming ceilings of an MI355X's memory system for the traffic shapes of the decentralized Adam
+// step: what plain kernels that do nothing but move bytes reach, so that the step's fraction of the
+// 8 TB/s peak can be judged against what the memory system gives to such traffic at all.
+//
+// A stand-alone measurement program (not part of libdadam, shares no code with it).  It makes one
+// large allocation (physically contiguous in a fresh process) and places its arrays at chosen
+// offsets inside it, which also shows how the sustained rate depends on where the arrays sit in
+// physical memory.  Every placement is checked against the allocation on the host before a launch;
+// every kernel is a plain grid with one tile per workgroup.
+//
+//   stream_probe            all cases
+//   stream_probe quick      one placement per traffic shape
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+#define CK(x)                                                                         \
+  do {                                                                                \
+    hipError_t e_ = (x);                                                              \
+    if (e_ != hipSuccess) {                                                           \
+      printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__);           \
+      exit(1);                                                                        \
+    }                                                                                 \
+  } while (0)
+
+constexpr double kPeak = 8.0e12;
+constexpr size_t kGiB = (size_t)1 << 30;
+constexpr size_t kMiB = (size_t)1 << 20;
+
+// n_read streams are read, their sum is written to n_write streams (n_write may be 0: the sum is
+// then stored only if it equals a value it never has).  Stream k starts at base + k * stride; one
+// workgroup moves one 4 KiB tile of every stream.
+__global__ __launch_bounds__(256) void k_streams(char* base, size_t stride, int n_read, int n_write, float never) {
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  f4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+  for (int k = 0; k < n_read; ++k)
+    acc += __builtin_nontemporal_load(reinterpret_cast<const f4*>(base + (size_t)k * stride) + e);
+  for (int k = 0; k < n_write; ++k)
+    __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(base + (size_t)(n_read + k) * stride) + e);
+  if (n_write == 0 && acc.x == never) reinterpret_cast<f4*>(base)[e] = acc;
+}
+
+// The traffic of one fused step for R = 16 rows that share their sources (degree 5): per 1 KiB
+// tile, 16 source slices staged in LDS, then per row g, m, v, b read and x, b written (FOLD: m and
+// v written too).  96 arrays: [0,16) sources, [16,32) g, [32,48) outputs, [48,96) m, v, b per row.
+constexpr int kRows = 16;
+constexpr int kStepArrays = 6 * kRows;
+template <bool FOLD>
+__global__ __launch_bounds__(256) void k_step_shape(char* base, size_t stride) {
+  const size_t t = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __shared__ f4 lds[kRows * 64];
+  for (int c = wave; c < kRows; c += 4)
+    lds[c * 64 + lane] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(base + (size_t)c * stride) + t * 64 + lane);
+  __syncthreads();
+  for (int i = wave; i < kRows; i += 4) {
+    const f4* gp = reinterpret_cast<const f4*>(base + (size_t)(kRows + i) * stride) + t * 64 + lane;
+    f4* mp = reinterpret_cast<f4*>(base + (size_t)(3 * kRows + 3 * i + 0) * stride) + t * 64 + lane;
+    f4* vp = reinterpret_cast<f4*>(base + (size_t)(3 * kRows + 3 * i + 1) * stride) + t * 64 + lane;
+    f4* bp = reinterpret_cast<f4*>(base + (size_t)(3 * kRows + 3 * i + 2) * stride) + t * 64 + lane;
+    f4 g = *gp, m = *mp, v = *vp, b = *bp;
+    f4 x = lds[i * 64 + lane] + lds[((i + 1) % kRows) * 64 + lane] + lds[((i + 2) % kRows) * 64 + lane] +
+           lds[((i + 4) % kRows) * 64 + lane] + lds[((i + 8) % kRows) * 64 + lane];
+    x += g * m + v;
+    b += g;
+    __builtin_nontemporal_store(x, reinterpret_cast<f4*>(base + (size_t)(2 * kRows + i) * stride) + t * 64 + lane);
+    __builtin_nontemporal_store(b, bp);
+    if (FOLD) {
+      __builtin_nontemporal_store(m + b, mp);
+      __builtin_nontemporal_store(v + b, vp);
+    }
+  }
+}
+
+struct Arena {
+  char* p = nullptr;
+  size_t bytes = 0;
+};
+
+// Does a family of n arrays of len bytes, the first at offset off and the others stride apart, lie
+// inside the arena without overlapping?
+bool fits(const Arena& a, size_t off, size_t stride, int n, size_t len) {
+  return n >= 1 && stride >= len && stride % 16 == 0 && off % 16 == 0 && off <= a.bytes &&
+         (size_t)(n - 1) * stride + len <= a.bytes - off;
+}
+
+template <typename Launch>
+double time_ms(Launch launch) {
+  hipEvent_t a, b;
+  CK(hipEventCreate(&a));
+  CK(hipEventCreate(&b));
+  launch();
+  CK(hipGetLastError());
+  CK(hipDeviceSynchronize());
+  CK(hipEventRecord(a));
+  for (int r = 0; r < 4; ++r) launch();
+  CK(hipEventRecord(b));
+  CK(hipEventSynchronize(b));
+  CK(hipGetLastError());
+  float ms = 0.f;
+  CK(hipEventElapsedTime(&ms, a, b));
+  CK(hipEventDestroy(a));
+  CK(hipEventDestroy(b));
+  return ms / 4.0;
+}
+
+void report(const char* shape, const char* place, double bytes, double ms) {
+  printf("%-34s %-34s %8.3f ms %6.2f TB/s  %.3f of peak\n", shape, place, ms, bytes / ms / 1e9, bytes / (ms * 1e-3) / kPeak);
+  fflush(stdout);
+}
+
+void run_streams(const Arena& a, const char* shape, const char* place, size_t off, size_t stride, int n_read,
+                 int n_write, size_t len) {
+  if (len % 4096 != 0 || len / 4096 > 0x7fffffffull || !fits(a, off, stride, n_read + n_write, len)) {
+    printf("%-34s %-34s skipped (does not fit the allocation)\n", shape, place);
+    return;
+  }
+  const unsigned grid = (unsigned)(len / 4096);
+  char* base = a.p + off;
+  const double ms = time_ms([&] { hipLaunchKernelGGL(k_streams, dim3(grid), dim3(256), 0, 0, base, stride, n_read, n_write, 12345.678f); });
+  report(shape, place, (double)len * (n_read + n_write), ms);
+}
+
+template <bool FOLD>
+void run_step(const Arena& a, const char* place, size_t off, size_t stride, size_t len) {
+  const char* shape = FOLD ? "step shape, fold (80 r + 64 w)" : "step shape, plain (80 r + 32 w)";
+  if (len % 1024 != 0 || len / 1024 > 0x7fffffffull || !fits(a, off, stride, kStepArrays, len)) {
+    printf("%-34s %-34s skipped (does not fit the allocation)\n", shape, place);
+    return;
+  }
+  const unsigned grid = (unsigned)(len / 1024);
+  char* base = a.p + off;
+  const double ms = time_ms([&] { hipLaunchKernelGGL((k_step_shape<FOLD>), dim3(grid), dim3(256), 0, 0, base, stride); });
+  report(shape, place, (double)len * kRows * (FOLD ? 9 : 7), ms);
+}
+
+// stride that spreads n arrays evenly over span bytes (2 MiB granularity)
+size_t spread_stride(size_t span, int n) { return span / (size_t)n / (2 * kMiB) * (2 * kMiB); }
+
+int main(int argc, char** argv) {
+  const bool quick = argc > 1 && strcmp(argv[1], "quick") == 0;
+  size_t free_b = 0, total_b = 0;
+  CK(hipMemGetInfo(&free_b, &total_b));
+  Arena a;
+  a.bytes = 270 * kGiB;
+  if (free_b < a.bytes + 8 * kGiB) a.bytes = free_b > 16 * kGiB ? (free_b - 8 * kGiB) / kGiB * kGiB : 0;
+  if (a.bytes < 64 * kGiB) {
+    printf("not enough free device memory (%zu GiB) for the probe\n", free_b / kGiB);
+    return 1;
+  }
+  CK(hipMalloc((void**)&a.p, a.bytes));
+  CK(hipMemset(a.p, 0, a.bytes));
+  CK(hipDeviceSynchronize());
+  printf("stream_probe: one allocation of %zu GiB (device total %zu GiB); fractions are of %.1f TB/s\n", a.bytes / kGiB,
+         total_b / kGiB, kPeak / 1e12);
+  printf("%-34s %-34s\n", "traffic shape", "placement of the arrays");
+
+  const size_t len = 475 * kMiB;           // one array of the step shape (GPT-2-small sized, float32)
+  const size_t big = 16 * kGiB;            // one long stream
+  const size_t whole = a.bytes;
+
+  // pure reads
+  run_streams(a, "1 read stream of 16 GiB", "at 0 (inside the first third)", 0, big, 1, 0, big);
+  run_streams(a, "1 read stream of 16 GiB", "at 88 GiB (across a boundary)", 88 * kGiB, big, 1, 0, big);
+  run_streams(a, "96 read streams of 475 MiB", "packed at 0", 0, len, 96, 0, len);
+  run_streams(a, "96 read streams of 475 MiB", "spread over the allocation", 0, spread_stride(whole, 96), 96, 0, len);
+  // copies
+  run_streams(a, "copy, 1 r + 1 w of 16 GiB", "packed at 0", 0, big, 1, 1, big);
+  run_streams(a, "copy, 1 r + 1 w of 16 GiB", "88 GiB apart, from 40 GiB", 40 * kGiB, 88 * kGiB, 1, 1, big);
+  run_streams(a, "5 r + 2 w of 4 GiB", "packed at 0", 0, 4 * kGiB, 5, 2, 4 * kGiB);
+  run_streams(a, "5 r + 2 w of 4 GiB", "spread over the allocation", 0, spread_stride(whole, 7), 5, 2, 4 * kGiB);
+  run_streams(a, "16 r + 16 w of 475 MiB", "packed at 0", 0, len, 16, 16, len);
+  run_streams(a, "16 r + 16 w of 475 MiB", "spread over the allocation", 0, spread_stride(whole, 32), 16, 16, len);
+  // the step's own shape
+  run_step<false>(a, "packed at 0", 0, len, len);
+  run_step<false>(a, "spread over the allocation", 0, spread_stride(whole, kStepArrays), len);
+  run_step<true>(a, "packed at 0", 0, len, len);
+  run_step<true>(a, "spread over the allocation", 0, spread_stride(whole, kStepArrays), len);
+  if (!quick) {
+    // where in physical memory: packed (44.5 GiB) at several offsets, spread over several windows
+    run_step<false>(a, "packed at 96 GiB", 96 * kGiB, len, len);
+    run_step<false>(a, "packed at 192 GiB", 192 * kGiB, len, len);
+    run_step<false>(a, "spread over [0, 96) GiB", 0, spread_stride(96 * kGiB, kStepArrays), len);
+    run_step<false>(a, "spread over [96, 192) GiB", 96 * kGiB, spread_stride(96 * kGiB, kStepArrays), len);
+    run_step<false>(a, "spread over [64, 128) GiB", 64 * kGiB, spread_stride(64 * kGiB, kStepArrays), len);
+    run_step<false>(a, "spread over [0, 192) GiB", 0, spread_stride(192 * kGiB, kStepArrays), len);
+  }
+  CK(hipFree(a.p));
+  return 0;
+}

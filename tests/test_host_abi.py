@@ -384,3 +384,31 @@ def test_c99_client_compiles_links_and_agrees_with_the_binding(tmp_path):
         assert int(got[key]) == int(getattr(info, key)), key
     assert int(got["mix_on_host_only_handle_rc"]) == B.DADAM_ESTATE
     assert int(got["set_lr_rc"]) == 0 and int(got["done"]) == 1
+
+
+def test_two_region_placement_policy():
+    """Placement advice for device buffers (memory management, no GPU needed): two regions either
+    side of the boundary between the first two thirds of the device memory, buffers dealt alternately."""
+    from paper_2410_11998_amd import arena as A
+    GIB = 1 << 30
+    total = 288 * GIB - (20 << 20)
+    sizes = [476 << 20] * 112                                   # configuration 2 with two gradient sets
+    regs = A.two_thirds_regions(sizes, 275 * GIB, total)
+    assert regs == [(30 * GIB, 94 * GIB), (98 * GIB, 162 * GIB)]
+    off = A.deal_offsets(sizes, regs)
+    for k, o in enumerate(off):
+        lo, hi = regs[k % 2]
+        assert lo <= o and o + sizes[k] <= hi and o % (2 << 20) == 0
+    spans = sorted((o, o + n) for o, n in zip(off, sizes))
+    assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
+    # any run of consecutive buffers is split evenly over the two sides
+    for start, count in ((0, 16), (16, 16), (0, 32), (80, 32)):
+        below = sum(1 for k in range(start, start + count) if off[k] < 96 * GIB)
+        assert below == count // 2
+    # large buffers widen the regions; what cannot fit two thirds falls back (None)
+    big = [2 * GIB] * 56
+    regs = A.two_thirds_regions(big, 275 * GIB, total)
+    assert regs is not None and regs[0][1] - regs[0][0] >= int(28 * 2 * GIB * 1.2) and regs[0][0] >= 0 and regs[1][1] <= 192 * GIB
+    assert A.two_thirds_regions([3 * GIB] * 56, 275 * GIB, total) is None
+    # an arena that does not cover the device gives no physical positions
+    assert A.two_thirds_regions(sizes, 200 * GIB, total) is None
