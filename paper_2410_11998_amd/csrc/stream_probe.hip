@@ -29,20 +29,28 @@ typedef float f4 __attribute__((ext_vector_type(4)));
   } while (0)
 
 constexpr double kPeak = 8.0e12;
+
+// Where array k of a family starts: arrays 2j and 2j + 1 form pair j; pairs are `pair` bytes apart,
+// the odd member of a pair `odd` bytes above the even one.  (pair = 2 * odd: equal distances;
+// odd = the distance between two regions: arrays dealt alternately over the two.)
+struct Place {
+  size_t pair, odd;
+};
+__host__ __device__ inline size_t place(Place p, int k) { return (size_t)(k >> 1) * p.pair + (size_t)(k & 1) * p.odd; }
 constexpr size_t kGiB = (size_t)1 << 30;
 constexpr size_t kMiB = (size_t)1 << 20;
 
 // n_read streams are read, their sum is written to n_write streams (n_write may be 0: the sum is
-// then stored only if it equals a value it never has).  Stream k starts at base + k * stride; one
+// then stored only if it equals a value it never has).  Stream k starts at base + place(p, k); one
 // workgroup moves one 4 KiB tile of every stream.
-__global__ __launch_bounds__(256) void k_streams(char* base, size_t stride, int n_read, int n_write, float never) {
+__global__ __launch_bounds__(256) void k_streams(char* base, Place p, int n_read, int n_write, float never) {
   const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
   f4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
   for (int k = 0; k < n_read; ++k)
-    acc += __builtin_nontemporal_load(reinterpret_cast<const f4*>(base + (size_t)k * stride) + e);
+    acc += __builtin_nontemporal_load(reinterpret_cast<const f4*>(base + place(p, k)) + e);
   for (int k = 0; k < n_write; ++k)
-    __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(base + (size_t)(n_read + k) * stride) + e);
+    __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(base + place(p, n_read + k)) + e);
   if (n_write == 0 && acc.x == never) reinterpret_cast<f4*>(base)[e] = acc;
 }
 
@@ -52,24 +60,24 @@ __global__ __launch_bounds__(256) void k_streams(char* base, size_t stride, int 
 constexpr int kRows = 16;
 constexpr int kStepArrays = 6 * kRows;
 template <bool FOLD>
-__global__ __launch_bounds__(256) void k_step_shape(char* base, size_t stride) {
+__global__ __launch_bounds__(256) void k_step_shape(char* base, Place p) {
   const size_t t = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   __shared__ f4 lds[kRows * 64];
   for (int c = wave; c < kRows; c += 4)
-    lds[c * 64 + lane] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(base + (size_t)c * stride) + t * 64 + lane);
+    lds[c * 64 + lane] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(base + place(p, c)) + t * 64 + lane);
   __syncthreads();
   for (int i = wave; i < kRows; i += 4) {
-    const f4* gp = reinterpret_cast<const f4*>(base + (size_t)(kRows + i) * stride) + t * 64 + lane;
-    f4* mp = reinterpret_cast<f4*>(base + (size_t)(3 * kRows + 3 * i + 0) * stride) + t * 64 + lane;
-    f4* vp = reinterpret_cast<f4*>(base + (size_t)(3 * kRows + 3 * i + 1) * stride) + t * 64 + lane;
-    f4* bp = reinterpret_cast<f4*>(base + (size_t)(3 * kRows + 3 * i + 2) * stride) + t * 64 + lane;
+    const f4* gp = reinterpret_cast<const f4*>(base + place(p, kRows + i)) + t * 64 + lane;
+    f4* mp = reinterpret_cast<f4*>(base + place(p, 3 * kRows + 3 * i + 0)) + t * 64 + lane;
+    f4* vp = reinterpret_cast<f4*>(base + place(p, 3 * kRows + 3 * i + 1)) + t * 64 + lane;
+    f4* bp = reinterpret_cast<f4*>(base + place(p, 3 * kRows + 3 * i + 2)) + t * 64 + lane;
     f4 g = *gp, m = *mp, v = *vp, b = *bp;
     f4 x = lds[i * 64 + lane] + lds[((i + 1) % kRows) * 64 + lane] + lds[((i + 2) % kRows) * 64 + lane] +
            lds[((i + 4) % kRows) * 64 + lane] + lds[((i + 8) % kRows) * 64 + lane];
     x += g * m + v;
     b += g;
-    __builtin_nontemporal_store(x, reinterpret_cast<f4*>(base + (size_t)(2 * kRows + i) * stride) + t * 64 + lane);
+    __builtin_nontemporal_store(x, reinterpret_cast<f4*>(base + place(p, 2 * kRows + i)) + t * 64 + lane);
     __builtin_nontemporal_store(b, bp);
     if (FOLD) {
       __builtin_nontemporal_store(m + b, mp);
@@ -83,11 +91,22 @@ struct Arena {
   size_t bytes = 0;
 };
 
-// Does a family of n arrays of len bytes, the first at offset off and the others stride apart, lie
-// inside the arena without overlapping?
-bool fits(const Arena& a, size_t off, size_t stride, int n, size_t len) {
-  return n >= 1 && stride >= len && stride % 16 == 0 && off % 16 == 0 && off <= a.bytes &&
-         (size_t)(n - 1) * stride + len <= a.bytes - off;
+// Does a family of n arrays of len bytes, array k at offset off + place(p, k), lie inside the arena
+// without two arrays overlapping?
+bool fits(const Arena& a, size_t off, Place p, int n, size_t len) {
+  if (n < 1 || n > 128 || off % 16 || p.pair % 16 || p.odd % 16 || off > a.bytes) return false;
+  size_t start[128];
+  for (int k = 0; k < n; ++k) {
+    start[k] = place(p, k);
+    if (start[k] > a.bytes - off || len > a.bytes - off - start[k]) return false;
+  }
+  for (int i = 0; i < n; ++i)
+    for (int j = 0; j < i; ++j) {
+      const size_t lo = start[i] < start[j] ? start[i] : start[j];
+      const size_t hi = start[i] < start[j] ? start[j] : start[i];
+      if (hi - lo < len) return false;
+    }
+  return true;
 }
 
 template <typename Launch>
@@ -110,38 +129,47 @@ double time_ms(Launch launch) {
   return ms / 4.0;
 }
 
-void report(const char* shape, const char* place, double bytes, double ms) {
-  printf("%-34s %-34s %8.3f ms %6.2f TB/s  %.3f of peak\n", shape, place, ms, bytes / ms / 1e9, bytes / (ms * 1e-3) / kPeak);
+void report(const char* shape, const char* where, double bytes, double ms) {
+  printf("%-34s %-34s %8.3f ms %6.2f TB/s  %.3f of peak\n", shape, where, ms, bytes / ms / 1e9, bytes / (ms * 1e-3) / kPeak);
   fflush(stdout);
 }
 
-void run_streams(const Arena& a, const char* shape, const char* place, size_t off, size_t stride, int n_read,
+void run_streams(const Arena& a, const char* shape, const char* where, size_t off, Place p, int n_read,
                  int n_write, size_t len) {
-  if (len % 4096 != 0 || len / 4096 > 0x7fffffffull || !fits(a, off, stride, n_read + n_write, len)) {
-    printf("%-34s %-34s skipped (does not fit the allocation)\n", shape, place);
+  if (len % 4096 != 0 || len / 4096 > 0x7fffffffull || !fits(a, off, p, n_read + n_write, len)) {
+    printf("%-34s %-34s skipped (does not fit the allocation)\n", shape, where);
     return;
   }
   const unsigned grid = (unsigned)(len / 4096);
   char* base = a.p + off;
-  const double ms = time_ms([&] { hipLaunchKernelGGL(k_streams, dim3(grid), dim3(256), 0, 0, base, stride, n_read, n_write, 12345.678f); });
-  report(shape, place, (double)len * (n_read + n_write), ms);
+  const double ms = time_ms([&] { hipLaunchKernelGGL(k_streams, dim3(grid), dim3(256), 0, 0, base, p, n_read, n_write, 12345.678f); });
+  report(shape, where, (double)len * (n_read + n_write), ms);
 }
 
 template <bool FOLD>
-void run_step(const Arena& a, const char* place, size_t off, size_t stride, size_t len) {
+void run_step(const Arena& a, const char* where, size_t off, Place p, size_t len) {
   const char* shape = FOLD ? "step shape, fold (80 r + 64 w)" : "step shape, plain (80 r + 32 w)";
-  if (len % 1024 != 0 || len / 1024 > 0x7fffffffull || !fits(a, off, stride, kStepArrays, len)) {
-    printf("%-34s %-34s skipped (does not fit the allocation)\n", shape, place);
+  if (len % 1024 != 0 || len / 1024 > 0x7fffffffull || !fits(a, off, p, kStepArrays, len)) {
+    printf("%-34s %-34s skipped (does not fit the allocation)\n", shape, where);
     return;
   }
   const unsigned grid = (unsigned)(len / 1024);
   char* base = a.p + off;
-  const double ms = time_ms([&] { hipLaunchKernelGGL((k_step_shape<FOLD>), dim3(grid), dim3(256), 0, 0, base, stride); });
-  report(shape, place, (double)len * kRows * (FOLD ? 9 : 7), ms);
+  const double ms = time_ms([&] { hipLaunchKernelGGL((k_step_shape<FOLD>), dim3(grid), dim3(256), 0, 0, base, p); });
+  report(shape, where, (double)len * kRows * (FOLD ? 9 : 7), ms);
 }
 
-// stride that spreads n arrays evenly over span bytes (2 MiB granularity)
-size_t spread_stride(size_t span, int n) { return span / (size_t)n / (2 * kMiB) * (2 * kMiB); }
+// n arrays at equal distances over span bytes (2 MiB granularity)
+Place even(size_t span, int n) {
+  const size_t stride = span / (size_t)n / (2 * kMiB) * (2 * kMiB);
+  return Place{2 * stride, stride};
+}
+Place packed(size_t len) { return Place{2 * len, len}; }
+// n arrays dealt alternately over two regions of `width` bytes whose starts are `apart` bytes apart
+Place dealt(size_t width, size_t apart, int n) {
+  const size_t stride = width / (size_t)((n + 1) / 2) / (2 * kMiB) * (2 * kMiB);
+  return Place{stride, apart};
+}
 
 int main(int argc, char** argv) {
   const bool quick = argc > 1 && strcmp(argv[1], "quick") == 0;
@@ -164,32 +192,40 @@ int main(int argc, char** argv) {
   const size_t len = 475 * kMiB;           // one array of the step shape (GPT-2-small sized, float32)
   const size_t big = 16 * kGiB;            // one long stream
   const size_t whole = a.bytes;
+  // "two thirds": regions [30, 94) and [98, 162) GiB, arrays dealt alternately
+  const size_t t_off = 30 * kGiB, t_width = 64 * kGiB, t_apart = 68 * kGiB;
+  const char* two = "dealt over [30,94) + [98,162) GiB";
 
   // pure reads
-  run_streams(a, "1 read stream of 16 GiB", "at 0 (inside the first third)", 0, big, 1, 0, big);
-  run_streams(a, "1 read stream of 16 GiB", "at 88 GiB (across a boundary)", 88 * kGiB, big, 1, 0, big);
-  run_streams(a, "96 read streams of 475 MiB", "packed at 0", 0, len, 96, 0, len);
-  run_streams(a, "96 read streams of 475 MiB", "spread over the allocation", 0, spread_stride(whole, 96), 96, 0, len);
+  run_streams(a, "1 read stream of 16 GiB", "at 0 (inside the first third)", 0, packed(big), 1, 0, big);
+  run_streams(a, "1 read stream of 16 GiB", "at 88 GiB (across a boundary)", 88 * kGiB, packed(big), 1, 0, big);
+  run_streams(a, "96 read streams of 475 MiB", "packed at 0", 0, packed(len), 96, 0, len);
+  run_streams(a, "96 read streams of 475 MiB", "equal distances, everything", 0, even(whole, 96), 96, 0, len);
+  run_streams(a, "96 read streams of 475 MiB", two, t_off, dealt(t_width, t_apart, 96), 96, 0, len);
   // copies
-  run_streams(a, "copy, 1 r + 1 w of 16 GiB", "packed at 0", 0, big, 1, 1, big);
-  run_streams(a, "copy, 1 r + 1 w of 16 GiB", "88 GiB apart, from 40 GiB", 40 * kGiB, 88 * kGiB, 1, 1, big);
-  run_streams(a, "5 r + 2 w of 4 GiB", "packed at 0", 0, 4 * kGiB, 5, 2, 4 * kGiB);
-  run_streams(a, "5 r + 2 w of 4 GiB", "spread over the allocation", 0, spread_stride(whole, 7), 5, 2, 4 * kGiB);
-  run_streams(a, "16 r + 16 w of 475 MiB", "packed at 0", 0, len, 16, 16, len);
-  run_streams(a, "16 r + 16 w of 475 MiB", "spread over the allocation", 0, spread_stride(whole, 32), 16, 16, len);
+  run_streams(a, "copy, 1 r + 1 w of 16 GiB", "packed at 0", 0, packed(big), 1, 1, big);
+  run_streams(a, "copy, 1 r + 1 w of 16 GiB", "at 40 and 128 GiB", 40 * kGiB, Place{0, 88 * kGiB}, 1, 1, big);
+  run_streams(a, "5 r + 2 w of 4 GiB", "packed at 0", 0, packed(4 * kGiB), 5, 2, 4 * kGiB);
+  run_streams(a, "5 r + 2 w of 4 GiB", "equal distances, everything", 0, even(whole, 7), 5, 2, 4 * kGiB);
+  run_streams(a, "5 r + 2 w of 4 GiB", two, t_off, dealt(t_width, t_apart, 7), 5, 2, 4 * kGiB);
+  run_streams(a, "16 r + 16 w of 475 MiB", "packed at 0", 0, packed(len), 16, 16, len);
+  run_streams(a, "16 r + 16 w of 475 MiB", "equal distances, everything", 0, even(whole, 32), 16, 16, len);
+  run_streams(a, "16 r + 16 w of 475 MiB", two, t_off, dealt(t_width, t_apart, 32), 16, 16, len);
   // the step's own shape
-  run_step<false>(a, "packed at 0", 0, len, len);
-  run_step<false>(a, "spread over the allocation", 0, spread_stride(whole, kStepArrays), len);
-  run_step<true>(a, "packed at 0", 0, len, len);
-  run_step<true>(a, "spread over the allocation", 0, spread_stride(whole, kStepArrays), len);
+  run_step<false>(a, "packed at 0", 0, packed(len), len);
+  run_step<false>(a, "equal distances, everything", 0, even(whole, kStepArrays), len);
+  run_step<false>(a, two, t_off, dealt(t_width, t_apart, kStepArrays), len);
+  run_step<true>(a, "packed at 0", 0, packed(len), len);
+  run_step<true>(a, "equal distances, everything", 0, even(whole, kStepArrays), len);
+  run_step<true>(a, two, t_off, dealt(t_width, t_apart, kStepArrays), len);
   if (!quick) {
-    // where in physical memory: packed (44.5 GiB) at several offsets, spread over several windows
-    run_step<false>(a, "packed at 96 GiB", 96 * kGiB, len, len);
-    run_step<false>(a, "packed at 192 GiB", 192 * kGiB, len, len);
-    run_step<false>(a, "spread over [0, 96) GiB", 0, spread_stride(96 * kGiB, kStepArrays), len);
-    run_step<false>(a, "spread over [96, 192) GiB", 96 * kGiB, spread_stride(96 * kGiB, kStepArrays), len);
-    run_step<false>(a, "spread over [64, 128) GiB", 64 * kGiB, spread_stride(64 * kGiB, kStepArrays), len);
-    run_step<false>(a, "spread over [0, 192) GiB", 0, spread_stride(192 * kGiB, kStepArrays), len);
+    // where in physical memory: packed (44.5 GiB) at several offsets, equal distances over several windows
+    run_step<false>(a, "packed at 96 GiB", 96 * kGiB, packed(len), len);
+    run_step<false>(a, "packed at 192 GiB", 192 * kGiB, packed(len), len);
+    run_step<false>(a, "equal distances, [0, 96) GiB", 0, even(96 * kGiB, kStepArrays), len);
+    run_step<false>(a, "equal distances, [96, 192) GiB", 96 * kGiB, even(96 * kGiB, kStepArrays), len);
+    run_step<false>(a, "equal distances, [64, 128) GiB", 64 * kGiB, even(64 * kGiB, kStepArrays), len);
+    run_step<false>(a, "equal distances, [0, 192) GiB", 0, even(192 * kGiB, kStepArrays), len);
   }
   CK(hipFree(a.p));
   return 0;
