@@ -25,15 +25,17 @@ namespace dadam {
 namespace {
 
 constexpr uint32_t kXcds = 8;  // accelerator complex dies of an MI355X, each with its own L2
+// distance (in elements) between the two groups of four that an 8-element lane vector consists of
+constexpr int kHalfWave = 4 * kWave;             // tile kernel: the lanes of a wavefront work side by side
+constexpr int kHalfGroup = 4 * kDirectThreads;   // direct and accumulate kernels: the whole workgroup does
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 
 // Element types, with the elements per lane and vector of a handle whose parameters have that type:
-// float32 4 (one 128-bit access); bfloat16 8 (one 128-bit access of x and g, two of each float32 state
-// vector, the lane's 32 bytes contiguous).  A 4-element bfloat16 variant with fully coalesced state
-// accesses was measured at +0.3 % and not kept.
+// float32 4 (one 128-bit access); bfloat16 8, held as two groups of four (two 64-bit accesses of x and
+// g, two 128-bit accesses of each float32 state vector; see load_vals for where the groups lie).
 struct TF32 {
   static constexpr int bytes = 4;
   static constexpr int vec = 4;
@@ -70,15 +72,22 @@ __device__ __forceinline__ void store_elem(void* base, uint64_t e, float v) {
   }
 }
 
-// VEC consecutive elements of type T starting at element e (e a multiple of VEC * ... such that the
-// address is 16-byte aligned), widened to float.  MASKED lanes that are not wholly inside [lo, hi)
-// touch only the elements that are; the others read as zero.
-// Streaming accesses: every global datum of a step is touched exactly once, so full-vector
+// The VEC elements of one lane and vector, of type T, widened to float.  VEC = 4: elements
+// [e, e + 4).  VEC = 8: two groups of four, [e, e + 4) and [e + H, e + H + 4), where H is four times
+// the number of lanes that work side by side (a wavefront in the tile kernel, a workgroup in the
+// others): every access instruction of the group then covers one contiguous run of memory, 16
+// bytes per lane for float32 and 8 for bfloat16, and every 128-byte line it touches is touched
+// whole.  (Giving a lane 8 consecutive elements instead makes each float32 state access two
+// instructions that each touch half of every line: measured 5-13 % slower once stores are involved.)
+// e is a multiple of 4, so every group is 16-byte (float32) or 8-byte (bfloat16) aligned.
+// MASKED groups that are not wholly inside [lo, hi) touch only the elements that are; the others
+// read as zero.
+// Streaming accesses: every global datum of a step is touched exactly once, so full-group
 // accesses may carry the non-temporal hint (NT) and leave the caches to nobody in particular.
 // Which classes of access carry the hint when a handle streams (all eight combinations measured):
-constexpr bool kNtSource = true;   // parameter (source) loads
-constexpr bool kNtStream = false;  // gradient / moment / accumulator loads: costs the bf16 variant 5 %
-constexpr bool kNtStore = true;    // all stores
+constexpr bool kNtSource = true;  // parameter (source) loads
+constexpr bool kNtStream = true;  // gradient / moment / accumulator loads
+constexpr bool kNtStore = true;   // all stores
 
 template <bool NT, typename V>
 __device__ __forceinline__ V vload(const V* p) {
@@ -91,94 +100,94 @@ __device__ __forceinline__ void vstore(V* p, V v) {
   else *p = v;
 }
 
-template <typename T, int VEC, bool MASKED, bool NT>
+template <typename T, int VEC, int H, bool MASKED, bool NT>
 __device__ __forceinline__ void load_vals(const void* base, uint64_t e, uint64_t lo, uint64_t hi,
                                           float (&out)[VEC]) {
-  if (!MASKED || (e >= lo && e + VEC <= hi)) {
-    if constexpr (T::bytes == 4) {
-      const f4* p = reinterpret_cast<const f4*>(reinterpret_cast<const float*>(base) + e);
+  static_assert(VEC == 4 || (VEC == 8 && H >= 4), "a lane holds one or two groups of four elements");
 #pragma unroll
-      for (int q = 0; q < VEC / 4; ++q) {
-        f4 v = vload<NT && kNtStream>(p + q);
-        out[4 * q + 0] = v.x; out[4 * q + 1] = v.y; out[4 * q + 2] = v.z; out[4 * q + 3] = v.w;
+  for (int h = 0; h < VEC / 4; ++h) {
+    const uint64_t eh = e + (uint64_t)h * H;
+    if (!MASKED || (eh >= lo && eh + 4 <= hi)) {
+      if constexpr (T::bytes == 4) {
+        f4 v = vload<NT && kNtStream>(reinterpret_cast<const f4*>(reinterpret_cast<const float*>(base) + eh));
+        out[4 * h + 0] = v.x; out[4 * h + 1] = v.y; out[4 * h + 2] = v.z; out[4 * h + 3] = v.w;
+      } else {
+        u2 v = vload<NT && kNtStream>(reinterpret_cast<const u2*>(reinterpret_cast<const uint16_t*>(base) + eh));
+        out[4 * h + 0] = __uint_as_float(v.x << 16); out[4 * h + 1] = __uint_as_float(v.x & 0xFFFF0000u);
+        out[4 * h + 2] = __uint_as_float(v.y << 16); out[4 * h + 3] = __uint_as_float(v.y & 0xFFFF0000u);
       }
-    } else if constexpr (VEC == 8) {
-      u4 v = vload<NT && kNtStream>(reinterpret_cast<const u4*>(reinterpret_cast<const uint16_t*>(base) + e));
-      out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xFFFF0000u);
-      out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xFFFF0000u);
-      out[4] = __uint_as_float(v.z << 16); out[5] = __uint_as_float(v.z & 0xFFFF0000u);
-      out[6] = __uint_as_float(v.w << 16); out[7] = __uint_as_float(v.w & 0xFFFF0000u);
     } else {
-      u2 v = vload<NT && kNtStream>(reinterpret_cast<const u2*>(reinterpret_cast<const uint16_t*>(base) + e));
-      out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xFFFF0000u);
-      out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xFFFF0000u);
-    }
-  } else {
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) {
-      uint64_t ej = e + j;
-      out[j] = (ej >= lo && ej < hi) ? load_elem<T>(base, ej) : 0.0f;
+      for (int j = 0; j < 4; ++j) {
+        const uint64_t ej = eh + j;
+        out[4 * h + j] = (ej >= lo && ej < hi) ? load_elem<T>(base, ej) : 0.0f;
+      }
     }
   }
 }
 
-template <typename T, int VEC, bool MASKED, bool NT>
+template <typename T, int VEC, int H, bool MASKED, bool NT>
 __device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, uint64_t hi,
                                            const float (&in)[VEC]) {
-  if (!MASKED || (e >= lo && e + VEC <= hi)) {
-    if constexpr (T::bytes == 4) {
-      f4* p = reinterpret_cast<f4*>(reinterpret_cast<float*>(base) + e);
+  static_assert(VEC == 4 || (VEC == 8 && H >= 4), "a lane holds one or two groups of four elements");
 #pragma unroll
-      for (int q = 0; q < VEC / 4; ++q) {
+  for (int h = 0; h < VEC / 4; ++h) {
+    const uint64_t eh = e + (uint64_t)h * H;
+    if (!MASKED || (eh >= lo && eh + 4 <= hi)) {
+      if constexpr (T::bytes == 4) {
         f4 v;
-        v.x = in[4 * q + 0]; v.y = in[4 * q + 1]; v.z = in[4 * q + 2]; v.w = in[4 * q + 3];
-        vstore<NT && kNtStore>(p + q, v);
+        v.x = in[4 * h + 0]; v.y = in[4 * h + 1]; v.z = in[4 * h + 2]; v.w = in[4 * h + 3];
+        vstore<NT && kNtStore>(reinterpret_cast<f4*>(reinterpret_cast<float*>(base) + eh), v);
+      } else {
+        u2 v;
+        v.x = f32_to_bf16_bits(in[4 * h + 0]) | (f32_to_bf16_bits(in[4 * h + 1]) << 16);
+        v.y = f32_to_bf16_bits(in[4 * h + 2]) | (f32_to_bf16_bits(in[4 * h + 3]) << 16);
+        vstore<NT && kNtStore>(reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(base) + eh), v);
       }
-    } else if constexpr (VEC == 8) {
-      u4 v;
-      v.x = f32_to_bf16_bits(in[0]) | (f32_to_bf16_bits(in[1]) << 16);
-      v.y = f32_to_bf16_bits(in[2]) | (f32_to_bf16_bits(in[3]) << 16);
-      v.z = f32_to_bf16_bits(in[4]) | (f32_to_bf16_bits(in[5]) << 16);
-      v.w = f32_to_bf16_bits(in[6]) | (f32_to_bf16_bits(in[7]) << 16);
-      vstore<NT && kNtStore>(reinterpret_cast<u4*>(reinterpret_cast<uint16_t*>(base) + e), v);
     } else {
-      u2 v;
-      v.x = f32_to_bf16_bits(in[0]) | (f32_to_bf16_bits(in[1]) << 16);
-      v.y = f32_to_bf16_bits(in[2]) | (f32_to_bf16_bits(in[3]) << 16);
-      vstore<NT && kNtStore>(reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(base) + e), v);
-    }
-  } else {
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) {
-      uint64_t ej = e + j;
-      if (ej >= lo && ej < hi) store_elem<T>(base, ej, in[j]);
+      for (int j = 0; j < 4; ++j) {
+        const uint64_t ej = eh + j;
+        if (ej >= lo && ej < hi) store_elem<T>(base, ej, in[4 * h + j]);
+      }
     }
   }
 }
 
-// The 16 raw bytes of a parameter vector (4 float32 or 8 bfloat16), as they are parked in LDS.
-template <typename XT, bool MASKED, bool NT>
+// The 16 raw bytes of a lane's parameter vector (4 float32, or 2 x 4 bfloat16 in the two groups
+// described above), as they are parked in LDS.
+template <typename XT, int H, bool MASKED, bool NT>
 __device__ __forceinline__ u4 load_raw(const void* base, uint64_t e, uint64_t lo, uint64_t hi) {
-  constexpr int VEC = XT::vec;
-  if (!MASKED || (e >= lo && e + VEC <= hi)) {
-    return vload<NT && kNtSource>(reinterpret_cast<const u4*>(reinterpret_cast<const char*>(base) + e * XT::bytes));
-  }
-  u4 r = {0u, 0u, 0u, 0u};
   if constexpr (XT::bytes == 4) {
+    if (!MASKED || (e >= lo && e + 4 <= hi))
+      return vload<NT && kNtSource>(reinterpret_cast<const u4*>(reinterpret_cast<const float*>(base) + e));
+    u4 r = {0u, 0u, 0u, 0u};
     const uint32_t* p = reinterpret_cast<const uint32_t*>(base);
     if (e + 0 >= lo && e + 0 < hi) r.x = p[e + 0];
     if (e + 1 >= lo && e + 1 < hi) r.y = p[e + 1];
     if (e + 2 >= lo && e + 2 < hi) r.z = p[e + 2];
     if (e + 3 >= lo && e + 3 < hi) r.w = p[e + 3];
+    return r;
   } else {
+    static_assert(XT::bytes == 4 || H >= 4, "bfloat16 vectors come in two groups");
     const uint16_t* p = reinterpret_cast<const uint16_t*>(base);
-    uint32_t h[8];
+    u2 half[2];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) h[j] = (e + j >= lo && e + j < hi) ? (uint32_t)p[e + j] : 0u;
-    r.x = h[0] | (h[1] << 16); r.y = h[2] | (h[3] << 16);
-    r.z = h[4] | (h[5] << 16); r.w = h[6] | (h[7] << 16);
+    for (int h = 0; h < 2; ++h) {
+      const uint64_t eh = e + (uint64_t)h * H;
+      if (!MASKED || (eh >= lo && eh + 4 <= hi)) {
+        half[h] = vload<NT && kNtSource>(reinterpret_cast<const u2*>(p + eh));
+      } else {
+        uint32_t q[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) q[j] = (eh + j >= lo && eh + j < hi) ? (uint32_t)p[eh + j] : 0u;
+        half[h].x = q[0] | (q[1] << 16);
+        half[h].y = q[2] | (q[3] << 16);
+      }
+    }
+    u4 r = {half[0].x, half[0].y, half[1].x, half[1].y};
+    return r;
   }
-  return r;
 }
 
 template <typename XT>
@@ -317,20 +326,20 @@ __device__ __forceinline__ void load_row_inputs(const StepArgs& a, int i, const 
   if constexpr (Needs<PHASE>::grad) {
     const void* gp = a.grad[i];
 #pragma unroll
-    for (int u = 0; u < UT; ++u) load_vals<GT, VEC, MASKED, NT>(gp, e[u], lo, hi, g[u]);
+    for (int u = 0; u < UT; ++u) load_vals<GT, VEC, kHalfWave, MASKED, NT>(gp, e[u], lo, hi, g[u]);
   }
   if constexpr (Needs<PHASE>::moments_in) {
     const float* mp = a.m_hat[i];
     const float* vp = a.v_hat[i];
 #pragma unroll
-    for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
+    for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, kHalfWave, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-    for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
+    for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, kHalfWave, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
   if constexpr (Needs<PHASE>::acc_in) {
     const float* bp = a.acc[i];
 #pragma unroll
-    for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
+    for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, kHalfWave, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
 }
 
@@ -391,19 +400,19 @@ __device__ __forceinline__ void finish_row(const StepArgs& a, const u4* lds, int
 
   void* xd = a.x_dst[i];
 #pragma unroll
-  for (int u = 0; u < UT; ++u) store_vals<XT, VEC, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
+  for (int u = 0; u < UT; ++u) store_vals<XT, VEC, kHalfWave, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
   if constexpr (Needs<PHASE>::acc_out) {
     float* bp = a.acc[i];
 #pragma unroll
-    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
+    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, kHalfWave, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   if constexpr (Needs<PHASE>::moments_out) {
     float* mp = a.m_hat[i];
     float* vp = a.v_hat[i];
 #pragma unroll
-    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
+    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, kHalfWave, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
+    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, kHalfWave, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
 }
 
@@ -413,7 +422,7 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
   constexpr int VEC = XT::vec;
   uint64_t e[UT];
 #pragma unroll
-  for (int u = 0; u < UT; ++u) e[u] = tbase + (uint64_t)(u * kWave + lane) * VEC;
+  for (int u = 0; u < UT; ++u) e[u] = tbase + (uint64_t)u * (kWave * VEC) + 4u * (uint32_t)lane;
 
   const int n_rows = (int)a.n_rows;
   const RowPtrs rp = load_row_ptrs(a, lane);
@@ -433,7 +442,7 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
         if (c < n_cols) {
           const void* src = a.x_src[c];
 #pragma unroll
-          for (int u = 0; u < UT; ++u) r[k][u] = load_raw<XT, MASKED, NT>(src, e[u], lo, hi);
+          for (int u = 0; u < UT; ++u) r[k][u] = load_raw<XT, kHalfWave, MASKED, NT>(src, e[u], lo, hi);
         }
       }
 #pragma unroll
@@ -450,7 +459,7 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
       const void* src = a.x_src[c];
       u4 r[UT];
 #pragma unroll
-      for (int u = 0; u < UT; ++u) r[u] = load_raw<XT, MASKED, NT>(src, e[u], lo, hi);
+      for (int u = 0; u < UT; ++u) r[u] = load_raw<XT, kHalfWave, MASKED, NT>(src, e[u], lo, hi);
 #pragma unroll
       for (int u = 0; u < UT; ++u) lds[(c * UT + u) * kWave + lane] = r[u];
     }
@@ -559,7 +568,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
       const void* src = a.x_src[list_col(rl, k)];
       wk[k] = list_w(rl, k);
 #pragma unroll
-      for (int u = 0; u < kUD; ++u) r[k][u] = load_raw<XT, MASKED, NT>(src, e[u], lo, hi);
+      for (int u = 0; u < kUD; ++u) r[k][u] = load_raw<XT, kHalfGroup, MASKED, NT>(src, e[u], lo, hi);
     }
 #pragma unroll
     for (int k = 0; k < DEG; ++k)
@@ -577,7 +586,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
 #pragma unroll
       for (int u = 0; u < kUD; ++u) {
         float xs[VEC];
-        unpack_raw<XT>(load_raw<XT, MASKED, NT>(src, e[u], lo, hi), xs);
+        unpack_raw<XT>(load_raw<XT, kHalfGroup, MASKED, NT>(src, e[u], lo, hi), xs);
 #pragma unroll
         for (int j = 0; j < VEC; ++j) mix[u][j] = w0 * xs[j];
       }
@@ -588,7 +597,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
 #pragma unroll
       for (int u = 0; u < kUD; ++u) {
         float xs[VEC];
-        unpack_raw<XT>(load_raw<XT, MASKED, NT>(src, e[u], lo, hi), xs);
+        unpack_raw<XT>(load_raw<XT, kHalfGroup, MASKED, NT>(src, e[u], lo, hi), xs);
 #pragma unroll
         for (int j = 0; j < VEC; ++j) mix[u][j] = fmaf(wk, xs[j], mix[u][j]);
       }
@@ -602,35 +611,32 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
   constexpr int VEC = XT::vec;
   uint64_t e[kUD];
 #pragma unroll
-  for (int u = 0; u < kUD; ++u) e[u] = tbase + (uint64_t)(u * kDirectThreads + threadIdx.x) * VEC;
-  // the neighbour list is fetched while every lane is still active: readlane below must find a
-  // loaded value in whichever lane it asks
+  for (int u = 0; u < kUD; ++u) e[u] = tbase + (uint64_t)u * (kDirectThreads * VEC) + 4u * threadIdx.x;
+  // The neighbour list sits one entry per lane and is handed out with readlane, which must find a
+  // loaded value in whichever lane it asks.  So no lane may leave before the last readlane: a
+  // thread of a clipped tile whose vectors all lie outside the range runs through the body with
+  // every access masked off instead of returning early.  (With an early return the compiler is
+  // free to sink the list's load below it, into the lanes that stay - and a row whose leading
+  // lanes lie before the segment then reads its neighbours' indices from lanes that never loaded.)
   RowList rl = load_row_list(a, row, lane);
-  if (MASKED) {
-    // a thread whose vectors all lie outside the range has nothing to do (no barrier in this kernel)
-    bool any = false;
-#pragma unroll
-    for (int u = 0; u < kUD; ++u) any = any || (e[u] < hi && e[u] + VEC > lo);
-    if (!any) return;
-  }
   float g[kUD][VEC], mh[kUD][VEC], vh[kUD][VEC], b[kUD][VEC];
   if constexpr (Needs<PHASE>::grad) {
     const void* gp = a.grad[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, MASKED, NT>(gp, e[u], lo, hi, g[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, kHalfGroup, MASKED, NT>(gp, e[u], lo, hi, g[u]);
   }
   if constexpr (Needs<PHASE>::moments_in) {
     const float* mp = a.m_hat[row];
     const float* vp = a.v_hat[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
   if constexpr (Needs<PHASE>::acc_in) {
     const float* bp = a.acc[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   float mix[kUD][VEC];
   switch (rl.deg) {
@@ -653,7 +659,7 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
 #pragma unroll
     for (int u = 0; u < kUD; ++u) {
       float xs[VEC];
-      unpack_raw<XT>(load_raw<XT, MASKED, false>(own, e[u], lo, hi), xs);
+      unpack_raw<XT>(load_raw<XT, kHalfGroup, MASKED, false>(own, e[u], lo, hi), xs);
 #pragma unroll
       for (int j = 0; j < VEC; ++j) decay[u][j] = wd * xs[j];
     }
@@ -666,19 +672,19 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
       xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j], decay[u][j]);
   void* xd = a.x_dst[row];
 #pragma unroll
-  for (int u = 0; u < kUD; ++u) store_vals<XT, VEC, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
+  for (int u = 0; u < kUD; ++u) store_vals<XT, VEC, kHalfGroup, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
   if constexpr (Needs<PHASE>::acc_out) {
     float* bp = a.acc[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, kHalfGroup, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   if constexpr (Needs<PHASE>::moments_out) {
     float* mp = a.m_hat[row];
     float* vp = a.v_hat[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, kHalfGroup, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, kHalfGroup, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
 }
 
@@ -723,23 +729,23 @@ __device__ __forceinline__ void acc_body(const StepArgs& a, int row, uint64_t tb
                                          uint64_t hi) {
   uint64_t e[kUD];
 #pragma unroll
-  for (int u = 0; u < kUD; ++u) e[u] = tbase + (uint64_t)(u * kDirectThreads + threadIdx.x) * VEC;
+  for (int u = 0; u < kUD; ++u) e[u] = tbase + (uint64_t)u * (kDirectThreads * VEC) + 4u * threadIdx.x;
   float g[kUD][VEC], mh[kUD][VEC], vh[kUD][VEC], b[kUD][VEC];
   const void* gp = a.grad[row];
 #pragma unroll
-  for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, MASKED, NT>(gp, e[u], lo, hi, g[u]);
+  for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, kHalfGroup, MASKED, NT>(gp, e[u], lo, hi, g[u]);
   if constexpr (Needs<PHASE>::moments_out) {
     const float* mp = a.m_hat[row];
     const float* vp = a.v_hat[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
   if constexpr (Needs<PHASE>::acc_in) {
     const float* bp = a.acc[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
+    for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
 #pragma unroll
   for (int u = 0; u < kUD; ++u)
@@ -748,15 +754,15 @@ __device__ __forceinline__ void acc_body(const StepArgs& a, int row, uint64_t tb
   if constexpr (Needs<PHASE>::acc_out) {
     float* bp = a.acc[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(bp, e[u], lo, hi, b[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, kHalfGroup, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   if constexpr (Needs<PHASE>::moments_out) {
     float* mp = a.m_hat[row];
     float* vp = a.v_hat[row];
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, kHalfGroup, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
-    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
+    for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, kHalfGroup, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
 }
 

@@ -246,23 +246,62 @@ def test_spread_offsets_properties():
     assert B.lib.dadam_spread_offsets(None, 1, 100, None) == B.DADAM_EINVAL
 
 
-def test_kernels_use_no_scratch_memory(tmp_path):
-    """Every kernel must keep its state in registers: a struct copied to private memory once cost
-    8 % of the step's bandwidth without any test noticing.  Compiles the device code with the
-    compiler's resource-usage remarks and checks the scratch size of every kernel."""
+def test_kernels_use_no_scratch_memory_and_load_neighbour_lists_with_all_lanes(tmp_path):
+    """Two properties of the compiled device code, read from the compiler's own output.
+
+    (1) Every kernel keeps its state in registers: a struct copied to private memory once cost 8 %
+    of the step's bandwidth without any test noticing (resource-usage remarks, scratch size 0).
+
+    (2) A row's neighbour list sits one entry per lane and is handed out with readlane, so its load
+    must run with every lane active.  The direct kernel once let threads of a clipped tile return
+    early; a later build sank the list's load below that exit and rows whose leading lanes lay before
+    the segment read indices from lanes that had never loaded.  The source must have no early exit
+    in device code, and in the direct kernels' assembly no register that readlane reads may be
+    loaded between a narrowing of the exec mask and its restoration."""
     import shutil
     import subprocess
     from paper_2410_11998_amd import build as bld
     if shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"):
         pytest.skip("hipcc not available")
+    src = open(os.path.join(bld.CSRC, "dadam_kernels.hip")).read()
+    device_code = src[:src.index("// dispatch tables")]
+    assert not re.search(r"\breturn\s*;", device_code), "an early exit in device code: see the docstring"
     flags = [f for f in bld.FLAGS if f not in ("-shared", "-fPIC")]
-    cmd = [bld.hipcc()] + flags + ["--cuda-device-only", "-c", os.path.join(bld.CSRC, "dadam_kernels.hip"),
-                                  "-o", str(tmp_path / "k.o"), "-Rpass-analysis=kernel-resource-usage"]
+    asm = tmp_path / "k.s"
+    cmd = [bld.hipcc()] + flags + ["--cuda-device-only", "-S", os.path.join(bld.CSRC, "dadam_kernels.hip"),
+                                  "-o", str(asm), "-Rpass-analysis=kernel-resource-usage"]
     r = subprocess.run(cmd, capture_output=True, text=True, timeout=900)
     assert r.returncode == 0, r.stderr[-2000:]
     sizes = [int(x) for x in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", r.stderr)]
     assert len(sizes) > 100, "no resource remarks found"
     assert max(sizes) == 0, f"{sum(1 for s in sizes if s)} kernels spill or copy to scratch"
+
+    name, depth, loads, checked, bad = None, 0, {}, 0, []
+    with open(asm) as f:
+        for line in f:
+            m = re.match(r"^(_ZN5dadam[A-Za-z0-9_]*k_direct[A-Za-z0-9_]*):", line)
+            if m:
+                name, depth, loads = m.group(1), 0, {}
+                continue
+            if name is None:
+                continue
+            if "s_endpgm" in line:
+                name = None
+            elif "s_and_saveexec_b64" in line:
+                depth += 1
+            elif "s_or_b64 exec, exec" in line:
+                depth = max(0, depth - 1)
+            else:
+                m = re.search(r"global_load_dword (v\d+),", line)
+                if m:
+                    loads[m.group(1)] = depth
+                m = re.search(r"v_readlane_b32 s\d+, (v\d+),", line)
+                if m and m.group(1) in loads:
+                    checked += 1
+                    if loads[m.group(1)] > 0:
+                        bad.append(name)
+    assert checked > 1000, "no readlane of a loaded register found in the direct kernels"
+    assert not bad, f"neighbour list loaded under a narrowed exec mask in {len(set(bad))} kernels, e.g. {bad[0]}"
 
 
 def test_bench_byte_accounting_matches_the_workload_table():
