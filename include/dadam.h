@@ -219,17 +219,32 @@ int dadam_slot_uses_tile_mode(const dadam_handle* h, uint32_t slot);
 int dadam_pack_offsets(const uint64_t* numel, uint32_t n, uint32_t align_elems, uint64_t* offsets,
                        uint64_t* d_out);
 
-/* Layout advice for HBM.  Measured on MI355X: the same step over the same bytes runs about 15 %
- * faster when the buffers it streams together straddle the boundaries between the 96 GiB thirds of
- * the device's physical memory than when they all lie inside one third (0.65 of peak bandwidth
- * inside one third - which is where a fresh process's allocations land - against 0.75-0.77).  This helper places n
- * buffers of nbytes[k] bytes in an arena of arena_bytes bytes, in the given order, each at a multiple
- * of 2 MiB, with equal gaps between consecutive buffers so that the first starts at 0 and the last
- * ends near the end of the arena.  nbytes[n] in, offsets[n] out (host).  The caller allocates the
- * arena (one allocation, e.g. most of the free device memory), hands `arena + offsets[k]` to
- * dadam_bind, and may use the gaps for anything else.
+/* Layout advice for HBM, part 1: equal distances.  Places n buffers of nbytes[k] bytes in a range of
+ * arena_bytes bytes, in the given order, each at a multiple of 2 MiB, with equal gaps between
+ * consecutive buffers so that the first starts at 0 and the last ends near the end of the range.
+ * nbytes[n] in, offsets[n] out (host).
  * Errors: DADAM_EINVAL if a pointer is null, n == 0, or the buffers do not fit. */
 int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t* offsets);
+
+/* Layout advice for HBM, part 2: where to put the buffers.  Measured on MI355X: the same step over
+ * the same bytes sustains 0.62-0.66 of peak bandwidth when the buffers it streams together all lie
+ * inside one third (96 GiB) of the device's physical memory - which is where a fresh process's
+ * allocations land - and 0.78-0.79 when every group of buffers that is streamed together lies half
+ * in one third and half in another.  The caller makes ONE allocation of arena_bytes bytes that covers
+ * nearly the whole device (within 16 GiB of device_total_bytes, so that offsets inside it are physical
+ * positions up to what was allocated before it); this helper then deals the buffers alternately over
+ * two regions, one ending 2 GiB below and one starting 2 GiB above the boundary between the first two
+ * thirds: buffers 0, 2, 4, ... below, 1, 3, 5, ... above, at equal distances inside each region
+ * (regions at least 64 GiB wide, wider when the buffers need it).  Any run of consecutive buffers -
+ * all sources, all outputs, one kind of state - is then split evenly.  When the arena does not cover
+ * the device or the buffers do not fit two thirds of it, they are placed at equal distances over the
+ * whole arena instead.  nbytes[n] in, offsets[n] out (host), every offset a multiple of 2 MiB.
+ * regions_out (may be null) receives lo0, hi0, lo1, hi1 of the two regions, or 0, arena_bytes, 0, 0 for
+ * the fall-back.  The caller hands `arena + offsets[k]` to dadam_bind and may use the space between
+ * the buffers for anything else.
+ * Errors: DADAM_EINVAL if a pointer is null, n == 0, or the buffers do not fit the arena at all. */
+int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes,
+                        uint64_t device_total_bytes, uint64_t* offsets, uint64_t* regions_out);
 
 /* Text of the last error recorded on this handle ("" if none).  With h == NULL: the text of the
  * last dadam_init failure of the calling thread.  The pointer stays valid until the next call on

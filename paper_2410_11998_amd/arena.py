@@ -56,17 +56,19 @@ class SpreadArena:
         self.base_offset = (-self.storage.data_ptr()) % unit            # start on a 2 MiB boundary
         self.span_bytes = span_bytes
         self.policy = "regions" if regions is not None else "window" if window is not None else "whole arena"
+        placed = None
         if regions is None and window is None and default_regions:
-            regions = two_thirds_regions(self.nbytes_rounded(nbytes, unit), span_bytes,
-                                         torch.cuda.mem_get_info(self.device)[1])
-            if regions is not None:
-                self.policy = "two thirds"
+            placed, used = B.dadam_place_offsets(nbytes, span_bytes, torch.cuda.mem_get_info(self.device)[1])
+            if len(used) == 2:
+                self.policy, regions = "two thirds", used
+            else:
+                placed = None
         self.regions_used = ([(int(lo), int(hi)) for lo, hi in regions] if regions is not None
                              else [(win_lo, win_hi)] if window is not None else [(0, span_bytes)])
         if regions is not None:
             for lo, hi in regions:
                 assert int(lo) % unit == 0 and int(lo) < int(hi) <= span_bytes, "region beyond the arena or not 2 MiB aligned"
-            self.offsets = deal_offsets(nbytes, regions)
+            self.offsets = placed if placed is not None else deal_offsets(nbytes, regions)
         elif window is not None:
             assert win_hi <= span_bytes, "window beyond the arena"
             self.offsets = [win_lo + o for o in B.dadam_spread_offsets(nbytes, win_hi - win_lo)]
@@ -110,18 +112,8 @@ def deal_offsets(nbytes: Sequence[int], regions: Sequence[Sequence[int]]) -> Lis
 
 def two_thirds_regions(rounded_nbytes: Sequence[int], span_bytes: int, total: int):
     """The two regions either side of the boundary between the first and the second third of the
-    device memory (total bytes), or None when the arena does not cover the device closely enough for its offsets to
-    be physical positions (within 16 GiB) or the buffers do not fit.  Each region is at least 64 GiB
-    wide (narrower ones measured slower) and starts / ends 2 GiB away from the boundary."""
-    if span_bytes < total - 16 * GIB:
-        return None
-    third = round(total / 3 / GIB) * GIB
-    margin = 2 * GIB
-    unit = 2 << 20
-    need = max(sum(rounded_nbytes[0::2]), sum(rounded_nbytes[1::2]))
-    width = max(64 * GIB, -(-int(need * 1.2) // unit) * unit)
-    lo0, hi0 = third - margin - width, third - margin
-    lo1, hi1 = third + margin, third + margin + width
-    if lo0 < 0 or hi1 > min(span_bytes, 2 * third):
-        return None
-    return [(lo0, hi0), (lo1, hi1)]
+    device memory (total bytes) that the library's placement advice (dadam_place_offsets) uses, or
+    None when it falls back to the whole arena: the arena does not cover the device closely enough
+    for its offsets to be physical positions, or the buffers do not fit."""
+    _offsets, regions = B.dadam_place_offsets(rounded_nbytes, span_bytes, total)
+    return regions if len(regions) == 2 else None

@@ -32,7 +32,8 @@ DADAM_WARN_NOT_COLUMN_STOCHASTIC = 1
 EXPORTS = [
     "dadam_init", "dadam_set_topology", "dadam_bind", "dadam_swap_x", "dadam_gossip_step",
     "dadam_gossip_step_range", "dadam_accumulate", "dadam_mix", "dadam_mix_consensus", "dadam_set_lr", "dadam_get_plan_info",
-    "dadam_slot_uses_tile_mode", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_last_error", "dadam_destroy",
+    "dadam_slot_uses_tile_mode", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_place_offsets", "dadam_last_error",
+    "dadam_destroy",
 ]
 
 
@@ -81,6 +82,8 @@ def _load() -> C.CDLL:
     lib.dadam_slot_uses_tile_mode.argtypes = [H, C.c_uint32]
     lib.dadam_pack_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
     lib.dadam_spread_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.POINTER(C.c_uint64)]
+    lib.dadam_place_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint64),
+                                        C.POINTER(C.c_uint64)]
     lib.dadam_last_error.argtypes = [H]
     lib.dadam_last_error.restype = C.c_char_p
     lib.dadam_destroy.argtypes = [H]
@@ -158,6 +161,19 @@ def dadam_spread_offsets(nbytes: Sequence[int], arena_bytes: int):
     if rc < 0:
         raise DadamError(rc, f"dadam_spread_offsets: {n} buffers of {sum(int(x) for x in nbytes)} bytes do not fit in {arena_bytes}")
     return [int(x) for x in o]
+
+
+def dadam_place_offsets(nbytes: Sequence[int], arena_bytes: int, device_total_bytes: int):
+    """Returns (offsets, regions) with regions = [(lo0, hi0), (lo1, hi1)], or [(0, arena_bytes)] for the fall-back."""
+    n = len(nbytes)
+    a = (C.c_uint64 * n)(*[int(x) for x in nbytes])
+    o = (C.c_uint64 * n)()
+    r = (C.c_uint64 * 4)()
+    rc = lib.dadam_place_offsets(a, n, int(arena_bytes), int(device_total_bytes), o, r)
+    if rc < 0:
+        raise DadamError(rc, f"dadam_place_offsets: {n} buffers of {sum(int(x) for x in nbytes)} bytes do not fit in {arena_bytes}")
+    regions = [(int(r[0]), int(r[1]))] + ([(int(r[2]), int(r[3]))] if r[3] else [])
+    return [int(x) for x in o], regions
 
 
 def dadam_init(n_rows: int, n_cols: int, d: int, offsets: Sequence[int], numels: Sequence[int],

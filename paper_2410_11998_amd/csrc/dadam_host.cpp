@@ -716,6 +716,45 @@ int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_byte
   return DADAM_OK;
 }
 
+int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t device_total_bytes,
+                        uint64_t* offsets, uint64_t* regions_out) {
+  if (!nbytes || !offsets || n == 0) return DADAM_EINVAL;
+  const uint64_t unit = 2ull << 20, gib = 1ull << 30;
+  std::vector<uint64_t> side[2];
+  uint64_t need[2] = {0, 0};
+  for (uint32_t k = 0; k < n; ++k) {
+    if (nbytes[k] > (1ull << 46)) return DADAM_EINVAL;
+    side[k & 1].push_back(nbytes[k]);
+    need[k & 1] += (nbytes[k] + unit - 1) / unit * unit;
+  }
+  const uint64_t third = (device_total_bytes + 3 * gib / 2) / (3 * gib) * gib;  // a third, to the nearest GiB
+  const uint64_t margin = 2 * gib;
+  const uint64_t most = need[0] > need[1] ? need[0] : need[1];
+  uint64_t width = (most + most / 5 + unit - 1) / unit * unit;                   // 20 % of room
+  if (width < 64 * gib) width = 64 * gib;
+  const bool covers = arena_bytes + 16 * gib >= device_total_bytes && third > margin;
+  const uint64_t top = arena_bytes < 2 * third ? arena_bytes : 2 * third;
+  if (covers && n >= 2 && third - margin >= width && third + margin + width <= top) {
+    const uint64_t lo[2] = {third - margin - width, third + margin};
+    for (int r = 0; r < 2; ++r) {
+      std::vector<uint64_t> off(side[r].size());
+      const int rc = dadam_spread_offsets(side[r].data(), (uint32_t)side[r].size(), width, off.data());
+      if (rc != DADAM_OK) return rc;
+      for (size_t j = 0; j < off.size(); ++j) offsets[2 * j + r] = lo[r] + off[j];
+    }
+    if (regions_out) {
+      regions_out[0] = lo[0]; regions_out[1] = lo[0] + width;
+      regions_out[2] = lo[1]; regions_out[3] = lo[1] + width;
+    }
+    return DADAM_OK;
+  }
+  if (regions_out) {
+    regions_out[0] = 0; regions_out[1] = arena_bytes;
+    regions_out[2] = 0; regions_out[3] = 0;
+  }
+  return dadam_spread_offsets(nbytes, n, arena_bytes, offsets);
+}
+
 const char* dadam_last_error(const dadam_handle* h) { return h ? h->err.c_str() : g_init_error.c_str(); }
 
 void dadam_destroy(dadam_handle* h) {

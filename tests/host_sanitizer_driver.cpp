@@ -5,6 +5,8 @@
 #include "dadam.h"
 #include "dadam_internal.h"
 #include <cstdio>
+#include <algorithm>
+#include <utility>
 #include <vector>
 #include <cmath>
 #include <random>
@@ -79,6 +81,26 @@ int main() {
   }
   std::vector<uint64_t> nb = {5, 1u << 21, 77, 3u << 20}; std::vector<uint64_t> off(4);
   (void)dadam_spread_offsets(nb.data(), 4, 1ull << 30, off.data());
+  // placement advice on random buffer lists: whatever it answers, buffers stay inside the arena,
+  // start at multiples of 2 MiB and do not overlap
+  for (int it = 0; it < 300; ++it) {
+    const uint32_t n = 1 + rng() % 130;
+    std::vector<uint64_t> sz(n), o(n);
+    for (auto& x : sz) x = (rng() % 5 == 0) ? (uint64_t)(rng() % 4096) << 20 : 1 + rng() % (3u << 20);
+    const uint64_t total = (uint64_t)(16 + rng() % 400) << 30;
+    const uint64_t arena = (rng() % 3 == 0) ? total - ((uint64_t)(rng() % 12) << 30) : (uint64_t)(1 + rng() % 300) << 30;
+    uint64_t reg[4];
+    if (dadam_place_offsets(sz.data(), n, arena, total, o.data(), (rng() & 1) ? reg : nullptr) != DADAM_OK) { ++n_err; continue; }
+    ++n_ok;
+    std::vector<std::pair<uint64_t, uint64_t>> iv;
+    for (uint32_t k = 0; k < n; ++k) {
+      if (o[k] % (2u << 20) != 0 || o[k] + sz[k] > arena + (2u << 20)) { printf("placement out of the arena\n"); return 1; }
+      iv.push_back({o[k], o[k] + sz[k]});
+    }
+    std::sort(iv.begin(), iv.end());
+    for (size_t k = 1; k < iv.size(); ++k)
+      if (iv[k].first < iv[k - 1].second) { printf("placement overlaps\n"); return 1; }
+  }
   printf("sanitizer driver finished: %d ok, %d rejected\n", n_ok, n_err);
   return 0;
 }

@@ -435,6 +435,8 @@ def test_two_region_placement_policy():
     regs = A.two_thirds_regions(sizes, 275 * GIB, total)
     assert regs == [(30 * GIB, 94 * GIB), (98 * GIB, 162 * GIB)]
     off = A.deal_offsets(sizes, regs)
+    placed, used = B.dadam_place_offsets(sizes, 275 * GIB, total)       # the C entry point gives the same answer
+    assert placed == off and used == regs
     for k, o in enumerate(off):
         lo, hi = regs[k % 2]
         assert lo <= o and o + sizes[k] <= hi and o % (2 << 20) == 0
@@ -449,5 +451,10 @@ def test_two_region_placement_policy():
     regs = A.two_thirds_regions(big, 275 * GIB, total)
     assert regs is not None and regs[0][1] - regs[0][0] >= int(28 * 2 * GIB * 1.2) and regs[0][0] >= 0 and regs[1][1] <= 192 * GIB
     assert A.two_thirds_regions([3 * GIB] * 56, 275 * GIB, total) is None
-    # an arena that does not cover the device gives no physical positions
+    # an arena that does not cover the device gives no physical positions: equal distances over all of it
     assert A.two_thirds_regions(sizes, 200 * GIB, total) is None
+    placed, used = B.dadam_place_offsets(sizes, 200 * GIB, total)
+    assert used == [(0, 200 * GIB)] and placed == B.dadam_spread_offsets(sizes, 200 * GIB)
+    assert B.lib.dadam_place_offsets(None, 1, 100, 100, None, None) == B.DADAM_EINVAL
+    with pytest.raises(B.DadamError):
+        B.dadam_place_offsets([5 << 20, 5 << 20], 8 << 20, 288 * GIB)
