@@ -234,8 +234,10 @@ int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_byte
  * nearly the whole device (within 16 GiB of device_total_bytes, so that offsets inside it are physical
  * positions up to what was allocated before it); this helper then deals the buffers alternately over
  * two regions, one ending 2 GiB below and one starting 2 GiB above the boundary between the first two
- * thirds: buffers 0, 2, 4, ... below, 1, 3, 5, ... above, at equal distances inside each region
- * (regions at least 64 GiB wide, wider when the buffers need it).  Any run of consecutive buffers -
+ * thirds: buffers 0, 2, 4, ... below, 1, 3, 5, ... above, spread over each region (regions at least
+ * 64 GiB wide, wider when the buffers need it) and staggered inside their gaps by a fixed pseudo-random
+ * number of 2 MiB steps, so that the bases do not form an arithmetic progression (for some distances
+ * between bases that costs 3-4 %).  Any run of consecutive buffers -
  * all sources, all outputs, one kind of state - is then split evenly.  When the arena does not cover
  * the device or the buffers do not fit two thirds of it, they are placed at equal distances over the
  * whole arena instead.  nbytes[n] in, offsets[n] out (host), every offset a multiple of 2 MiB.

@@ -27,12 +27,13 @@ from . import binding as B
 class SpreadArena:
     def __init__(self, nbytes: Sequence[int], device, span_bytes: Optional[int] = None, keep_free_bytes: int = 12 << 30,
                  window: Optional[Sequence[int]] = None, regions: Optional[Sequence[Sequence[int]]] = None,
-                 default_regions: bool = True):
+                 default_regions: bool = True, offsets: Optional[Sequence[int]] = None):
         """nbytes: sizes of the buffers, in the order they are laid out.  span_bytes: size of the
         arena; default is the free device memory minus ``keep_free_bytes``, but never less than the
         packed size.  window = (lo, hi) in bytes: spread the buffers over that part of the arena only.
         regions = [(lo, hi), ...]: deal the buffers round-robin over these parts.  With neither, the two
-        regions described above are used when they apply (default_regions=False: never)."""
+        regions described above are used when they apply (default_regions=False: never).
+        offsets: an explicit placement (one offset per buffer, multiples of 2 MiB, inside the arena)."""
         self.device = torch.device(device)
         unit = 2 << 20
         packed = sum(-(-int(n) // unit) * unit for n in nbytes)
@@ -57,7 +58,10 @@ class SpreadArena:
         self.span_bytes = span_bytes
         self.policy = "regions" if regions is not None else "window" if window is not None else "whole arena"
         placed = None
-        if regions is None and window is None and default_regions:
+        if offsets is not None:
+            self.policy, placed = "given offsets", [int(o) for o in offsets]
+            regions = [(min(placed), max(o + int(n) for o, n in zip(placed, nbytes)))]
+        elif regions is None and window is None and default_regions:
             placed, used = B.dadam_place_offsets(nbytes, span_bytes, torch.cuda.mem_get_info(self.device)[1])
             if len(used) == 2:
                 self.policy, regions = "two thirds", used

@@ -740,6 +740,19 @@ int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes
       std::vector<uint64_t> off(side[r].size());
       const int rc = dadam_spread_offsets(side[r].data(), (uint32_t)side[r].size(), width, off.data());
       if (rc != DADAM_OK) return rc;
+      // Stagger the buffers inside their gaps by a fixed pseudo-random number of 2 MiB steps, so that their
+      // bases do not form an arithmetic progression: for some distances (660 MiB, 884 MiB between 476 MiB
+      // buffers) a progression costs 3-4 % of bandwidth, staggered bases never did.  A buffer moves forward
+      // by less than the gap behind it; the last one stays where it is.
+      for (size_t j = 0; j + 1 < off.size(); ++j) {
+        const uint64_t end = off[j] + (side[r][j] + unit - 1) / unit * unit;
+        const uint64_t slots = off[j + 1] > end ? (off[j + 1] - end) / unit : 0;
+        uint64_t z = ((uint64_t)j + 1) * 0x9E3779B97F4A7C15ull;  // a fixed 64-bit mix of the buffer's number
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        if (slots > 1) off[j] += z % slots * unit;
+      }
       for (size_t j = 0; j < off.size(); ++j) offsets[2 * j + r] = lo[r] + off[j];
     }
     if (regions_out) {

@@ -68,15 +68,16 @@ class GpuSim:
         dts = [pdt] * n_cols + ([] if inplace else [pdt] * n_rows) + [torch.float32] * (n_rows * (3 if hp.s > 1 else 2))
         if spread:
             # the benchmark's layout: one arena over most of the free memory, buffers at equal distances
-            from paper_2410_11998_amd.arena import SpreadArena, two_thirds_regions
+            from paper_2410_11998_amd.arena import SpreadArena
             sizes = [d * (2 if dt == torch.bfloat16 else 4) for dt in dts]
             keep = 48 << 30                                         # room for the gradients and temporaries of the test
             free, total = torch.cuda.mem_get_info(self.dev)
-            # the benchmark's two regions, as far as the smaller arena of the test reaches
-            regs = two_thirds_regions(SpreadArena.nbytes_rounded(sizes, 2 << 20), total, total)
-            if regs is not None and regs[-1][1] > free - keep:
-                regs = None
-            self.arena = SpreadArena(sizes, self.dev, keep_free_bytes=keep, regions=regs)
+            # the benchmark's placement (computed for an arena over the whole device), as far as the
+            # smaller arena of the test reaches
+            placed, _regions = B.dadam_place_offsets(sizes, total, total)
+            if max(o + n for o, n in zip(placed, sizes)) > free - keep:
+                placed = None
+            self.arena = SpreadArena(sizes, self.dev, keep_free_bytes=keep, offsets=placed)
             bufs = self.arena.views(dts)
             for t in bufs:
                 t.zero_()

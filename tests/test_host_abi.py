@@ -427,25 +427,30 @@ def test_c99_client_compiles_links_and_agrees_with_the_binding(tmp_path):
 
 def test_two_region_placement_policy():
     """Placement advice for device buffers (memory management, no GPU needed): two regions either
-    side of the boundary between the first two thirds of the device memory, buffers dealt alternately."""
+    side of the boundary between the first two thirds of the device memory, buffers dealt alternately
+    and staggered inside their gaps."""
     from paper_2410_11998_amd import arena as A
     GIB = 1 << 30
     total = 288 * GIB - (20 << 20)
     sizes = [476 << 20] * 112                                   # configuration 2 with two gradient sets
     regs = A.two_thirds_regions(sizes, 275 * GIB, total)
     assert regs == [(30 * GIB, 94 * GIB), (98 * GIB, 162 * GIB)]
-    off = A.deal_offsets(sizes, regs)
-    placed, used = B.dadam_place_offsets(sizes, 275 * GIB, total)       # the C entry point gives the same answer
-    assert placed == off and used == regs
+    off, used = B.dadam_place_offsets(sizes, 275 * GIB, total)
+    assert used == regs and (off, used) == B.dadam_place_offsets(sizes, 275 * GIB, total)      # deterministic
+    even = A.deal_offsets(sizes, regs)                          # the same regions at equal distances
     for k, o in enumerate(off):
         lo, hi = regs[k % 2]
         assert lo <= o and o + sizes[k] <= hi and o % (2 << 20) == 0
+        assert even[k] <= o and (k + 2 >= len(off) or o + sizes[k] <= even[k + 2]), "a buffer left its own gap"
     spans = sorted((o, o + n) for o, n in zip(off, sizes))
     assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))
+    # the bases of a region do not form an arithmetic progression
+    below = [o for k, o in enumerate(off) if k % 2 == 0]
+    assert len({b - a for a, b in zip(below, below[1:])}) > len(below) // 2
     # any run of consecutive buffers is split evenly over the two sides
     for start, count in ((0, 16), (16, 16), (0, 32), (80, 32)):
-        below = sum(1 for k in range(start, start + count) if off[k] < 96 * GIB)
-        assert below == count // 2
+        n_below = sum(1 for k in range(start, start + count) if off[k] < 96 * GIB)
+        assert n_below == count // 2
     # large buffers widen the regions; what cannot fit two thirds falls back (None)
     big = [2 * GIB] * 56
     regs = A.two_thirds_regions(big, 275 * GIB, total)
