@@ -463,3 +463,29 @@ def test_two_region_placement_policy():
     assert B.lib.dadam_place_offsets(None, 1, 100, 100, None, None) == B.DADAM_EINVAL
     with pytest.raises(B.DadamError):
         B.dadam_place_offsets([5 << 20, 5 << 20], 8 << 20, 288 * GIB)
+
+
+def test_device_access_helpers_on_the_cpu_under_sanitizers(tmp_path):
+    """The kernels' vector load / store helpers (the lane-to-element layout, clipping at segment
+    edges, the two-group layout of 8-element lanes) compiled for the host from the kernel source's
+    own text and run on exact-size buffers under ASan + UBSan."""
+    import shutil
+    import subprocess
+    from paper_2410_11998_amd import build as bld
+    clang = "/opt/rocm/llvm/bin/clang++" if os.path.exists("/opt/rocm/llvm/bin/clang++") else shutil.which("clang++")
+    if clang is None:
+        pytest.skip("no clang++ (the helpers use clang vector extensions)")
+    src = open(os.path.join(bld.CSRC, "dadam_kernels.hip")).read()
+    a = src.index("typedef float f4 __attribute__((ext_vector_type(4)));")
+    b = src.index("// Algorithm 3, lines 6-13, for one element.")
+    b = src.rindex("// ----", a, b)
+    (tmp_path / "helpers.inc").write_text(src[a:b])
+    exe = str(tmp_path / "emulate")
+    cmd = [clang, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-I", str(tmp_path), os.path.join(ROOT, "tests", "emulate_access_helpers.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    env = {k: v for k, v in os.environ.items()}
+    env["ASAN_OPTIONS"] = "detect_leaks=0"
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=600)
+    assert r.returncode == 0 and "fails 0" in r.stdout, (r.stdout[-1500:], r.stderr[-1500:])
+    assert r.stdout.count(" ok") == 10
