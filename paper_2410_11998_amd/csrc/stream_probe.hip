@@ -59,7 +59,10 @@ __global__ __launch_bounds__(256) void k_streams(char* base, Place p, int n_read
 // v written too).  96 arrays: [0,16) sources, [16,32) g, [32,48) outputs, [48,96) m, v, b per row.
 constexpr int kRows = 16;
 constexpr int kStepArrays = 6 * kRows;
-template <bool FOLD>
+// BLOCKED: the three state arrays of a row are one array of 3 KiB blocks (m, v, b of a tile side by
+// side) instead of three arrays - 64 streams instead of 96 (arrays 48 + 3 i hold row i's blocks and
+// are three times as long; arrays 48 + 3 i + 1, + 2 are unused).
+template <bool FOLD, bool BLOCKED = false>
 __global__ __launch_bounds__(256) void k_step_shape(char* base, Place p) {
   const size_t t = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -69,9 +72,15 @@ __global__ __launch_bounds__(256) void k_step_shape(char* base, Place p) {
   __syncthreads();
   for (int i = wave; i < kRows; i += 4) {
     const f4* gp = reinterpret_cast<const f4*>(base + place(p, kRows + i)) + t * 64 + lane;
-    f4* mp = reinterpret_cast<f4*>(base + place(p, 3 * kRows + 3 * i + 0)) + t * 64 + lane;
-    f4* vp = reinterpret_cast<f4*>(base + place(p, 3 * kRows + 3 * i + 1)) + t * 64 + lane;
-    f4* bp = reinterpret_cast<f4*>(base + place(p, 3 * kRows + 3 * i + 2)) + t * 64 + lane;
+    f4 *mp, *vp, *bp;
+    if (BLOCKED) {
+      f4* blk = reinterpret_cast<f4*>(base + place(p, 3 * kRows + 3 * i)) + t * 192;
+      mp = blk + lane; vp = blk + 64 + lane; bp = blk + 128 + lane;
+    } else {
+      mp = reinterpret_cast<f4*>(base + place(p, 3 * kRows + 3 * i + 0)) + t * 64 + lane;
+      vp = reinterpret_cast<f4*>(base + place(p, 3 * kRows + 3 * i + 1)) + t * 64 + lane;
+      bp = reinterpret_cast<f4*>(base + place(p, 3 * kRows + 3 * i + 2)) + t * 64 + lane;
+    }
     f4 g = *gp, m = *mp, v = *vp, b = *bp;
     f4 x = lds[i * 64 + lane] + lds[((i + 1) % kRows) * 64 + lane] + lds[((i + 2) % kRows) * 64 + lane] +
            lds[((i + 4) % kRows) * 64 + lane] + lds[((i + 8) % kRows) * 64 + lane];
@@ -159,6 +168,20 @@ void run_step(const Arena& a, const char* where, size_t off, Place p, size_t len
   report(shape, where, (double)len * kRows * (FOLD ? 9 : 7), ms);
 }
 
+// The blocked form of the step shape: every array slot must be able to hold 3 * len bytes.
+template <bool FOLD>
+void run_step_blocked(const Arena& a, const char* where, size_t off, Place p, size_t len) {
+  const char* shape = FOLD ? "step shape, fold, blocked state" : "step shape, plain, blocked state";
+  if (len % 1024 != 0 || len / 1024 > 0x7fffffffull || !fits(a, off, p, kStepArrays, 3 * len)) {
+    printf("%-34s %-34s skipped (does not fit the allocation)\n", shape, where);
+    return;
+  }
+  const unsigned grid = (unsigned)(len / 1024);
+  char* base = a.p + off;
+  const double ms = time_ms([&] { hipLaunchKernelGGL((k_step_shape<FOLD, true>), dim3(grid), dim3(256), 0, 0, base, p); });
+  report(shape, where, (double)len * kRows * (FOLD ? 9 : 7), ms);
+}
+
 // n arrays at equal distances over span bytes (2 MiB granularity)
 Place even(size_t span, int n) {
   const size_t stride = span / (size_t)n / (2 * kMiB) * (2 * kMiB);
@@ -218,6 +241,10 @@ int main(int argc, char** argv) {
   run_step<true>(a, "packed at 0", 0, packed(len), len);
   run_step<true>(a, "equal distances, everything", 0, even(whole, kStepArrays), len);
   run_step<true>(a, two, t_off, dealt(t_width, t_apart, kStepArrays), len);
+  // the same with the optimizer state of a row in one blocked array (regions wide enough for 3 * len per slot)
+  run_step<false>(a, "dealt over [6,94) + [98,186) GiB", 6 * kGiB, dealt(88 * kGiB, 92 * kGiB, kStepArrays), len);
+  run_step_blocked<false>(a, "dealt over [6,94) + [98,186) GiB", 6 * kGiB, dealt(88 * kGiB, 92 * kGiB, kStepArrays), len);
+  run_step_blocked<true>(a, "dealt over [6,94) + [98,186) GiB", 6 * kGiB, dealt(88 * kGiB, 92 * kGiB, kStepArrays), len);
   if (!quick) {
     // where in physical memory: packed (44.5 GiB) at several offsets, equal distances over several windows
     run_step<false>(a, "packed at 96 GiB", 96 * kGiB, packed(len), len);
