@@ -84,7 +84,8 @@ __device__ __forceinline__ void store_elem(void* base, uint64_t e, float v) {
 // read as zero.
 // Streaming accesses: every global datum of a step is touched exactly once, so full-group
 // accesses may carry the non-temporal hint (NT) and leave the caches to nobody in particular.
-// Which classes of access carry the hint when a handle streams (measured: all of them):
+// Which classes of access carry the hint when a handle streams (all eight combinations measured:
+// the hints on the stream loads and on the stores carry the gain, the one on source loads is neutral):
 constexpr bool kNtSource = true;  // parameter (source) loads
 constexpr bool kNtStream = true;  // gradient / moment / accumulator loads
 constexpr bool kNtStore = true;   // all stores
