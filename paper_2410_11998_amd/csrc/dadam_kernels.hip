@@ -13,10 +13,12 @@
 //             memory (a node's own parameters plus receive buffers: no source is shared by two rows).
 //   k_acc     accumulate / fold only (Algorithm 3 lines 9-13).
 //
-// Every access of a full tile is a 128-bit load or store per lane; lanes at the ragged edge of a
-// segment fall back to element accesses.  Neighbour lists are read once per row as one coalesced
-// load (one entry per lane) and handed out with readlane, so the inner loop has no dependent
-// scalar memory traffic.
+// Every access of a full tile is a 128-bit (float32) or 64-bit (bfloat16) load or store per lane,
+// laid out so that each instruction of a wavefront covers one contiguous run of memory; lanes at
+// the ragged edge of a segment fall back to element accesses.  Neighbour lists are read once per
+// row as one coalesced load (one entry per lane) and handed out with readlane, so the inner loop
+// has no dependent scalar memory traffic - which also means that no lane may leave a wavefront
+// before the last readlane (see direct_body).
 #include <hip/hip_runtime.h>
 
 #include "dadam_internal.h"
