@@ -7,13 +7,17 @@ workload: one call of dadam_gossip_step (all rows, all elements) followed by the
 ping-pong parameter buffers.  Inputs (parameters, a small pool of pre-generated gradient sets,
 zero moments) are resident in HBM before the timed region starts.  Prints ONE JSON line.
 
-The default workload is the benchmark's configuration 2 (16 replicas, static exponential graph,
-GPT-2-small tensor shapes, float32, s = 4); --config selects 1..5.
+The headline workload is the benchmark's configuration 2 (16 replicas, static exponential graph,
+GPT-2-small tensor shapes, float32, s = 4); --config selects 1..5.  Without --config the same line
+also carries, under "per_config", the same measurement of configurations 3, 4 and 5 (each with its
+own step count, buffers freed in between) and, under "packed_frac", configuration 2 again with one
+ordinary allocation per buffer instead of the placed arena.
 
 Other measurements share the set-up (none of them is the benchmark's value): --path selects another
 call sequence (unfused, mix, mix_consensus, accumulate, buckets), --bucket-streams and
---standin-backward shape the bucket sequence, --graph replays a recorded HIP graph, --layout packed
-uses one ordinary allocation per buffer, --mode forces a kernel.  See --help.
+--standin-backward shape the bucket sequence, --graph replays a recorded HIP graph, --layout selects
+where the buffers sit in HBM, --prealloc-gib allocates that much first (a job's weights and
+activations), --mode forces a kernel.  See --help.
 """
 
 from __future__ import annotations
@@ -30,17 +34,27 @@ if ROOT not in sys.path:
 
 HBM_PEAK_BYTES_PER_S = 8.0e12   # MI355X HBM3E, published peak
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, each in a run of
-# its own, each scaled by what the same counter reads for a plain 1 GiB device copy: FETCH_SIZE x 2.000,
-# WRITE_SIZE x 1.000), by workload and phase of the accumulation loop.  The summaries these come from
-# are profiles/fused_step_<workload>.txt.  They cannot be measured inside this script, so they are
-# quoted; a workload or kernel shape without a measurement reports null.
-MEASURED_TRAFFIC_BYTES = {
-    "cfg2_exp16_gpt2small": {"loopstart": 47784529742, "plain": 55747879784, "fold": 71676151167},
-    "cfg3_nodeshare_gpt2medium": {"loopstart": 11354285401, "plain": 12773537619, "fold": 15612116211},
-    "cfg4_onepeer64_resnet50": {"loopstart": 39255220798, "fold": 58882770772},
-    "cfg5_ring8_gpt2large_bf16": {"loopstart": 111464158248, "plain": 136232861925, "fold": 185794734270},
-}
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, each in a run of its
+# own, each scaled by what the same counter reads for a plain 1 GiB device copy) cannot be measured
+# inside this script.  paper_2410_11998_amd/rocprof_summary.py writes them, per workload, kernel and
+# phase, into profiles/hbm_traffic.txt from the profiler's own CSV files; the line quotes them only
+# for the very kernel shape that was profiled and says where they come from.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic():
+    """{(workload, kernel): {phase: (bytes, source)}} from profiles/hbm_traffic.txt; empty if absent."""
+    table = {}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                if line.startswith("#") or not line.strip():
+                    continue
+                workload, kernel, phase, nbytes, source = line.split()
+                table.setdefault((workload, kernel), {})[phase] = (float(nbytes), source)
+    except OSError:
+        pass
+    return table
 
 
 def phase_of(t: int, s: int) -> str:
@@ -138,66 +152,26 @@ def host_cpu():
     return model, n
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2)
-    ap.add_argument("--mode", choices=["auto", "tile", "direct"], default="auto")
-    ap.add_argument("--inplace", action="store_true", help="update parameters in place instead of ping-pong")
-    ap.add_argument("--pool", type=int, default=2, help="number of pre-generated gradient sets cycled through")
-    ap.add_argument("--path", choices=["fused", "unfused", "mix", "mix_consensus", "accumulate", "buckets"], default="fused",
-                    help="fused: one dadam_gossip_step per iteration (the benchmark); unfused: dadam_gossip_step without "
-                         "accumulation followed by dadam_accumulate; mix: dadam_mix only; accumulate: dadam_accumulate only; "
-                         "buckets: the fused step issued tensor range by tensor range (--bucket-mb)")
-    ap.add_argument("--bucket-mb", type=float, default=25.0, help="target bucket size for --path buckets")
-    ap.add_argument("--bucket-streams", type=int, default=1,
-                    help="--path buckets: deal the buckets of a step over that many streams (1: the step's own stream)")
-    ap.add_argument("--standin-backward", type=int, default=0,
-                    help="--path buckets: before each bucket's update run an N x N bfloat16 matmul on the step's stream as a "
-                         "stand-in for that bucket's backward pass; with --bucket-streams >= 2 the updates go to side "
-                         "streams and overlap the next stand-in (the value then is not the benchmark's metric)")
-    ap.add_argument("--standin-only", action="store_true", help="with --standin-backward: skip the updates (the stand-in alone)")
-    ap.add_argument("--layout", choices=["spread", "whole", "packed"], default="spread",
-                    help="spread: one arena over most of the free HBM, buffers dealt alternately over two regions either "
-                         "side of the boundary between the first two thirds of the memory (fastest, see "
-                         "paper_2410_11998_amd/arena.py); whole: the same arena, buffers at equal distances over all "
-                         "of it; packed: one ordinary allocation per buffer")
-    ap.add_argument("--span-gib", type=int, default=0, help="arena size for --layout spread (default: free memory minus 12 GiB)")
-    ap.add_argument("--window-gib", type=int, nargs=2, default=None, metavar=("LO", "HI"),
-                    help="--layout spread: use only [LO, HI) GiB of the arena")
-    ap.add_argument("--regions-gib", type=int, nargs="+", default=None, metavar="LO HI",
-                    help="--layout spread: deal the buffers round-robin over the windows [LO, HI) GiB of the arena")
-    ap.add_argument("--scale-div", type=int, default=1, help="divide tensor dimensions (debugging only)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--graph", action="store_true",
-                    help="record a whole number of accumulation loops in a HIP graph once and time its replays "
-                         "(launch gaps of --path buckets); per-launch times then are replay averages")
-    ap.add_argument("--repeats", type=int, default=5,
-                    help="after the timed region, time that many minus one further regions of the same length and "
-                         "report all of them (median and minimum) next to the first, which stays the reported value")
-    ap.add_argument("--cpu-sample", type=int, default=None, help="coordinates per row given to the CPU oracle")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run plain device copies of a known size (1 GiB read + 1 GiB written each), so that "
-                         "profiler byte counters can be scaled by what they read for a known transfer")
-    args = ap.parse_args()
+def kernel_name(info, tile_mode: bool, wl, path: str) -> str:
+    """Name of the kernel shape a launch uses, as the profile summaries spell it."""
+    dt = {"f32": "TF32", "bf16": "TBF16"}
+    nt = "true" if info.streaming else "false"
+    if path in ("mix", "mix_consensus"):
+        return f"k_tile<{dt[wl.param_dtype]},{dt[wl.grad_dtype]},{info.mix_waves},{info.mix_vectors},{nt}>" if tile_mode else \
+               f"k_direct<{dt[wl.param_dtype]},{dt[wl.grad_dtype]},{nt}>"
+    if tile_mode:
+        return f"k_tile<{dt[wl.param_dtype]},{dt[wl.grad_dtype]},{info.tile_waves},{info.tile_vectors},{nt}>"
+    return f"k_direct<{dt[wl.param_dtype]},{dt[wl.grad_dtype]},{nt}>"
 
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; all replicas of the simulated run (or one node's share) live in "
-              "one HBM and there is no multi-GPU path to time. Use --gpus 1.", file=sys.stderr)
-        return 2
 
+def measure(args, want_cpu_sample: bool):
+    """Set up one workload, time it, free everything.  Returns (result dict, cpu sample or None)."""
     import numpy as np
     import torch
     from paper_2410_11998_amd import binding as B
     from paper_2410_11998_amd import workloads as WL
 
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        return 2
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
     wl = WL.workload(args.config, scale_div=args.scale_div)
     K = args.steps if args.steps is not None else wl.steps
     W = args.warmup
@@ -209,30 +183,28 @@ def main() -> int:
     inplace = args.inplace or R != C
 
     # ---- resident inputs ----------------------------------------------------------------
+    prealloc = torch.empty(args.prealloc_gib << 30, dtype=torch.uint8, device=dev) if args.prealloc_gib else None
     # Buffers in layout order: sources (own replicas, then receive buffers), outputs (unless in
     # place), m_hat, v_hat, b, then the gradient pool.
     n_pool = max(1, args.pool)
     kinds = [("x_src", pdt)] * C + ([] if inplace else [("x_dst", pdt)] * R) + [("m", torch.float32)] * R + \
             [("v", torch.float32)] * R + ([("b", torch.float32)] * R if wl.s > 1 else []) + [("g", gdt)] * (R * n_pool)
     esize = {torch.float32: 4, torch.bfloat16: 2}
-    if args.layout in ("spread", "whole"):
+    arena = None
+    placement_advice = None
+    if args.layout in ("spread", "compact", "whole"):
         from paper_2410_11998_amd.arena import SpreadArena
-        arena = SpreadArena([d * esize[dt] for _, dt in kinds], dev,
-                            span_bytes=(args.span_gib << 30) if args.span_gib else None,
-                            window=[g << 30 for g in args.window_gib] if args.window_gib else None,
-                            regions=[(args.regions_gib[2 * r] << 30, args.regions_gib[2 * r + 1] << 30)
-                                     for r in range(len(args.regions_gib) // 2)] if args.regions_gib else None,
-                            default_regions=(args.layout == "spread"))
+        arena = SpreadArena([d * esize[dt] for _, dt in kinds], dev, two_regions=(args.layout != "whole"),
+                            compact=(args.layout == "compact"))
         bufs = arena.views([dt for _, dt in kinds])
-        span_gib = arena.span_bytes / 2 ** 30
-        gib = lambda v: f"{v / 2 ** 30:.0f}"
-        used = sorted({(lo, hi) for lo, hi in getattr(arena, "regions_used", [])})
-        hbm_layout = (f"{arena.policy}: " + " + ".join(f"[{gib(lo)}, {gib(hi)})" for lo, hi in used) +
-                      f" GiB of a {span_gib:.0f} GiB allocation")
+        hbm_layout = arena.describe()
+        placement_advice = {B.DADAM_PLACE_TWO_REGIONS: "two regions", B.DADAM_PLACE_ARENA_ELSEWHERE: "arena elsewhere",
+                            B.DADAM_PLACE_TOO_LARGE: "too large"}.get(arena.advice, "none")
     else:
         bufs = [torch.empty(d, dtype=dt, device=dev) for _, dt in kinds]
-        span_gib = None
-        hbm_layout = "packed: one allocation per buffer"
+        hbm_layout = "packed: one ordinary allocation per buffer"
+    if args.prealloc_gib:
+        hbm_layout += f"; {args.prealloc_gib} GiB allocated first"
     take = lambda name: [b for (k, _), b in zip(kinds, bufs) if k == name]
     x_src = take("x_src")
     x_dst = x_src[:R] if inplace else take("x_dst")
@@ -265,15 +237,16 @@ def main() -> int:
     B.dadam_bind(h, x_src, x_dst, m_hat, v_hat, acc)
     flags = B.DADAM_FUSE_ACCUM | {"auto": 0, "tile": B.DADAM_FORCE_TILE, "direct": B.DADAM_FORCE_DIRECT}[args.mode]
     tile_mode = (args.mode == "tile") or (args.mode == "auto" and B.dadam_slot_uses_tile_mode(h, 0))
+    info = B.dadam_get_plan_info(h)
+    tables = [B.grad_table(h, g) for g in pool]          # pointer tables marshalled once, as a training loop would
 
     # sample for the CPU baseline, taken before anything is updated
     # about 1e9 replica-param updates of CPU work: 2^26 / R coordinates per row
-    ns = min(args.cpu_sample if args.cpu_sample else (1 << 26) // R, d)
-    if not args.no_cpu_baseline:
-        x0_sample = [x[:ns].to(torch.float64).cpu().numpy() for x in x_src]
-        g_samples = [[g[:ns].to(torch.float64).cpu().numpy() for g in gs] for gs in pool]
-
-    stream = None      # read at call time: a graph capture changes torch's current stream
+    sample = None
+    if want_cpu_sample:
+        ns = min(args.cpu_sample if args.cpu_sample else (1 << 26) // R, d)
+        sample = (wl, ns, [x[:ns].to(torch.float64).cpu().numpy() for x in x_src],
+                  [[g[:ns].to(torch.float64).cpu().numpy() for g in gs] for gs in pool], csrs)
 
     # tensor ranges of about --bucket-mb of parameters each, in layout order (the granularity at which
     # the paper's implementation updates and communicates)
@@ -293,10 +266,11 @@ def main() -> int:
     if args.standin_backward > 0 and args.path == "buckets":
         standin = torch.randn(args.standin_backward, args.standin_backward, device=dev, dtype=torch.bfloat16)
         standin_out = torch.empty_like(standin)
+    launches_per_step = len(buckets) if args.path == "buckets" else 2 if args.path == "unfused" else 1
 
     def one_step(t: int):
-        stream = B.current_stream()
-        g = pool[t % len(pool)]
+        stream = B.current_stream()      # read at call time: a graph capture changes torch's current stream
+        g = tables[t % len(tables)]
         slot = wl.slot_of_step(t)
         if args.path == "fused":
             B.dadam_gossip_step(h, slot, g, t, flags, stream)
@@ -394,6 +368,7 @@ def main() -> int:
     elapsed = time.perf_counter() - t_begin
 
     region_ms = [elapsed / K * 1e3]
+    issue_s = []                    # host time of the call loop alone (nothing waited for), per region
     for _ in range(max(0, args.repeats - 1)):
         torch.cuda.synchronize()
         r0 = time.perf_counter()
@@ -404,6 +379,7 @@ def main() -> int:
         else:
             for r in range(K // L):
                 graph.replay()
+        issue_s.append(time.perf_counter() - r0)
         torch.cuda.synchronize()
         region_ms.append((time.perf_counter() - r0) / K * 1e3)
 
@@ -417,13 +393,17 @@ def main() -> int:
     value = replica_params * K / elapsed
     bytes_per_launch = replica_params * sum(path_bytes_per_replica_param(wl, p, args.path) for p in phases) / K
     achieved = bytes_per_launch / avg_kernel_s
-    traffic = None
-    table = MEASURED_TRAFFIC_BYTES.get(wl.name)
-    if table is not None and args.mode == "auto" and args.path == "fused" and all(p in table for p in phases):
-        traffic = sum(table[p] for p in phases) / K
     by_phase = {}
     for p, ms in zip(phases, kernel_ms):
         by_phase.setdefault(p, []).append(ms)
+
+    # counter-measured HBM bytes, only for the kernel shape that was profiled
+    kname = kernel_name(info, tile_mode, wl, args.path)
+    traffic, traffic_source = None, None
+    table = measured_traffic().get((wl.name, kname))
+    if table is not None and args.path == "fused" and all(p in table for p in phases):
+        traffic = sum(table[p][0] for p in phases) / K
+        traffic_source = f"{sorted({table[p][1] for p in phases})[0]} ({kname}; rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not this run)"
 
     out = {
         "metric": "replica-params updated/sec for fused gossip+Adam step",
@@ -433,7 +413,10 @@ def main() -> int:
         "steps": K,
         "warmup": W,
         "ms_per_step": elapsed / K * 1e3,
-        "ms_per_step_regions": {"all": region_ms, "median": sorted(region_ms)[len(region_ms) // 2], "min": min(region_ms)},
+        "ms_per_step_regions": {"n": len(region_ms), "median": sorted(region_ms)[len(region_ms) // 2], "min": min(region_ms),
+                                "max": max(region_ms)},
+        # host time of one library call through the Python binding, nothing waited for (None: one region only)
+        "host_us_per_call": (min(issue_s) / (K * launches_per_step) * 1e6) if issue_s and graph is None else None,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -441,9 +424,10 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": wl.name, "param_dtype": wl.param_dtype, "grad_dtype": wl.grad_dtype, "state_dtype": "f32", "n_rows": R, "n_sources": C, "d": d, "tensors": len(layout.names), "topology": wl.topology,
-            "accum_s": wl.s, "kernel": ("k_tile" if tile_mode else "k_direct"), "path": args.path,
-            "launches_per_step": (len(buckets) if args.path == "buckets" else 2 if args.path == "unfused" else 1), "x_buffers": "in-place" if inplace else "ping-pong",
-            "hbm_layout": hbm_layout,
+            "accum_s": wl.s, "kernel": kname, "lds_bytes_per_workgroup": int(info.lds_bytes_tile) if tile_mode else 0,
+            "device_lds_limit": int(info.lds_limit_bytes), "device_xcds": int(info.n_xcds), "path": args.path,
+            "launches_per_step": launches_per_step, "x_buffers": "in-place" if inplace else "ping-pong",
+            "hbm_layout": hbm_layout, "placement_advice": placement_advice,
             "grad_pool": len(pool),
             "issue": "eager" if graph is None else f"graph of {L} iterations, replayed",
             "bucket_streams": max(1, len(side)) if args.path == "buckets" else None,
@@ -451,7 +435,7 @@ def main() -> int:
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK_BYTES_PER_S / 1e9, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_BYTES_PER_S, "traffic": traffic,
+            "frac": achieved / HBM_PEAK_BYTES_PER_S, "traffic": traffic, "traffic_source": traffic_source,
             "algorithmic_bytes_per_launch": bytes_per_launch, "avg_launch_ms": avg_kernel_s * 1e3,
             "ms_by_phase": {p: sum(v) / len(v) for p, v in by_phase.items()},
         },
@@ -467,11 +451,112 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if not args.no_cpu_baseline:
-        del x_src, x_dst, m_hat, v_hat, acc, pool, gflat, bufs
-        if args.layout in ("spread", "whole"):
-            del arena
-        torch.cuda.empty_cache()
+    return out, sample
+
+
+def measure_and_release(args, want_cpu_sample: bool):
+    """measure(), then make sure its device memory is back with the driver: the next measurement places
+    its buffers by what is in use at that moment."""
+    import gc
+    import torch
+    res = measure(args, want_cpu_sample)
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    return res
+
+
+def brief(res: dict) -> dict:
+    """What "per_config" keeps of a measurement."""
+    return {"workload": res["config"]["workload"], "kernel": res["config"]["kernel"], "steps": res["steps"],
+            "value": res["value"], "ms_per_step": res["ms_per_step"], "ms_per_step_regions": res["ms_per_step_regions"],
+            "avg_launch_ms": res["roofline"]["avg_launch_ms"], "ms_by_phase": res["roofline"]["ms_by_phase"],
+            "algorithmic_bytes_per_launch": res["roofline"]["algorithmic_bytes_per_launch"],
+            "achieved_GBps": res["roofline"]["achieved"], "frac": res["roofline"]["frac"],
+            "host_us_per_call": res["host_us_per_call"], "hbm_layout": res["config"]["hbm_layout"]}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=None,
+                    help="1..5; default: 2 as the headline plus configurations 3, 4, 5 and the packed layout on the side")
+    ap.add_argument("--mode", choices=["auto", "tile", "direct"], default="auto")
+    ap.add_argument("--inplace", action="store_true", help="update parameters in place instead of ping-pong")
+    ap.add_argument("--pool", type=int, default=2, help="number of pre-generated gradient sets cycled through")
+    ap.add_argument("--path", choices=["fused", "unfused", "mix", "mix_consensus", "accumulate", "buckets"], default="fused",
+                    help="fused: one dadam_gossip_step per iteration (the benchmark); unfused: dadam_gossip_step without "
+                         "accumulation followed by dadam_accumulate; mix: dadam_mix only; accumulate: dadam_accumulate only; "
+                         "buckets: the fused step issued tensor range by tensor range (--bucket-mb)")
+    ap.add_argument("--bucket-mb", type=float, default=25.0, help="target bucket size for --path buckets")
+    ap.add_argument("--bucket-streams", type=int, default=1,
+                    help="--path buckets: deal the buckets of a step over that many streams (1: the step's own stream)")
+    ap.add_argument("--standin-backward", type=int, default=0,
+                    help="--path buckets: before each bucket's update run an N x N bfloat16 matmul on the step's stream as a "
+                         "stand-in for that bucket's backward pass; with --bucket-streams >= 2 the updates go to side "
+                         "streams and overlap the next stand-in (the value then is not the benchmark's metric)")
+    ap.add_argument("--standin-only", action="store_true", help="with --standin-backward: skip the updates (the stand-in alone)")
+    ap.add_argument("--layout", choices=["spread", "compact", "whole", "packed"], default="spread",
+                    help="spread: one arena over most of the free HBM, buffers dealt alternately over two regions either "
+                         "side of the boundary between the first two thirds of the memory (see paper_2410_11998_amd/arena.py); "
+                         "compact: the same two regions in an arena only as large as they need, pushed into place by a "
+                         "throw-away allocation that is released again; whole: the big arena, buffers at equal distances "
+                         "over all of it; packed: one ordinary allocation per buffer")
+    ap.add_argument("--prealloc-gib", type=int, default=0,
+                    help="allocate that much device memory first and keep it (stands for a job's weights and activations)")
+    ap.add_argument("--scale-div", type=int, default=1, help="divide tensor dimensions (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-side-configs", action="store_true", help="headline only: skip per_config and packed_frac")
+    ap.add_argument("--graph", action="store_true",
+                    help="record a whole number of accumulation loops in a HIP graph once and time its replays "
+                         "(launch gaps of --path buckets); per-launch times then are replay averages")
+    ap.add_argument("--repeats", type=int, default=30,
+                    help="after the timed region, time that many minus one further regions of the same length and "
+                         "report their median, minimum and maximum next to the first, which stays the reported value")
+    ap.add_argument("--cpu-sample", type=int, default=None, help="coordinates per row given to the CPU oracle")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device copies of a known size (1 GiB read + 1 GiB written each), so that "
+                         "profiler byte counters can be scaled by what they read for a known transfer")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; all replicas of the simulated run (or one node's share) live in "
+              "one HBM and there is no multi-GPU path to time. Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(torch.device("cuda:0"))
+
+    side_configs = args.config is None and not args.no_side_configs and args.path == "fused" and not args.graph
+    if args.config is None:
+        args.config = 2
+    out, sample = measure_and_release(args, want_cpu_sample=not args.no_cpu_baseline)
+
+    if side_configs:
+        # the other configurations of the benchmark, each over its own step count, and configuration 2 again
+        # with ordinary allocations; shorter runs of regions (the headline's regions carry the statistics)
+        import copy
+        per = {}
+        for cfg in (3, 4, 5):
+            a = copy.copy(args)
+            a.config, a.steps, a.repeats, a.copy_calibration = cfg, None, min(args.repeats, 5), False
+            res, _ = measure_and_release(a, want_cpu_sample=False)
+            per[f"cfg{cfg}"] = brief(res)
+        out["per_config"] = per
+        a = copy.copy(args)
+        a.layout, a.repeats, a.copy_calibration = "packed", min(args.repeats, 5), False
+        res, _ = measure_and_release(a, want_cpu_sample=False)
+        out["packed_frac"] = res["roofline"]["frac"]
+        out["packed"] = brief(res)
+
+    if sample is not None:
+        wl, ns, x0_sample, g_samples, csrs = sample
+        R = wl.n_rows
         iters = min(wl.steps, max(wl.s + 1, int(1.2e9 // (R * ns))))
         v, dt = cpu_baseline(wl, x0_sample, g_samples, csrs, iters)
         model, logical = host_cpu()

@@ -52,7 +52,7 @@
 extern "C" {
 #endif
 
-#define DADAM_ABI_VERSION 1u
+#define DADAM_ABI_VERSION 2u
 #define DADAM_MAX_ROWS 64u
 #define DADAM_MAX_SLOTS 16u
 #define DADAM_DEVICE_NONE (-1) /* host-only handle: validation and planning work, launches fail */
@@ -108,6 +108,12 @@ typedef struct {
                       taken as a misprint and the default, selected by a negative value or NaN, is
                       beta2.  Any value in [0, 1) selects it explicitly. */
   int32_t device;  /* HIP device ordinal, or DADAM_DEVICE_NONE */
+  uint32_t lds_limit_bytes; /* LDS one workgroup may use.  0: what the device reports (a host-only handle
+                               assumes 65536).  A non-zero value plans for that much instead (e.g. to keep
+                               room for other kernels' LDS); on a device handle it must not exceed what the
+                               device reports. */
+  uint32_t n_xcds;          /* accelerator complex dies (each with its own L2) that consecutive workgroup
+                               ids are dealt over.  0: what the device reports (host-only handle: 8). */
 } dadam_config;
 
 /* Arrays (host) of DEVICE pointers, caller-owned; the arrays themselves are copied.
@@ -132,6 +138,15 @@ typedef struct {
   uint64_t n_tiles_direct;  /* tiles per row in direct mode (work items = this * n_rows)        */
   uint32_t lds_bytes_tile;  /* LDS per workgroup in tile mode                                   */
   uint32_t tile_mode_possible; /* 1 if the source tile fits in LDS                              */
+  uint32_t lds_limit_bytes; /* LDS per workgroup the plan was made for                          */
+  uint32_t n_xcds;          /* dies the tile order is laid out for                              */
+  uint32_t mix_tile_elems;  /* elements of one tile of the mixing-only launch (tile mode)       */
+  uint32_t lds_bytes_mix;   /* LDS per workgroup of the mixing-only launch                      */
+  uint64_t n_tiles_mix;     /* work items of a mixing-only launch in tile mode                  */
+  uint32_t tile_waves, tile_vectors; /* shape of the fused step's tile kernel: wavefronts per workgroup,
+                                        16-byte vectors per lane and row                          */
+  uint32_t mix_waves, mix_vectors;   /* the same for the mixing-only launch                       */
+  uint32_t streaming;       /* 1 if accesses carry the non-temporal hint (large working sets)   */
 } dadam_plan_info;
 
 /* Create a handle.  Validates the configuration, builds the segment table from the tensor list
@@ -230,23 +245,36 @@ int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_byte
  * the same bytes sustains 0.62-0.66 of peak bandwidth when the buffers it streams together all lie
  * inside one third (96 GiB) of the device's physical memory - which is where a fresh process's
  * allocations land - and 0.78-0.79 when every group of buffers that is streamed together lies half
- * in one third and half in another.  The caller makes ONE allocation of arena_bytes bytes that covers
- * nearly the whole device (within 16 GiB of device_total_bytes, so that offsets inside it are physical
- * positions up to what was allocated before it); this helper then deals the buffers alternately over
- * two regions, one ending 2 GiB below and one starting 2 GiB above the boundary between the first two
- * thirds: buffers 0, 2, 4, ... below, 1, 3, 5, ... above, spread over each region (regions at least
- * 64 GiB wide, wider when the buffers need it) and staggered inside their gaps by a fixed pseudo-random
- * number of 2 MiB steps, so that the bases do not form an arithmetic progression (for some distances
- * between bases that costs 3-4 %).  Any run of consecutive buffers -
- * all sources, all outputs, one kind of state - is then split evenly.  When the arena does not cover
- * the device or the buffers do not fit two thirds of it, they are placed at equal distances over the
- * whole arena instead.  nbytes[n] in, offsets[n] out (host), every offset a multiple of 2 MiB.
- * regions_out (may be null) receives lo0, hi0, lo1, hi1 of the two regions, or 0, arena_bytes, 0, 0 for
- * the fall-back.  The caller hands `arena + offsets[k]` to dadam_bind and may use the space between
- * the buffers for anything else.
+ * in one third and half in another.  The library cannot see physical addresses; what it can use is
+ * that a process's allocations fill the device memory from the bottom, so that a byte at offset o of
+ * an allocation made when arena_base_bytes of device memory were already in use (device total minus
+ * free, read just before allocating) sits near physical position arena_base_bytes + o.  The caller
+ * makes ONE allocation of arena_bytes that reaches across the boundary between the first two thirds
+ * (e.g. nearly all free memory); this helper deals the buffers alternately over two regions, one ending
+ * 2 GiB below and one starting 2 GiB above that boundary: buffers 0, 2, 4, ... below, 1, 3, 5, ...
+ * above, spread over each region (64 GiB wide where the arena allows, never narrower than the buffers
+ * of that side need) and staggered inside their gaps by a fixed pseudo-random number of 2 MiB steps, so
+ * that the bases do not form an arithmetic progression (for some distances between bases that costs
+ * 3-4 %).  Any run of consecutive buffers - all sources, all outputs, one kind of state - is then split
+ * evenly.  nbytes[n] in, offsets[n] out (host), offsets relative to the arena, every one a multiple of
+ * 2 MiB.  regions_out (may be null) receives lo0, hi0, lo1, hi1 of the two regions as arena offsets, or
+ * 0, arena_bytes, 0, 0 for the fall-back.  *advice_out (may be null) says what was done:
+ *   DADAM_PLACE_TWO_REGIONS     the rule above was applied; it is as good as arena_base_bytes is;
+ *   DADAM_PLACE_ARENA_ELSEWHERE the arena does not reach across the boundary with room for each side's
+ *                               buffers: offsets in it say nothing useful about physical positions, and
+ *                               the buffers are placed at equal distances over the whole arena instead
+ *                               (expect the lower level if the arena lies inside one third);
+ *   DADAM_PLACE_TOO_LARGE       half of the buffers do not fit below the boundary or the other half
+ *                               between it and the next one: equal distances over the whole arena.
+ * The caller hands `arena + offsets[k]` to dadam_bind and may use the space between the buffers for
+ * anything else.
  * Errors: DADAM_EINVAL if a pointer is null, n == 0, or the buffers do not fit the arena at all. */
-int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes,
-                        uint64_t device_total_bytes, uint64_t* offsets, uint64_t* regions_out);
+#define DADAM_PLACE_TWO_REGIONS 1u
+#define DADAM_PLACE_ARENA_ELSEWHERE 2u
+#define DADAM_PLACE_TOO_LARGE 4u
+int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t arena_base_bytes,
+                        uint64_t device_total_bytes, uint64_t* offsets, uint64_t* regions_out,
+                        uint32_t* advice_out);
 
 /* Text of the last error recorded on this handle ("" if none).  With h == NULL: the text of the
  * last dadam_init failure of the calling thread.  The pointer stays valid until the next call on

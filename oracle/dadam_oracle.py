@@ -46,13 +46,15 @@ Readings of the paper taken here (each is also listed in the design document):
 
 Pins: tests/test_oracle_pins.py checks every function below against closed forms,
 library routines (torch.optim.Adam), brute force with a dense mixing matrix, and
-the invariants the paper states.  No function here is "parity unpinned".
+the invariants the paper states; the two error scales at the end (not part of the
+method, but every relative tolerance of the parity tests is relative to them) are
+pinned to hand values on the hand-worked trace and to what a float32 evaluation of
+an iteration actually commits.  No function here is "parity unpinned".
 """
 
 from __future__ import annotations
 
-import math
-from dataclasses import dataclass, field
+from dataclasses import dataclass
 from typing import List, Optional, Sequence
 
 import numpy as np
@@ -329,3 +331,25 @@ def magnitude_scale(state: State, grads: Sequence[np.ndarray], csr: Csr, t: int,
             scale = scale + hp.lr * np.abs(np.asarray(weight_decay, dtype=np.float64) * state.x_src[i])
         out.append(scale)
     return out
+
+
+def state_magnitude_scales(state: State, grads: Sequence[np.ndarray], t: int, hp: Hyper):
+    """Per row, the sums of the magnitudes of the terms that make up b, m_hat and v_hat after
+    iteration t (state = what the iteration starts from):
+        b:      |b| + |g|/s
+        m_hat:  beta1 |m_hat| + (1-beta1) (|b| + |g|/s)      on a fold iteration, |m_hat| otherwise
+        v_hat:  betav |v_hat| + (1-betav) (|b| + |g|/s)^2    on a fold iteration, |v_hat| otherwise
+    Returns (scale_b, scale_m, scale_v), each a list with one array per row."""
+    sb, sm, sv = [], [], []
+    fold = (t % hp.s == 0)
+    for i in range(len(grads)):
+        g = np.abs(np.asarray(grads[i], dtype=np.float64))
+        bmag = np.abs(state.b[i]) + g / hp.s
+        sb.append(bmag)
+        if fold:
+            sm.append(hp.beta1 * np.abs(state.m_hat[i]) + (1 - hp.beta1) * bmag)
+            sv.append(hp.bv() * np.abs(state.v_hat[i]) + (1 - hp.bv()) * bmag * bmag)
+        else:
+            sm.append(np.abs(state.m_hat[i]))
+            sv.append(np.abs(state.v_hat[i]))
+    return sb, sm, sv

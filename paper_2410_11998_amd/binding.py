@@ -18,9 +18,9 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("DADAM_LIB") or os.path.join(_HERE, "libdadam.so")   # DADAM_LIB: a differently tuned build
+LIB_PATH = os.path.join(_HERE, "libdadam.so")
 
-DADAM_ABI_VERSION = 1
+DADAM_ABI_VERSION = 2
 DADAM_MAX_ROWS = 64
 DADAM_MAX_SLOTS = 16
 DADAM_DEVICE_NONE = -1
@@ -28,6 +28,7 @@ DADAM_F32, DADAM_BF16 = 0, 1
 DADAM_OK, DADAM_EINVAL, DADAM_EALIGN, DADAM_ETOPO, DADAM_EALIAS, DADAM_ESTATE, DADAM_EHIP = 0, -1, -2, -3, -4, -5, -6
 DADAM_FUSE_ACCUM, DADAM_FORCE_DIRECT, DADAM_FORCE_TILE = 1, 2, 4
 DADAM_WARN_NOT_COLUMN_STOCHASTIC = 1
+DADAM_PLACE_TWO_REGIONS, DADAM_PLACE_ARENA_ELSEWHERE, DADAM_PLACE_TOO_LARGE = 1, 2, 4
 
 EXPORTS = [
     "dadam_init", "dadam_set_topology", "dadam_bind", "dadam_swap_x", "dadam_gossip_step",
@@ -48,6 +49,7 @@ class dadam_config(C.Structure):
         ("param_dtype", C.c_uint32), ("grad_dtype", C.c_uint32),
         ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
         ("accum_s", C.c_uint32), ("beta_vhat", C.c_float), ("device", C.c_int32),
+        ("lds_limit_bytes", C.c_uint32), ("n_xcds", C.c_uint32),
     ]
 
 
@@ -59,7 +61,10 @@ class dadam_buffers(C.Structure):
 class dadam_plan_info(C.Structure):
     _fields_ = [("n_segments", C.c_uint32), ("tile_elems", C.c_uint32), ("direct_elems", C.c_uint32),
                 ("n_tiles_tile", C.c_uint64), ("n_tiles_direct", C.c_uint64), ("lds_bytes_tile", C.c_uint32),
-                ("tile_mode_possible", C.c_uint32)]
+                ("tile_mode_possible", C.c_uint32), ("lds_limit_bytes", C.c_uint32), ("n_xcds", C.c_uint32),
+                ("mix_tile_elems", C.c_uint32), ("lds_bytes_mix", C.c_uint32), ("n_tiles_mix", C.c_uint64),
+                ("tile_waves", C.c_uint32), ("tile_vectors", C.c_uint32), ("mix_waves", C.c_uint32),
+                ("mix_vectors", C.c_uint32), ("streaming", C.c_uint32)]
 
 
 def _load() -> C.CDLL:
@@ -82,8 +87,8 @@ def _load() -> C.CDLL:
     lib.dadam_slot_uses_tile_mode.argtypes = [H, C.c_uint32]
     lib.dadam_pack_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
     lib.dadam_spread_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.POINTER(C.c_uint64)]
-    lib.dadam_place_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint64),
-                                        C.POINTER(C.c_uint64)]
+    lib.dadam_place_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64,
+                                        C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
     lib.dadam_last_error.argtypes = [H]
     lib.dadam_last_error.restype = C.c_char_p
     lib.dadam_destroy.argtypes = [H]
@@ -163,23 +168,26 @@ def dadam_spread_offsets(nbytes: Sequence[int], arena_bytes: int):
     return [int(x) for x in o]
 
 
-def dadam_place_offsets(nbytes: Sequence[int], arena_bytes: int, device_total_bytes: int):
-    """Returns (offsets, regions) with regions = [(lo0, hi0), (lo1, hi1)], or [(0, arena_bytes)] for the fall-back."""
+def dadam_place_offsets(nbytes: Sequence[int], arena_bytes: int, arena_base_bytes: int, device_total_bytes: int):
+    """Returns (offsets, regions, advice) with regions = [(lo0, hi0), (lo1, hi1)], or [(0, arena_bytes)] for the
+    fall-back, and advice the DADAM_PLACE_* flag the library reports."""
     n = len(nbytes)
     a = (C.c_uint64 * n)(*[int(x) for x in nbytes])
     o = (C.c_uint64 * n)()
     r = (C.c_uint64 * 4)()
-    rc = lib.dadam_place_offsets(a, n, int(arena_bytes), int(device_total_bytes), o, r)
+    adv = C.c_uint32(0)
+    rc = lib.dadam_place_offsets(a, n, int(arena_bytes), int(arena_base_bytes), int(device_total_bytes), o, r, C.byref(adv))
     if rc < 0:
         raise DadamError(rc, f"dadam_place_offsets: {n} buffers of {sum(int(x) for x in nbytes)} bytes do not fit in {arena_bytes}")
     regions = [(int(r[0]), int(r[1]))] + ([(int(r[2]), int(r[3]))] if r[3] else [])
-    return [int(x) for x in o], regions
+    return [int(x) for x in o], regions, int(adv.value)
 
 
 def dadam_init(n_rows: int, n_cols: int, d: int, offsets: Sequence[int], numels: Sequence[int],
                param_dtype: int = DADAM_F32, grad_dtype: int = DADAM_F32, lr: float = 1e-3, beta1: float = 0.9,
                beta2: float = 0.999, eps: float = 1e-8, accum_s: int = 1, beta_vhat: float = -1.0,
-               device: int = 0, abi_version: int = DADAM_ABI_VERSION, weight_decay=None, tensor_flags=None):
+               device: int = 0, abi_version: int = DADAM_ABI_VERSION, weight_decay=None, tensor_flags=None,
+               lds_limit_bytes: int = 0, n_xcds: int = 0):
     n = len(offsets)
     descs = (dadam_tensor_desc * max(n, 1))()
     for k in range(n):
@@ -188,7 +196,7 @@ def dadam_init(n_rows: int, n_cols: int, d: int, offsets: Sequence[int], numels:
         descs[k].weight_decay = float(weight_decay[k]) if weight_decay is not None else 0.0
         descs[k].flags = int(tensor_flags[k]) if tensor_flags is not None else 0
     cfg = dadam_config(abi_version, n_rows, n_cols, d, n, descs, param_dtype, grad_dtype, lr, beta1, beta2, eps,
-                       accum_s, beta_vhat, device)
+                       accum_s, beta_vhat, device, lds_limit_bytes, n_xcds)
     h = C.c_void_p()
     rc = lib.dadam_init(C.byref(cfg), C.byref(h))
     if rc < 0:
@@ -221,7 +229,15 @@ def dadam_swap_x(h) -> None:
 
 
 def _grad_ptrs(h, grads):
+    if isinstance(grads, C.Array):          # a table made by grad_table(): already marshalled and checked
+        return grads
     return _ptr_array(_ptrs_of(grads, h, _SHAPE_OF_HANDLE.get(h.value, (0, 0, 0))[2], "grads"))
+
+
+def grad_table(h, grads):
+    """The host array of device pointers that the step calls take, marshalled (and size-checked) once; callers
+    that reuse a gradient set pass this instead of the list of tensors.  The tensors must stay alive."""
+    return _grad_ptrs(h, grads)
 
 
 def dadam_gossip_step(h, slot: int, grads, t: int, flags: int = DADAM_FUSE_ACCUM, stream: int = 0) -> None:

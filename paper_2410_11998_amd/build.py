@@ -1,7 +1,15 @@
-"""Build libdadam.so (gfx950) in-tree with hipcc.  Cross-compiles without a GPU."""
+"""Build libdadam.so (gfx950) in-tree with hipcc.  Cross-compiles without a GPU.
+
+    python -m paper_2410_11998_amd.build [--incremental] [extra hipcc flags]
+
+Each source is compiled to an object under _build/ and the objects are linked into
+libdadam.so beside this file.  build() recompiles everything; --incremental skips sources whose
+object is newer than the source and every header.
+"""
 
 from __future__ import annotations
 
+import glob
 import os
 import shutil
 import subprocess
@@ -10,12 +18,13 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdadam.so")
 
 SOURCES = ["dadam_kernels.hip", "dadam_host.cpp"]
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-x", "hip",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -31,28 +40,30 @@ def hipcc() -> str:
     return exe
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
-    cmd = [hipcc()] + FLAGS + list(extra_flags) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
 
 
-PROBE = os.path.join(HERE, "stream_probe")
-
-
-def build_probe(verbose: bool = True) -> str:
-    """The stand-alone streaming-bandwidth probe (csrc/stream_probe.hip), an executable of its own."""
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
-           os.path.join(CSRC, "stream_probe.hip"), "-o", PROBE]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
-    return PROBE
+def build(verbose: bool = True, extra_flags=(), incremental: bool = False, lib: str = LIB) -> str:
+    os.makedirs(OBJ, exist_ok=True)
+    tag = "" if not extra_flags else "." + "".join(c if c.isalnum() else "_" for c in "".join(extra_flags))
+    headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    objs = []
+    for s in SOURCES:
+        src = os.path.join(CSRC, s)
+        obj = os.path.join(OBJ, s + tag + ".o")
+        objs.append(obj)
+        newest = max(os.path.getmtime(p) for p in [src, __file__] + headers)
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > newest:
+            continue
+        _run([hipcc()] + FLAGS + list(extra_flags) + ["-c", src, "-o", obj], verbose)
+    _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", lib], verbose)
+    return lib
 
 
 if __name__ == "__main__":
-    build(extra_flags=sys.argv[1:])
-    build_probe()
+    argv = sys.argv[1:]
+    inc = "--incremental" in argv
+    build(extra_flags=[a for a in argv if a != "--incremental"], incremental=inc)

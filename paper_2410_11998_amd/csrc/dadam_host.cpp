@@ -12,6 +12,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "dadam_internal.h"
@@ -74,7 +75,19 @@ struct dadam_handle {
   float* m_hat[kMaxRows] = {};
   float* v_hat[kMaxRows] = {};
   float* acc[kMaxRows] = {};
-  int32_t inplace_col[kMaxRows];  // source that x_dst[i] coincides with, or -1
+  std::vector<int32_t> inplace_cols[kMaxRows];  // every source buffer that x_dst[i] coincides with
+  uint32_t lds_limit = 65536;  // LDS one workgroup may use
+  uint32_t n_xcds = 8;         // dies consecutive workgroup ids are dealt over
+  // Gradient tables that passed check_grads against the current outputs: a caller that cycles a few
+  // gradient sets (or issues a step bucket by bucket) is checked once per set, not once per call.
+  struct CheckedGrads { uint64_t gen; std::vector<const void*> ptrs; };
+  std::vector<CheckedGrads> checked;
+  size_t checked_next = 0;
+  // Names the set of output buffers: dadam_bind moves on to the next even number, dadam_swap_x flips
+  // the lowest bit (two exchanges give back the same tables).
+  uint64_t outputs_gen = 0;
+  std::vector<std::pair<uintptr_t, uintptr_t>> outputs_sorted[2];  // [lo, hi) of x_dst, m_hat, v_hat, b, by lo
+  uint64_t outputs_sorted_gen[2] = {~0ull, ~0ull};
   float lr = 0.f;
   double betav = 0.0;
   mutable std::string err;
@@ -104,11 +117,17 @@ struct Interval {
 
 bool overlaps(const Interval& a, const Interval& b) { return a.lo < b.hi && b.lo < a.hi; }
 
+// Measurement builds (-DDADAM_TUNING, never what build() makes) let the environment override kernel
+// shapes when a handle is created; the shipped library has no such switches.
+#ifdef DADAM_TUNING
 int env_int(const char* name, int fallback) {
   const char* v = getenv(name);
   if (!v || !*v) return fallback;
   return atoi(v);
 }
+#else
+constexpr int env_int(const char*, int fallback) { return fallback; }
+#endif
 
 // Build maximal runs of contiguous tensors and number the tiles of both tile grids.
 int plan(dadam_handle* h) {
@@ -160,35 +179,56 @@ void work_range(const dadam_handle* h, Grid grid, uint32_t s0, uint32_t s1, uint
   *w1 = b.work0[grid] + (uint32_t)((hi - 1) / T - b.first_tile[grid]) + 1;
 }
 
-int check_launchable(const dadam_handle* h) {
-  if (h->cfg.device == DADAM_DEVICE_NONE)
-    return fail(h, DADAM_ESTATE, "host-only handle (device = DADAM_DEVICE_NONE) cannot launch");
+int check_bound(const dadam_handle* h) {
   if (!h->bound) return fail(h, DADAM_ESTATE, "no buffers bound: call dadam_bind first");
   return DADAM_OK;
 }
 
-int check_grads(const dadam_handle* h, const void* const* grads) {
+// The last check before a launch, after every argument has been validated (so that a host-only
+// handle reports what is wrong with a call exactly as a device handle would).
+int check_device(const dadam_handle* h) {
+  if (h->cfg.device == DADAM_DEVICE_NONE)
+    return fail(h, DADAM_ESTATE, "host-only handle (device = DADAM_DEVICE_NONE) cannot launch");
+  return DADAM_OK;
+}
+
+// Gradients are read-only; what they must not overlap is anything the call writes.  The outputs are
+// pairwise disjoint (dadam_bind checked that), so they are kept sorted and each gradient is located
+// with a binary search; a table that passed is remembered until the outputs change.
+int check_grads(dadam_handle* h, const void* const* grads) {
   if (!grads) return fail(h, DADAM_EINVAL, "grads is null");
   const uint32_t R = h->cfg.n_rows;
+  for (const auto& ok : h->checked)
+    if (ok.gen == h->outputs_gen && std::equal(ok.ptrs.begin(), ok.ptrs.end(), grads)) return DADAM_OK;
   const size_t gb = h->cfg.d * dtype_bytes(h->cfg.grad_dtype);
   const size_t xb = h->cfg.d * dtype_bytes(h->cfg.param_dtype);
   const size_t sb = h->cfg.d * 4;
+  const int par = (int)(h->outputs_gen & 1u);
+  auto& o = h->outputs_sorted[par];
+  if (h->outputs_sorted_gen[par] != h->outputs_gen) {
+    o.clear();
+    for (uint32_t j = 0; j < R; ++j) {
+      o.push_back({(uintptr_t)h->x_dst[j], (uintptr_t)h->x_dst[j] + xb});
+      o.push_back({(uintptr_t)h->m_hat[j], (uintptr_t)h->m_hat[j] + sb});
+      o.push_back({(uintptr_t)h->v_hat[j], (uintptr_t)h->v_hat[j] + sb});
+      if (h->acc[j]) o.push_back({(uintptr_t)h->acc[j], (uintptr_t)h->acc[j] + sb});
+    }
+    std::sort(o.begin(), o.end());
+    h->outputs_sorted_gen[par] = h->outputs_gen;
+  }
   for (uint32_t i = 0; i < R; ++i) {
     if (!grads[i]) return fail(h, DADAM_EINVAL, "grads[%u] is null", i);
     if (!aligned16(grads[i])) return fail(h, DADAM_EALIGN, "grads[%u] is not 16-byte aligned", i);
+    const uintptr_t lo = (uintptr_t)grads[i], hi = lo + gb;
+    // first output that ends beyond lo; it overlaps iff it starts below hi
+    auto it = std::upper_bound(o.begin(), o.end(), lo,
+                               [](uintptr_t v, const std::pair<uintptr_t, uintptr_t>& iv) { return v < iv.second; });
+    if (it != o.end() && it->first < hi)
+      return fail(h, DADAM_EALIAS, "grads[%u] overlaps an output buffer (x_dst, m_hat, v_hat or acc)", i);
   }
-  for (uint32_t i = 0; i < R; ++i) {
-    Interval g{(uintptr_t)grads[i], (uintptr_t)grads[i] + gb, 3, (int)i};
-    for (uint32_t j = 0; j < R; ++j) {
-      Interval outs[4] = {{(uintptr_t)h->x_dst[j], (uintptr_t)h->x_dst[j] + xb, 1, (int)j},
-                          {(uintptr_t)h->m_hat[j], (uintptr_t)h->m_hat[j] + sb, 2, (int)j},
-                          {(uintptr_t)h->v_hat[j], (uintptr_t)h->v_hat[j] + sb, 2, (int)j},
-                          {(uintptr_t)h->acc[j], (uintptr_t)h->acc[j] + (h->acc[j] ? sb : 0), 2, (int)j}};
-      for (const Interval& o : outs)
-        if (o.lo && overlaps(g, o))
-          return fail(h, DADAM_EALIAS, "grads[%u] overlaps an output buffer of row %u", i, j);
-    }
-  }
+  dadam_handle::CheckedGrads ok{h->outputs_gen, std::vector<const void*>(grads, grads + R)};
+  if (h->checked.size() < 8) h->checked.push_back(std::move(ok));
+  else { h->checked[h->checked_next] = std::move(ok); h->checked_next = (h->checked_next + 1) % 8; }
   return DADAM_OK;
 }
 
@@ -212,6 +252,7 @@ void fill_args(const dadam_handle* h, const Slot* slot, const void* const* grads
   a->n_seg = (uint32_t)h->segs.size();
   a->n_rows = R;
   a->n_cols = C;
+  a->n_xcd = h->n_xcds;
 }
 
 // Scalars of iteration t (Algorithm 3 lines 4 and 8), computed in double and rounded once.
@@ -245,12 +286,14 @@ int choose_mode(const dadam_handle* h, const Slot& slot, uint32_t flags, bool* t
   if ((flags & DADAM_FORCE_DIRECT) && (flags & DADAM_FORCE_TILE))
     return fail(h, DADAM_EINVAL, "DADAM_FORCE_DIRECT and DADAM_FORCE_TILE are exclusive");
   bool direct_legal = true;
-  for (uint32_t i = 0; i < h->cfg.n_rows; ++i) {
-    int32_t c = h->inplace_col[i];
-    if (c < 0) continue;
-    int32_t sr = slot.sole_reader[c];
-    if (!(sr == -1 || sr == (int32_t)i)) direct_legal = false;
-  }
+  // A row updated in place overwrites every source buffer that shares its memory (two source
+  // entries may name one buffer); the direct kernel may do that only if nobody but the row itself
+  // reads any of them.
+  for (uint32_t i = 0; i < h->cfg.n_rows; ++i)
+    for (int32_t c : h->inplace_cols[i]) {
+      int32_t sr = slot.sole_reader[c];
+      if (!(sr == -1 || sr == (int32_t)i)) direct_legal = false;
+    }
   if (flags & DADAM_FORCE_TILE) {
     if (!h->tile_possible) return fail(h, DADAM_EINVAL, "tile mode needs the source tile to fit in LDS");
     *tile_mode = true;
@@ -293,7 +336,7 @@ int resolve_range(const dadam_handle* h, uint32_t tb, uint32_t te, bool whole, u
 int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint64_t t, uint32_t flags,
               bool whole, uint32_t tb, uint32_t te, bool mix_only, void* stream, double* consensus_out = nullptr) {
   if (!h) return DADAM_EINVAL;
-  int rc = check_launchable(h);
+  int rc = check_bound(h);
   if (rc) return rc;
   if (slot_id >= DADAM_MAX_SLOTS || !h->slots[slot_id].set)
     return fail(h, DADAM_ESTATE, "topology slot %u is not set", slot_id);
@@ -322,6 +365,8 @@ int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint6
   uint32_t s0 = 0, s1 = 0;
   bool empty = false;
   rc = resolve_range(h, tb, te, whole, &lo, &hi, &s0, &s1, &empty);
+  if (rc) return rc;
+  rc = check_device(h);
   if (rc) return rc;
   DeviceGuard guard(h->cfg.device);
   if (guard.err != hipSuccess) return fail(h, DADAM_EHIP, "hipSetDevice: %s", hipGetErrorString(guard.err));
@@ -414,7 +459,28 @@ int dadam_init(const dadam_config* cfg, dadam_handle** out) {
   h->cfg.tensors = nullptr;
   h->lr = cfg->lr;
   h->betav = betav;
-  for (int i = 0; i < kMaxRows; ++i) h->inplace_col[i] = -1;
+
+  // What the chip offers: LDS one workgroup may use and the number of dies (XCDs), asked of the
+  // device; a host-only handle plans for 64 KB and 8 dies unless the configuration says otherwise.
+  if (cfg->device != DADAM_DEVICE_NONE) {
+    int lds = 0, xcc = 0;
+    hipError_t e = hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, cfg->device);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&xcc, hipDeviceAttributeNumberOfXccs, cfg->device);
+    if (e != hipSuccess || lds <= 0) {
+      delete h;
+      return fail(nullptr, DADAM_EHIP, "cannot read the device's LDS size / die count: %s", hipGetErrorString(e));
+    }
+    h->lds_limit = (uint32_t)lds;
+    h->n_xcds = xcc > 0 ? (uint32_t)xcc : 1u;
+    if (cfg->lds_limit_bytes > h->lds_limit) {
+      delete h;
+      return fail(nullptr, DADAM_EINVAL, "lds_limit_bytes %u exceeds the device's %u", cfg->lds_limit_bytes, h->lds_limit);
+    }
+  }
+  if (cfg->lds_limit_bytes) h->lds_limit = cfg->lds_limit_bytes;
+  if (cfg->n_xcds) h->n_xcds = cfg->n_xcds;
+  h->n_xcds = (uint32_t)env_int("DADAM_XCDS", (int)h->n_xcds);
+  if (h->n_xcds > 64) { delete h; return fail(nullptr, DADAM_EINVAL, "n_xcds out of range"); }
 
   // tile geometry: 16 bytes per lane and vector, `ut` vectors per lane, all source buffers' slices
   // of one tile resident in LDS.  Measured on MI355X: one vector per lane (many small workgroups)
@@ -439,19 +505,21 @@ int dadam_init(const dadam_config* cfg, dadam_handle** out) {
   h->tile_elems = (uint32_t)(kWave * h->vec * shape.ut);
   h->direct_elems = (uint32_t)(kDirectThreads * h->vec * direct_unroll());
   h->lds_bytes = cfg->n_cols * (uint32_t)shape.ut * kWave * 16u;
-  h->tile_possible = h->lds_bytes <= 65536u;
+  h->tile_possible = h->lds_bytes <= h->lds_limit;
   // The mixing-only launch moves few bytes per row, so it wants more of them in flight per
-  // wavefront: two vectors per lane and four wavefronts when that tile still fits (measured: up to
-  // a quarter faster than the fused step's shape when the buffers sit badly in memory, 3 % when
-  // they sit well).
+  // wavefront: two vectors per lane and four wavefronts, as long as that tile stays small enough
+  // (32 KB) for five workgroups to share a CU's LDS.  Measured: 16 sources (32 KB) +3 % over the
+  // step's shape; 64 sources (128 KB, one workgroup per CU) 0.68-0.75 of peak against 0.76 with the
+  // step's one-vector tile, so large source counts keep that.
   h->mix_shape = shape;
-  if (cfg->n_cols * 2u * kWave * 16u <= 65536u && env_int("DADAM_TILE_UT", 0) == 0 && env_int("DADAM_TILE_WAVES", 0) == 0) {
+  if (cfg->n_cols * 2u * kWave * 16u <= 32768u && h->lds_limit >= 32768u && env_int("DADAM_TILE_UT", 0) == 0 &&
+      env_int("DADAM_TILE_WAVES", 0) == 0) {
     h->mix_shape.ut = 2;
     h->mix_shape.waves = 4;
   }
   h->mix_shape.ut = env_int("DADAM_MIX_UT", h->mix_shape.ut);
   h->mix_shape.waves = env_int("DADAM_MIX_WAVES", h->mix_shape.waves);
-  if (!tile_shape_supported(h->mix_shape) || cfg->n_cols * (uint32_t)h->mix_shape.ut * kWave * 16u > 65536u)
+  if (!tile_shape_supported(h->mix_shape) || cfg->n_cols * (uint32_t)h->mix_shape.ut * kWave * 16u > h->lds_limit)
     h->mix_shape = shape;
   h->mix_tile_elems = (uint32_t)(kWave * h->vec * h->mix_shape.ut);
   h->mix_lds_bytes = cfg->n_cols * (uint32_t)h->mix_shape.ut * kWave * 16u;
@@ -567,8 +635,7 @@ int dadam_bind(dadam_handle* h, const dadam_buffers* b) {
       iv.push_back({(uintptr_t)ps[q], (uintptr_t)ps[q] + (q == 0 ? xb : sb), q == 0 ? 1 : 2, (int)i});
     }
   }
-  int32_t inplace[kMaxRows];
-  for (int i = 0; i < kMaxRows; ++i) inplace[i] = -1;
+  std::vector<int32_t> inplace[kMaxRows];
   for (size_t p = 0; p < iv.size(); ++p)
     for (size_t q = p + 1; q < iv.size(); ++q) {
       const Interval& a = iv[p];
@@ -576,7 +643,7 @@ int dadam_bind(dadam_handle* h, const dadam_buffers* b) {
       if (!overlaps(a, c)) continue;
       if (a.kind == 0 && c.kind == 0) continue;  // two read-only sources may coincide
       if (a.kind == 0 && c.kind == 1 && a.lo == c.lo) {  // update in place
-        if (inplace[c.index] < 0) inplace[c.index] = a.index;
+        inplace[c.index].push_back(a.index);
         continue;
       }
       return fail(h, DADAM_EALIAS, "buffers overlap: kind %d index %d and kind %d index %d (0 x_src, 1 x_dst, 2 state)",
@@ -588,9 +655,10 @@ int dadam_bind(dadam_handle* h, const dadam_buffers* b) {
     h->m_hat[i] = b->m_hat[i];
     h->v_hat[i] = b->v_hat[i];
     h->acc[i] = b->acc ? b->acc[i] : nullptr;
-    h->inplace_col[i] = inplace[i];
+    h->inplace_cols[i] = inplace[i];
   }
   h->bound = true;
+  h->outputs_gen = (h->outputs_gen | 1u) + 1u;
   return DADAM_OK;
 }
 
@@ -599,11 +667,12 @@ int dadam_swap_x(dadam_handle* h) {
   if (!h->bound) return fail(h, DADAM_ESTATE, "no buffers bound");
   if (h->cfg.n_rows != h->cfg.n_cols) return fail(h, DADAM_ESTATE, "swap needs n_rows == n_cols");
   for (uint32_t i = 0; i < h->cfg.n_rows; ++i) {
-    if (h->inplace_col[i] >= 0) continue;  // in-place rows stay as they are
+    if (!h->inplace_cols[i].empty()) continue;  // in-place rows stay as they are
     void* s = const_cast<void*>(h->x_src[i]);
     h->x_src[i] = h->x_dst[i];
     h->x_dst[i] = s;
   }
+  h->outputs_gen ^= 1u;
   return DADAM_OK;
 }
 
@@ -632,7 +701,7 @@ int dadam_mix_consensus(dadam_handle* h, uint32_t slot, uint32_t flags, double* 
 
 int dadam_accumulate(dadam_handle* h, const void* const* grads, uint64_t t, void* hip_stream) {
   if (!h) return DADAM_EINVAL;
-  int rc = check_launchable(h);
+  int rc = check_bound(h);
   if (rc) return rc;
   if (t == 0) return fail(h, DADAM_EINVAL, "iterations are numbered from 1");
   rc = check_grads(h, grads);
@@ -640,6 +709,8 @@ int dadam_accumulate(dadam_handle* h, const void* const* grads, uint64_t t, void
   if (h->cfg.accum_s > 1)
     for (uint32_t i = 0; i < h->cfg.n_rows; ++i)
       if (!h->acc[i]) return fail(h, DADAM_ESTATE, "accumulator of row %u is not bound", i);
+  rc = check_device(h);
+  if (rc) return rc;
   if (h->segs.empty()) return DADAM_OK;
   StepArgs a;
   fill_args(h, nullptr, grads, &a);
@@ -674,6 +745,16 @@ int dadam_get_plan_info(const dadam_handle* h, dadam_plan_info* out) {
   out->n_tiles_direct = h->n_work_d;
   out->lds_bytes_tile = h->lds_bytes;
   out->tile_mode_possible = h->tile_possible ? 1u : 0u;
+  out->lds_limit_bytes = h->lds_limit;
+  out->n_xcds = h->n_xcds;
+  out->mix_tile_elems = h->mix_tile_elems;
+  out->lds_bytes_mix = h->mix_lds_bytes;
+  out->n_tiles_mix = h->n_work_m;
+  out->tile_waves = (uint32_t)h->shape.waves;
+  out->tile_vectors = (uint32_t)h->shape.ut;
+  out->mix_waves = (uint32_t)h->mix_shape.waves;
+  out->mix_vectors = (uint32_t)h->mix_shape.ut;
+  out->streaming = h->nontemporal ? 1u : 0u;
   return DADAM_OK;
 }
 
@@ -716,8 +797,8 @@ int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_byte
   return DADAM_OK;
 }
 
-int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t device_total_bytes,
-                        uint64_t* offsets, uint64_t* regions_out) {
+int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t arena_base_bytes,
+                        uint64_t device_total_bytes, uint64_t* offsets, uint64_t* regions_out, uint32_t* advice_out) {
   if (!nbytes || !offsets || n == 0) return DADAM_EINVAL;
   const uint64_t unit = 2ull << 20, gib = 1ull << 30;
   std::vector<uint64_t> side[2];
@@ -727,18 +808,38 @@ int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes
     side[k & 1].push_back(nbytes[k]);
     need[k & 1] += (nbytes[k] + unit - 1) / unit * unit;
   }
+  if (arena_bytes > (1ull << 50) || arena_base_bytes > (1ull << 50) || device_total_bytes > (1ull << 50)) return DADAM_EINVAL;
   const uint64_t third = (device_total_bytes + 3 * gib / 2) / (3 * gib) * gib;  // a third, to the nearest GiB
   const uint64_t margin = 2 * gib;
-  const uint64_t most = need[0] > need[1] ? need[0] : need[1];
-  uint64_t width = (most + most / 5 + unit - 1) / unit * unit;                   // 20 % of room
-  if (width < 64 * gib) width = 64 * gib;
-  const bool covers = arena_bytes + 16 * gib >= device_total_bytes && third > margin;
-  const uint64_t top = arena_bytes < 2 * third ? arena_bytes : 2 * third;
-  if (covers && n >= 2 && third - margin >= width && third + margin + width <= top) {
-    const uint64_t lo[2] = {third - margin - width, third + margin};
+  // Physical positions [p_lo, p_hi) the arena is taken to cover (its start rounded up to 2 MiB: offset 0
+  // of the answer is that point), and the two regions in the same terms: region 0 ends `margin` below
+  // the boundary between the first two thirds, region 1 starts `margin` above it and ends no later than
+  // `margin` below the next boundary.
+  const uint64_t p_lo = (arena_base_bytes + unit - 1) / unit * unit;
+  const uint64_t p_hi = arena_base_bytes + arena_bytes;
+  uint32_t advice = 0;
+  uint64_t lo[2] = {0, 0}, width[2] = {0, 0};
+  if (n < 2 || third <= 2 * margin) {
+    advice = 0;  // nothing to deal over two sides
+  } else if (need[0] > third - margin || need[1] > third - 2 * margin) {
+    advice = DADAM_PLACE_TOO_LARGE;
+  } else if (p_lo + need[0] > third - margin || third + margin + need[1] > p_hi) {
+    advice = DADAM_PLACE_ARENA_ELSEWHERE;
+  } else {
+    for (int r = 0; r < 2; ++r) {
+      uint64_t want = (need[r] + need[r] / 5 + unit - 1) / unit * unit;  // 20 % of room for the stagger
+      if (want < 64 * gib) want = 64 * gib;
+      const uint64_t room = r == 0 ? third - margin - p_lo : (p_hi < 2 * third - margin ? p_hi : 2 * third - margin) - (third + margin);
+      width[r] = (want < room ? want : room) / unit * unit;  // >= need[r] by the tests above
+      lo[r] = r == 0 ? third - margin - width[r] : third + margin;
+    }
+    advice = DADAM_PLACE_TWO_REGIONS;
+  }
+  if (advice_out) *advice_out = advice;
+  if (advice == DADAM_PLACE_TWO_REGIONS) {
     for (int r = 0; r < 2; ++r) {
       std::vector<uint64_t> off(side[r].size());
-      const int rc = dadam_spread_offsets(side[r].data(), (uint32_t)side[r].size(), width, off.data());
+      const int rc = dadam_spread_offsets(side[r].data(), (uint32_t)side[r].size(), width[r], off.data());
       if (rc != DADAM_OK) return rc;
       // Stagger the buffers inside their gaps by a fixed pseudo-random number of 2 MiB steps, so that their
       // bases do not form an arithmetic progression: for some distances (660 MiB, 884 MiB between 476 MiB
@@ -753,11 +854,12 @@ int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes
         z ^= z >> 31;
         if (slots > 1) off[j] += z % slots * unit;
       }
-      for (size_t j = 0; j < off.size(); ++j) offsets[2 * j + r] = lo[r] + off[j];
+      // from physical positions to offsets inside the arena
+      for (size_t j = 0; j < off.size(); ++j) offsets[2 * j + r] = lo[r] - p_lo + off[j];
     }
     if (regions_out) {
-      regions_out[0] = lo[0]; regions_out[1] = lo[0] + width;
-      regions_out[2] = lo[1]; regions_out[3] = lo[1] + width;
+      regions_out[0] = lo[0] - p_lo; regions_out[1] = lo[0] - p_lo + width[0];
+      regions_out[2] = lo[1] - p_lo; regions_out[3] = lo[1] - p_lo + width[1];
     }
     return DADAM_OK;
   }

@@ -66,6 +66,7 @@ struct StepArgs {
   uint32_t n_rows, n_cols;
   uint32_t grid;        // Grid: which tile numbering work items refer to
   uint32_t work_begin;  // first work item (in tiles) of this launch
+  uint32_t n_xcd;       // dies that consecutive workgroup ids are dealt over (tile order)
   uint64_t clip_lo, clip_hi;  // element range of this launch (whole layout or a tensor range)
   double* partials;           // kConsensusPartials doubles (device), used by kMixConsensus only
   Scalars s;

@@ -21,12 +21,15 @@
 // before the last readlane (see direct_body).
 #include <hip/hip_runtime.h>
 
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "dadam_internal.h"
 
 namespace dadam {
 namespace {
 
-constexpr uint32_t kXcds = 8;  // accelerator complex dies of an MI355X, each with its own L2
 // distance (in elements) between the two groups of four that an 8-element lane vector consists of
 constexpr int kHalfWave = 4 * kWave;             // tile kernel: the lanes of a wavefront work side by side
 constexpr int kHalfGroup = 4 * kDirectThreads;   // direct and accumulate kernels: the whole workgroup does
@@ -532,14 +535,15 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
   u4* lds = reinterpret_cast<u4*>(lds_bytes);
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  // Consecutive workgroup ids are dispatched to the 8 XCDs in turn.  Give each XCD one contiguous
-  // eighth of the tiles instead of every eighth tile, so that each XCD (and its L2) walks its own
-  // region of every array front to back: measured 1-3 % faster.  The map is a bijection of
-  // [0, 8 * chunk) onto itself; the last gridDim.x mod 8 workgroups keep their tile.
+  // Consecutive workgroup ids are dispatched to the device's X dies (XCDs, 8 on an MI355X) in turn.
+  // Give each die one contiguous X-th of the tiles instead of every X-th tile, so that each die (and
+  // its L2) walks its own region of every array front to back: measured 1-3 % faster.  The map is a
+  // bijection of [0, X * chunk) onto itself; the last gridDim.x mod X workgroups keep their tile.
   uint32_t b = blockIdx.x;
   {
-    const uint32_t chunk = gridDim.x / kXcds;
-    if (b < chunk * kXcds) b = (b % kXcds) * chunk + b / kXcds;
+    const uint32_t X = a.n_xcd;
+    const uint32_t chunk = gridDim.x / X;
+    if (b < chunk * X) b = (b % X) * chunk + b / X;
   }
   uint64_t tile_index, lo, hi;
   float wd;
@@ -834,6 +838,14 @@ KernelFn tile_kernel_for_shape_nt(int phase, TileShape s) {
   if (s.waves == 4 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 4, 2, NT>(phase);
   if (s.waves == 8 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 8, 1, NT>(phase);
   if (s.waves == 8 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 8, 2, NT>(phase);
+#ifdef DADAM_TUNING  // further shapes for measurements, same-type pairs only to bound the build time
+  if constexpr (XT::bytes == GT::bytes) {
+    if (s.waves == 16 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 16, 1, NT>(phase);
+    if (s.waves == 16 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 16, 2, NT>(phase);
+    if (s.waves == 4 && s.ut == 4) return tile_kernel_for_phase<XT, GT, 4, 4, NT>(phase);
+    if (s.waves == 8 && s.ut == 4) return tile_kernel_for_phase<XT, GT, 8, 4, NT>(phase);
+  }
+#endif
   return nullptr;
 }
 template <typename XT, typename GT>
@@ -865,9 +877,29 @@ KernelFn acc_kernel_for_phase(int phase) {
   return nullptr;
 }
 
+// A kernel may use more than 64 KB of dynamic LDS only after its limit has been raised; that is done
+// once per (device, kernel), up to the largest size asked for so far.
+int raise_lds_limit(KernelFn fn, uint32_t lds) {
+  static std::mutex mu;
+  static std::map<std::pair<int, const void*>, uint32_t> raised;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  std::lock_guard<std::mutex> lock(mu);
+  uint32_t& have = raised[{dev, reinterpret_cast<const void*>(fn)}];
+  if (have >= lds) return (int)hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e == hipSuccess) have = lds;
+  return (int)e;
+}
+
 int launch(KernelFn fn, uint32_t grid, uint32_t block, uint32_t lds, const StepArgs& a, void* stream) {
   if (fn == nullptr) return (int)hipErrorInvalidDeviceFunction;
   if (grid == 0) return (int)hipSuccess;
+  if (lds > 65536u) {
+    const int e = raise_lds_limit(fn, lds);
+    if (e != (int)hipSuccess) return e;
+  }
   hipLaunchKernelGGL(fn, dim3(grid), dim3(block), lds, reinterpret_cast<hipStream_t>(stream), a);
   return (int)hipGetLastError();
 }
@@ -889,6 +921,9 @@ int launch_consensus_sum(const double* partials, double* out, void* stream) {
 int vec_elems(int xdt) { return xdt == DADAM_BF16 ? TBF16::vec : TF32::vec; }
 int direct_unroll() { return kUD; }
 bool tile_shape_supported(TileShape s) {
+#ifdef DADAM_TUNING
+  if ((s.waves == 16 && (s.ut == 1 || s.ut == 2)) || ((s.waves == 4 || s.waves == 8) && s.ut == 4)) return true;
+#endif
   return (s.waves == 4 || s.waves == 8) && (s.ut == 1 || s.ut == 2);
 }
 

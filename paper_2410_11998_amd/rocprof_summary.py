@@ -1,0 +1,205 @@
+"""Turn rocprofv3 output of bench.py runs into the short text summaries kept under profiles/.
+
+    python -m paper_2410_11998_amd.rocprof_summary fused --kt DIR --fetch DIR --write DIR --out profiles/NAME.txt
+                                                          [--traffic profiles/hbm_traffic.txt]
+    python -m paper_2410_11998_amd.rocprof_summary counters --run LABEL=DIR [--run LABEL=DIR ...] --out profiles/NAME.txt
+
+Every DIR is the -d directory of ONE rocprofv3 run whose program was `python3 bench.py ...`, with the
+program's output saved as DIR/bench.out (its JSON line is read from there):
+
+* --kt     rocprofv3 --kernel-trace --stats --output-format csv        (kernel durations)
+* --fetch  rocprofv3 --pmc FETCH_SIZE --output-format csv, bench.py --copy-calibration
+* --write  rocprofv3 --pmc WRITE_SIZE --output-format csv, bench.py --copy-calibration
+* --run    rocprofv3 --pmc <any counters> --output-format csv          (averaged per kernel)
+
+The byte counters are scaled by what they read for the plain 1 GiB device copies bench.py
+--copy-calibration runs last (the last four copy kernels of the run).  `fused` also rewrites the lines of
+--traffic that belong to the workload: "workload kernel phase bytes source", which bench.py quotes
+as roofline.traffic for exactly that kernel shape.
+
+This is bookkeeping around the profiler's CSV files; nothing of the method is computed here.
+"""
+
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import glob
+import json
+import os
+import re
+import sys
+
+PHASES = {0: "mix", 1: "updateonly", 2: "plain", 3: "loopstart", 4: "fold", 5: "alg1", 6: "mix_consensus"}
+
+
+def parse_kernel(name: str):
+    """(kernel shape as bench.py names it, phase name) of one of the library's kernels, else (None, None)."""
+    m = re.search(r"\b(k_tile|k_direct|k_acc)<(.*)>\(", name)
+    if not m:
+        return None, None
+    args = [a.strip().split("::")[-1] for a in m.group(2).split(",")]
+    kind = m.group(1)
+    try:
+        if kind == "k_tile":          # <param type, grad type, phase, waves, vectors, non-temporal>
+            return f"k_tile<{args[0]},{args[1]},{args[3]},{args[4]},{args[5]}>", PHASES[int(args[2])]
+        if kind == "k_direct":        # <param type, grad type, phase, non-temporal>
+            return f"k_direct<{args[0]},{args[1]},{args[3]}>", PHASES[int(args[2])]
+        return f"k_acc<{args[0]},{args[1]},{args[3]}>", PHASES[int(args[2])]     # <grad type, elements per vector, phase, nt>
+    except (IndexError, KeyError, ValueError):
+        return None, None
+
+
+def one_file(directory: str, pattern: str) -> str:
+    hits = glob.glob(os.path.join(directory, "**", pattern), recursive=True)
+    if not hits:
+        raise SystemExit(f"no {pattern} under {directory}")
+    return max(hits, key=os.path.getmtime)
+
+
+def bench_line(directory: str) -> dict:
+    with open(os.path.join(directory, "bench.out")) as f:
+        lines = [l for l in f if l.startswith("{")]
+    if not lines:
+        raise SystemExit(f"no JSON line in {directory}/bench.out")
+    return json.loads(lines[-1])
+
+
+def bench_command(directory: str) -> str:
+    """The bench.py command of a run, as rocprofv3 logged it."""
+    with open(os.path.join(directory, "bench.out")) as f:
+        for l in f:
+            m = re.search(r"'(python3? \S*bench\.py[^']*)'", l)
+            if m:
+                return re.sub(r"\S*/bench\.py", "bench.py", m.group(1))
+    return "python3 bench.py ..."
+
+
+def kernel_stats(directory: str):
+    rows = []
+    with open(one_file(directory, "*kernel_stats.csv")) as f:
+        for r in csv.DictReader(f):
+            shape, phase = parse_kernel(r["Name"])
+            if shape:
+                rows.append((shape, phase, int(r["Calls"]), float(r["AverageNs"]) / 1e6, float(r["MinNs"]) / 1e6, float(r["MaxNs"]) / 1e6))
+    return sorted(rows)
+
+
+def counter_values(directory: str):
+    """{(kernel shape or 'copy', phase): {counter: [values per dispatch]}}"""
+    out = collections.defaultdict(lambda: collections.defaultdict(list))
+    with open(one_file(directory, "*counter_collection.csv")) as f:
+        for r in csv.DictReader(f):
+            shape, phase = parse_kernel(r["Kernel_Name"])
+            if shape is None and "copyBuffer" in r["Kernel_Name"]:
+                shape, phase = "copy", ""
+            if shape:
+                out[(shape, phase)][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    return out
+
+
+def mean(v):
+    return sum(v) / len(v)
+
+
+def cmd_fused(a) -> int:
+    j = bench_line(a.kt)
+    wl = j["config"]["workload"]
+    lines = [f"rocprofv3 summary: {j['config']['path']} step, workload {wl}, one MI355X", "",
+             "Commands (run from /tmp with TMPDIR=/tmp; paths relative to the repository root; written by",
+             "python -m paper_2410_11998_amd.rocprof_summary fused from the profiler's CSV files):",
+             f"  rocprofv3 --kernel-trace --stats --output-format csv -d OUT/kt -- {bench_command(a.kt)}",
+             f"  rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT/fetch -- {bench_command(a.fetch)}",
+             f"  rocprofv3 --pmc WRITE_SIZE --output-format csv -d OUT/write -- {bench_command(a.write)}", "",
+             "bench.py line of the kernel-trace run (per_config / packed / cpu_baseline left out):",
+             "  " + json.dumps({k: v for k, v in j.items() if k not in ("per_config", "packed", "cpu_baseline")}), "",
+             "Kernel statistics (*_kernel_stats.csv), the library's kernels; shape = <param type, grad type, [waves, vectors",
+             "per lane,] non-temporal>:",
+             f"  {'kernel':34s} {'phase':13s} {'calls':>5s} {'avg ms':>9s} {'min ms':>9s} {'max ms':>9s}"]
+    for shape, phase, calls, avg, lo, hi in kernel_stats(a.kt):
+        lines.append(f"  {shape:34s} {phase:13s} {calls:5d} {avg:9.3f} {lo:9.3f} {hi:9.3f}")
+    fetch, write = counter_values(a.fetch), counter_values(a.write)
+    cal_f = mean(fetch[("copy", "")]["FETCH_SIZE"][-4:])
+    cal_w = mean(write[("copy", "")]["WRITE_SIZE"][-4:])
+    kf, kw = 1048576.0 / cal_f, 1048576.0 / cal_w
+    lines += ["", "HBM traffic per dispatch (KiB as the counters report them):",
+              f"  calibration: plain device copies of 1 GiB (1048576 KiB read, 1048576 KiB written; the last four copy kernels",
+              f"  of the run, averaged): FETCH_SIZE reads {cal_f:.0f}, WRITE_SIZE reads {cal_w:.0f}",
+              f"  => scale factors: FETCH_SIZE x {kf:.4f}, WRITE_SIZE x {kw:.4f}"]
+    traffic = []
+    R, d = j["config"]["n_rows"], j["config"]["d"]
+    for key in sorted(k for k in fetch if k[0] != "copy"):
+        fv, wv = fetch[key]["FETCH_SIZE"], write.get(key, {}).get("WRITE_SIZE", [0.0])
+        fb, wb = mean(fv) * kf * 1024, mean(wv) * kw * 1024
+        lines.append(f"  {key[0]:34s} {key[1]:13s} dispatches {len(fv):3d}  FETCH_SIZE avg {mean(fv):12.0f} -> {fb / 1e9:7.2f} GB   "
+                     f"WRITE_SIZE avg {mean(wv):12.0f} -> {wb / 1e9:7.2f} GB   total {(fb + wb) / 1e9:7.2f} GB = "
+                     f"{(fb + wb) / (R * d):.3f} B per replica-param")
+        traffic.append((wl, key[0], key[1], fb + wb))
+    ro = j["roofline"]
+    lines += ["", f"Algorithmic bytes per dispatch, average over the timed steps (R*d = {R * d} elements): {ro['algorithmic_bytes_per_launch']:.0f}",
+              f"roofline of the kernel-trace run: achieved {ro['achieved']:.0f} GB/s of {ro['peak']:.0f} GB/s = {ro['frac']:.3f}; "
+              f"avg launch {ro['avg_launch_ms']:.3f} ms; by phase {json.dumps(ro['ms_by_phase'])}"]
+    with open(a.out, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    if a.traffic:
+        keep = []
+        if os.path.exists(a.traffic):
+            with open(a.traffic) as f:
+                keep = [l.rstrip("\n") for l in f if l.strip() and not l.startswith("#") and l.split()[0] != wl]
+        head = ["# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by a plain 1 GiB copy),",
+                "# written by python -m paper_2410_11998_amd.rocprof_summary fused; bench.py quotes them as roofline.traffic.",
+                "# workload kernel phase bytes source"]
+        rows = keep + [f"{w} {k} {p} {b:.0f} {os.path.relpath(a.out, os.path.dirname(os.path.dirname(os.path.abspath(a.traffic))))}"
+                       for w, k, p, b in traffic]
+        with open(a.traffic, "w") as f:
+            f.write("\n".join(head + sorted(rows)) + "\n")
+    print("\n".join(lines))
+    return 0
+
+
+def cmd_counters(a) -> int:
+    lines = ["rocprofv3 counter summary (averages per dispatch of the library's kernels), one MI355X", "",
+             "Runs (from /tmp with TMPDIR=/tmp; written by python -m paper_2410_11998_amd.rocprof_summary counters):"]
+    table = collections.defaultdict(dict)      # (kernel, phase, counter) -> {label: value}
+    labels = []
+    for spec in a.run:
+        label, directory = spec.split("=", 1)
+        labels.append(label)
+        vals = counter_values(directory)
+        names = sorted({c for v in vals.values() for c in v})
+        j = bench_line(directory)
+        lines.append(f"  {label}: rocprofv3 --pmc {' '.join(names)} --output-format csv -d OUT -- {bench_command(directory)}")
+        lines.append(f"      {j['config']['workload']}, {j['config']['hbm_layout']}: {j['ms_per_step']:.3f} ms per step, "
+                     f"roofline fraction {j['roofline']['frac']:.3f}")
+        for (shape, phase), cs in vals.items():
+            if shape == "copy":
+                continue
+            for c, v in cs.items():
+                table[(shape, phase, c)][label] = mean(v)
+    lines += ["", f"  {'kernel':30s} {'phase':10s} {'counter':44s} " + " ".join(f"{l:>14s}" for l in labels)]
+    for (shape, phase, c) in sorted(table):
+        row = table[(shape, phase, c)]
+        lines.append(f"  {shape:30s} {phase:10s} {c:44s} " + " ".join(f"{row[l]:14.5g}" if l in row else f"{'-':>14s}" for l in labels))
+    with open(a.out, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print("\n".join(lines))
+    return 0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    f = sub.add_parser("fused")
+    for name in ("--kt", "--fetch", "--write", "--out"):
+        f.add_argument(name, required=True)
+    f.add_argument("--traffic", default=None)
+    c = sub.add_parser("counters")
+    c.add_argument("--run", action="append", required=True, metavar="LABEL=DIR")
+    c.add_argument("--out", required=True)
+    a = ap.parse_args()
+    return cmd_fused(a) if a.cmd == "fused" else cmd_counters(a)
+
+
+if __name__ == "__main__":
+    sys.exit(main())

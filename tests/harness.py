@@ -55,7 +55,8 @@ class GpuSim:
 
     def __init__(self, n_rows: int, n_cols: int, layout: WL.PackedLayout, hp: HyperF32, csrs: Sequence,
                  param_dtype: str = "f32", grad_dtype: str = "f32", inplace: bool = False,
-                 pad_fill: Optional[float] = None, device: str = "cuda:0", weight_decay=None, spread: bool = False):
+                 pad_fill: Optional[float] = None, device: str = "cuda:0", weight_decay=None, spread: bool = False,
+                 lds_limit_bytes: int = 0):
         self.R, self.C, self.layout, self.hp = n_rows, n_cols, layout, hp
         self.pd, self.gd = param_dtype, grad_dtype
         self.dev = torch.device(device)
@@ -67,17 +68,11 @@ class GpuSim:
         pdt = TORCH_DT[param_dtype]
         dts = [pdt] * n_cols + ([] if inplace else [pdt] * n_rows) + [torch.float32] * (n_rows * (3 if hp.s > 1 else 2))
         if spread:
-            # the benchmark's layout: one arena over most of the free memory, buffers at equal distances
+            # the benchmark's layout: one arena over most of the free memory, buffers dealt over two regions
             from paper_2410_11998_amd.arena import SpreadArena
             sizes = [d * (2 if dt == torch.bfloat16 else 4) for dt in dts]
             keep = 48 << 30                                         # room for the gradients and temporaries of the test
-            free, total = torch.cuda.mem_get_info(self.dev)
-            # the benchmark's placement (computed for an arena over the whole device), as far as the
-            # smaller arena of the test reaches
-            placed, _regions = B.dadam_place_offsets(sizes, total, total)
-            if max(o + n for o, n in zip(placed, sizes)) > free - keep:
-                placed = None
-            self.arena = SpreadArena(sizes, self.dev, keep_free_bytes=keep, offsets=placed)
+            self.arena = SpreadArena(sizes, self.dev, keep_free_bytes=keep)
             bufs = self.arena.views(dts)
             for t in bufs:
                 t.zero_()
@@ -100,7 +95,7 @@ class GpuSim:
                 t[inv] = pad_fill
         self.h = B.dadam_init(n_rows, n_cols, d, layout.offsets, layout.numels, ABI_DT[param_dtype], ABI_DT[grad_dtype],
                               hp.lr, hp.beta1, hp.beta2, hp.eps, hp.s, hp.beta_vhat, device=self.dev.index or 0,
-                              weight_decay=weight_decay)
+                              weight_decay=weight_decay, lds_limit_bytes=lds_limit_bytes)
         self.csrs = list(csrs)
         for k, (rp, col, w) in enumerate(self.csrs):
             B.dadam_set_topology(self.h, k, rp, col, w)
@@ -172,19 +167,7 @@ def csr_oracle(t3) -> O.Csr:
 
 def state_scales(prev: O.State, grads64, t: int, hp: O.Hyper):
     """Magnitudes of the terms of b, m_hat, v_hat after iteration t (for relative bounds)."""
-    sb, sm, sv = [], [], []
-    fold = (t % hp.s == 0)
-    for i in range(len(grads64)):
-        g = np.abs(grads64[i])
-        bmag = np.abs(prev.b[i]) + g / hp.s
-        sb.append(bmag)
-        if fold:
-            sm.append(hp.beta1 * np.abs(prev.m_hat[i]) + (1 - hp.beta1) * bmag)
-            sv.append(hp.bv() * np.abs(prev.v_hat[i]) + (1 - hp.bv()) * bmag * bmag)
-        else:
-            sm.append(np.abs(prev.m_hat[i]))
-            sv.append(np.abs(prev.v_hat[i]))
-    return sb, sm, sv
+    return O.state_magnitude_scales(prev, grads64, t, hp)
 
 
 def per_coordinate_decay(layout: WL.PackedLayout, weight_decay) -> Optional[np.ndarray]:
@@ -285,6 +268,21 @@ class FreeBounds:
         return worst
 
 
+def record(name: str, values: dict):
+    """Print a parity figure and append it to gpurun_out/parity_ratios.jsonl (kept with a GPU run's output)."""
+    import json
+    import os
+    line = json.dumps({"test": name, **{k: (float(v) if isinstance(v, (int, float, np.floating)) else v) for k, v in values.items()}})
+    print("parity:", line, flush=True)
+    try:
+        out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+        os.makedirs(out, exist_ok=True)
+        with open(os.path.join(out, "parity_ratios.jsonl"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
+
+
 def to_device(arr: np.ndarray, dtype: str, dev) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(arr)).to(device=dev, dtype=TORCH_DT[dtype])
 
@@ -292,13 +290,21 @@ def to_device(arr: np.ndarray, dtype: str, dev) -> torch.Tensor:
 def run_parity(wl_name: str, n_rows: int, n_cols: int, layout: WL.PackedLayout, hp: HyperF32, csrs, slot_of_t,
                T: int, seed: int, param_dtype="f32", grad_dtype="f32", grad_std=1e-2, flags=B.DADAM_FUSE_ACCUM,
                inplace=False, shared_init=False, refresh_extra_sources=False, unfused=False, free_running=True,
-               pad_fill: Optional[float] = 777.0, weight_decay=None):
+               pad_fill: Optional[float] = 777.0, weight_decay=None, ranges=None, range_streams: int = 1,
+               lds_limit_bytes: int = 0):
     """Whole-vector parity over T iterations.  Each iteration is checked teacher-forced (the
     oracle restarts from the device's previous state) and, with free_running, a second oracle
-    that never sees device state is compared at the end."""
+    that never sees device state is compared at every iteration within the accumulated bound
+    (FreeBounds); the plain ratio |device - oracle| / (tolerance x scale of the last iteration) at the
+    end of the run is printed and recorded beside it.
+
+    ranges = [(tensor_begin, tensor_end), ...]: every iteration is issued as that sequence of
+    dadam_gossip_step_range calls (the paper's bucket-by-bucket update) instead of one whole step,
+    dealt round-robin over range_streams streams when that is more than one."""
     dev = torch.device("cuda:0")
     sim = GpuSim(n_rows, n_cols, layout, hp, csrs, param_dtype, grad_dtype, inplace=inplace, pad_fill=pad_fill,
-                 weight_decay=weight_decay)
+                 weight_decay=weight_decay, lds_limit_bytes=lds_limit_bytes)
+    side = [torch.cuda.Stream(device=dev) for _ in range(range_streams)] if (ranges and range_streams > 1) else []
     wd = per_coordinate_decay(layout, weight_decay)
     ohp = hp.oracle()
     mask = valid_mask(layout)
@@ -326,6 +332,11 @@ def run_parity(wl_name: str, n_rows: int, n_cols: int, layout: WL.PackedLayout, 
         if unfused:
             sim.step(grads, t, slot, flags & ~B.DADAM_FUSE_ACCUM)
             sim.accumulate(grads, t)
+        elif ranges:
+            torch.cuda.synchronize()                      # inputs are ready before side streams start
+            for k, (tb, te) in enumerate(ranges):
+                st = side[k % len(side)].cuda_stream if side else sim.stream()
+                B.dadam_gossip_step_range(sim.h, slot, grads, t, flags, tb, te, st)
         else:
             sim.step(grads, t, slot, flags)
         torch.cuda.synchronize()
@@ -334,13 +345,21 @@ def run_parity(wl_name: str, n_rows: int, n_cols: int, layout: WL.PackedLayout, 
         ref_x = O.dadam_step(ref_state, g64, csr, t, ohp, "O32m", param_dtype, weight_decay=wd)
         w = compare_step(prev, ref_x, ref_state, got, g64, csr, t, ohp, param_dtype, mask, f"{wl_name} t={t}", wd=wd)
         assert_within(w, f"{wl_name} teacher-forced t={t}")
-        for k in worst_all:
+        for k in w:
             worst_all[k] = max(worst_all[k], w[k])
         if free is not None:
             fprev = O.State(list(free.x_src), list(free.m_hat), list(free.v_hat), list(free.b))
             fx = O.dadam_step(free, g64, csr, t, ohp, "O32m", param_dtype, weight_decay=wd)
             bounds.advance(fprev, g64, csr, t, ohp, 1e-6 / H_RTOL(param_dtype), wd=wd)
-            bounds.check(got, fx, free, H_RTOL(param_dtype), mask, f"{wl_name} free-running t={t}")
+            wf = bounds.check(got, fx, free, H_RTOL(param_dtype), mask, f"{wl_name} free-running t={t}")
+            if t == T:
+                # the plain figure: distance from the free-running oracle over the tolerance times the
+                # scale of this last iteration alone (no allowance for what earlier iterations left behind)
+                s_T = O.magnitude_scale(fprev, g64, csr, t, ohp, weight_decay=wd)
+                plain = max(float((np.abs(got[0][i] - fx[i])[mask] / (H_RTOL(param_dtype) * s_T[i][mask] + 1e-300)).max(initial=0.0))
+                            for i in range(n_rows))
+                worst_all["free_plain_x"] = plain
+                worst_all["free_bound_x"] = wf["x"]
             for i in range(n_rows):
                 free.x_src[i] = fx[i]
         if not inplace:
@@ -362,4 +381,5 @@ def run_parity(wl_name: str, n_rows: int, n_cols: int, layout: WL.PackedLayout, 
                 vals = arr[i][inv]
                 assert bool(torch.all(vals == pad_fill)), f"{wl_name}: padding of {name}[{i}] was written"
     sim.close()
+    record(wl_name, {"dtype": param_dtype, "iterations": T, **worst_all})
     return worst_all

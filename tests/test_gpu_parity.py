@@ -800,3 +800,174 @@ def test_gossip_rounds_in_place_and_ring_contraction_on_the_device():
     for e0, e1 in zip(errs, errs[1:]):
         assert abs(e1 / e0 - 1.0 / 9.0) < 1e-5 * (1.0 / 9.0) * 10
     a.close(); b.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# the per-bucket update against the oracle
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode,topo,inplace,streams,dtype", [
+    ("tile", "ring6", False, 1, "f32"), ("tile", "ring6", True, 2, "f32"), ("tile", "ring6", False, 2, "bf16"),
+    ("direct", "ring6", False, 1, "f32"), ("direct", "ring6", False, 2, "f32"),
+    ("direct", "node_share", True, 1, "f32"), ("direct", "node_share", True, 2, "bf16"), ("tile", "node_share", True, 2, "f32")])
+def test_bucket_by_bucket_update_matches_oracle(mode, topo, inplace, streams, dtype):
+    """The paper updates (and communicates) parameters bucket by bucket (section on overlapping
+    communication and computation); an iteration issued as tensor ranges - in shuffled order, with an
+    empty range, ranges that meet inside a tile of either kernel, on one stream or dealt over two, ping-pong
+    or in place - is compared with the oracle's whole iteration (Algorithm 3 lines 4-13) element by element."""
+    say("case", mode, topo, inplace, streams, dtype)
+    layout = WL.pack(WL.odd_shapes() + [("big", (70001,)), ("mid", (4099,)), ("tail", (333,))])
+    nt = len(layout.names)
+    cuts = [0, 1, 2, 5, 9, nt - 3, nt - 2, nt - 1, nt]
+    ranges = [(cuts[k], cuts[k + 1]) for k in range(len(cuts) - 1)] + [(4, 4)]
+    order = np.random.default_rng(12).permutation(len(ranges))
+    ranges = [ranges[k] for k in order]
+    if topo == "ring6":
+        R, C, csr3 = 6, 6, WL.ring(6)
+    else:
+        R, C, csr3 = 1, 3, WL.node_share_ring()
+    s = 3
+    w = H.run_parity(f"buckets-{mode}-{topo}-{'inplace' if inplace else 'pingpong'}-{streams}streams-{dtype}", R, C, layout,
+                     H.HyperF32(lr=2e-3, s=s), [csr3], lambda t: 0, 2 * s + 1, seed=120, param_dtype=dtype, grad_dtype=dtype,
+                     grad_std=1e-2, flags=B.DADAM_FUSE_ACCUM | MODES[mode], inplace=inplace,
+                     refresh_extra_sources=(topo == "node_share"), ranges=ranges, range_streams=streams,
+                     pad_fill=None if inplace else 777.0)
+    say("worst error / tolerance:", w)
+
+
+# ---------------------------------------------------------------------------------------------
+# exact arithmetic: inputs on which every intermediate is representable, so the bits must agree
+# ---------------------------------------------------------------------------------------------
+
+def dyadic_case(rng, n, d):
+    """Inputs for which every operation of iterations t = 1..4 with s = 4 (group index 1 throughout) is exact in
+    float32: beta1 = 1/2, beta2 = 3/4 (bias corrections 1/2 and 1/4), eps = u = 2^-6, lr = 2^-7, weights 1/2
+    and 1/4.  With v_hat = w u^2 and g = a u the root is sqrt(3 w + a^2) u, an integer q times u for the pairs
+    below, and q + 1 is a power of two, so the division is exact as well."""
+    u = 2.0 ** -6
+    classes = [(0, (1, 3, 7)), (16, (1,)), (15, (2,)), (11, (4,)), (8, (5,)), (3, (0,))]      # w, |a| allowed
+    cls = rng.integers(0, len(classes), size=(n, d))
+    v_hat = np.zeros((n, d))
+    for k, (w, _) in enumerate(classes):
+        v_hat[cls == k] = w * u * u
+    def grads():
+        g = np.zeros((n, d))
+        for k, (_, allowed) in enumerate(classes):
+            sel = cls == k
+            g[sel] = rng.choice(allowed, size=int(sel.sum())) * rng.choice([-1.0, 1.0], size=int(sel.sum())) * u
+        return g
+    m_hat = rng.integers(-8, 9, size=(n, d)) * u
+    x0 = rng.integers(-255, 256, size=(n, d)) * 2.0 ** -7          # 8 significant bits: exact in bfloat16 too
+    return u, x0, m_hat, v_hat, grads
+
+
+@pytest.mark.parametrize("mode", ["tile", "direct"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_dyadic_inputs_give_the_oracles_bits(mode, dtype):
+    """Sums of two, three and four neighbours with weights 1/2 and 1/4, the moment and update arithmetic,
+    accumulation, fold and the bfloat16 store (round to nearest even, ties included) on inputs where
+    nothing is rounded before the final store: the device's bits must equal the oracle's, for every
+    element of a ragged layout, over a whole accumulation loop that ends in a fold."""
+    say("case", mode, dtype)
+    n, s = 4, 4
+    layout = WL.pack(WL.odd_shapes() + [("big", (60001,))])
+    d = layout.d
+    rng = np.random.default_rng(99)
+    u, x0, m0, v0, grads = dyadic_case(rng, n, d)
+    hp = H.HyperF32(lr=2.0 ** -7, beta1=0.5, beta2=0.75, eps=u, s=s)
+    ohp = hp.oracle()
+    half, quarter = np.float32(0.5), np.float32(0.25)
+    rows = (np.array([0, 3, 6, 9, 12], np.int32), np.array([0, 1, 2, 1, 2, 3, 2, 3, 0, 3, 0, 1], np.int32),
+            np.array([half, quarter, quarter] * 4, np.float32))                       # 1/2 self, 1/4 to two neighbours
+    csrs = [WL.one_peer_exponential(n, 0), WL.complete(n), rows, WL.one_peer_exponential(n, 1)]
+    sim = H.GpuSim(n, n, layout, hp, csrs, dtype, dtype, pad_fill=None)
+    dev = torch.device(DEV)
+    for i in range(n):
+        sim.x_src[i].copy_(H.to_device(x0[i], dtype, dev))
+        sim.m[i].copy_(H.to_device(m0[i], "f32", dev))
+        sim.v[i].copy_(H.to_device(v0[i], "f32", dev))
+    state = sim.snapshot()
+    assert all(np.array_equal(state.x_src[i], x0[i]) for i in range(n)), "inputs are not exact in the storage type"
+    mask = H.valid_mask(layout)
+    ties = 0
+    bits = (lambda t_: t_.view(torch.int32)) if dtype == "f32" else (lambda t_: t_.view(torch.int16))
+    for t in range(1, s + 1):
+        g = grads()
+        gd = [H.to_device(g[i], dtype, dev) for i in range(n)]
+        csr = H.csr_oracle(csrs[t - 1])
+        exact = O.dadam_step(O.State(list(state.x_src), list(state.m_hat), list(state.v_hat), list(state.b)),
+                             list(g), csr, t, ohp, "O64", dtype)                  # nothing rounded
+        ref_x = O.dadam_step(state, list(g), csr, t, ohp, "O32m", dtype)
+        if dtype == "f32":
+            assert all(np.array_equal(exact[i], ref_x[i]) for i in range(n)), "the case is not exact in float32"
+        else:
+            for i in range(n):                                                       # exact halves of a bfloat16 step
+                f = exact[i][mask]
+                e = np.floor(np.log2(np.maximum(np.abs(f), 1e-30)))
+                ties += int(np.sum((f != 0) & (np.mod(np.abs(f) / 2.0 ** (e - 7), 1.0) == 0.5)))
+        sim.step(gd, t, t - 1, B.DADAM_FUSE_ACCUM | MODES[mode])
+        torch.cuda.synchronize()
+        for name, got, want, dt in (("x", sim.x_dst, ref_x, dtype), ("m_hat", sim.m, state.m_hat, "f32"),
+                                    ("v_hat", sim.v, state.v_hat, "f32"), ("b", sim.b, state.b, "f32")):
+            view = (lambda t_: t_.view(torch.int16)) if dt == "bf16" else (lambda t_: t_.view(torch.int32))
+            for i in range(n):
+                w_ = H.to_device(want[i], dt, dev)
+                vm = torch.from_numpy(mask).to(dev)
+                same = view(got[i])[vm] == view(w_)[vm]
+                both_zero = (got[i][vm] == 0) & (w_[vm] == 0)                         # +0 and -0 are the same value
+                assert bool(torch.all(same | both_zero)), \
+                    f"t={t} {name}[{i}]: {int((~(same | both_zero)).sum())} elements differ in their bits"
+        state.x_src = ref_x
+        sim.swap()
+    assert bool(np.all(state.b[0] == 0)) and float(np.abs(state.m_hat[0]).max()) > 0       # the loop ended in a fold
+    if dtype == "bf16":
+        say("bfloat16 stores that were exact ties:", ties)
+        assert ties >= 8, "the case does not exercise ties of the bfloat16 store"
+    sim.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# 64 sources: the tile the device's LDS allows, and the direct kernel when it does not fit
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("lds_limit", [0, 32768])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_64_sources_with_and_without_room_for_the_tile(lds_limit, dtype):
+    """The planner works from the LDS size the device reports (160 KB per workgroup on an MI355X): 64
+    sources need a 64 KB tile.  A handle limited to 32 KB cannot stage them and falls back to the direct
+    kernel although sources are shared.  Mixing and the fused step in both, against the oracle, on a
+    one-peer exponential graph of 64 replicas."""
+    say("case", lds_limit, dtype)
+    n = 64
+    layout = WL.pack([("a", (9001,)), ("b", (257,)), ("c", (1030,))])
+    d = layout.d
+    csrs = [WL.one_peer_exponential(n, k) for k in (0, 3, 5)]
+    sim = H.GpuSim(n, n, layout, H.HyperF32(s=2), csrs, dtype, dtype, pad_fill=None, lds_limit_bytes=lds_limit)
+    info = B.dadam_get_plan_info(sim.h)
+    say("plan: lds limit", info.lds_limit_bytes, "dies", info.n_xcds, "tile LDS", info.lds_bytes_tile, "tile mode", info.tile_mode_possible)
+    if lds_limit == 0:
+        assert info.lds_limit_bytes >= 65536 and info.n_xcds >= 1 and info.tile_mode_possible == 1
+        assert B.dadam_slot_uses_tile_mode(sim.h, 0)
+    else:
+        assert info.lds_limit_bytes == 32768 and info.tile_mode_possible == 0
+        assert not B.dadam_slot_uses_tile_mode(sim.h, 0)
+        with pytest.raises(B.DadamError):
+            sim.mix(0, B.DADAM_FORCE_TILE)
+    for c in range(n):
+        sim.x_src[c].copy_(H.to_device(WL.normal_np(4100 + c, d, 0.5), dtype, DEV))
+    mask = H.valid_mask(layout)
+    for slot in range(3):
+        sim.mix(slot)
+        torch.cuda.synchronize()
+        xs = sim._get(sim.x_src, None)
+        csr = H.csr_oracle(csrs[slot])
+        ref = O.mix_only(xs, csr, "O32m", dtype)
+        got = sim._get(sim.x_dst, None)
+        for i in range(n):
+            scale = sum(abs(csr.w[k]) * np.abs(xs[csr.col[k]]) for k in range(csr.row_ptr[i], csr.row_ptr[i + 1]))
+            assert np.all(np.abs(got[i] - ref[i])[mask] <= (H.RTOL[dtype] * scale)[mask]), f"slot {slot} row {i}"
+        sim.swap()
+    sim.close()
+    w = H.run_parity(f"onepeer64-lds{lds_limit}-{dtype}", n, n, layout, H.HyperF32(s=2), csrs, lambda t: (t - 1) % 3, 3, seed=130,
+                     param_dtype=dtype, grad_dtype=dtype, flags=B.DADAM_FUSE_ACCUM, pad_fill=None, lds_limit_bytes=lds_limit)
+    say("worst error / tolerance:", w)

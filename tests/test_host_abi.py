@@ -97,6 +97,36 @@ def test_planner_segments_and_tiles():
         B.dadam_destroy(h)
 
 
+def test_planner_uses_the_lds_and_die_count_it_is_given():
+    """A host-only handle plans for 64 KB of LDS per workgroup and 8 dies unless the configuration says
+    otherwise (a device handle asks the device).  The mixing pass takes its two-vector tile only while
+    that stays within 32 KB (16 sources); a tile that does not fit the limit rules tile mode out."""
+    L = WL.pack([("flat", (100000,))])
+    mk = lambda n, **kw: B.dadam_init(n, n, L.d, L.offsets, L.numels, device=B.DADAM_DEVICE_NONE, **kw)
+    h = mk(64)
+    i = B.dadam_get_plan_info(h)
+    assert (i.lds_limit_bytes, i.n_xcds) == (65536, 8)
+    assert i.tile_mode_possible == 1 and i.lds_bytes_tile == 65536 and (i.mix_vectors, i.lds_bytes_mix) == (1, 65536)
+    B.dadam_destroy(h)
+    h = mk(64, lds_limit_bytes=160 * 1024, n_xcds=4)
+    i = B.dadam_get_plan_info(h)
+    assert (i.lds_limit_bytes, i.n_xcds) == (160 * 1024, 4)
+    assert (i.mix_vectors, i.lds_bytes_mix, i.mix_tile_elems) == (1, 65536, 256)
+    B.dadam_destroy(h)
+    h = mk(16)
+    i = B.dadam_get_plan_info(h)
+    assert (i.mix_waves, i.mix_vectors, i.lds_bytes_mix, i.mix_tile_elems) == (4, 2, 32768, 512)
+    assert i.n_tiles_mix == -(-L.d // 512) and i.n_tiles_tile == -(-L.d // 256)
+    B.dadam_destroy(h)
+    h = mk(32, lds_limit_bytes=16 * 1024)            # 32 sources need 32 KB: no tile mode
+    i = B.dadam_get_plan_info(h)
+    assert i.tile_mode_possible == 0
+    B.dadam_set_topology(h, 0, *WL.ring(32))
+    assert B.dadam_slot_uses_tile_mode(h, 0) is False
+    B.dadam_destroy(h)
+    expect(B.DADAM_EINVAL, mk, 4, n_xcds=1000)
+
+
 def test_pack_offsets_matches_workload_packer():
     L = WL.pack(WL.odd_shapes(), align_elems=8)
     off, d = B.dadam_pack_offsets([int(n) for n in L.numels], 8)
@@ -164,13 +194,82 @@ def test_bind_alignment_and_aliasing_rules():
     assert B.dadam_slot_uses_tile_mode(h, 1) is False                      # in place, nothing shared: direct is legal
     B.dadam_set_topology(h, 2, np.array([0, 1, 2], np.int32), np.array([1, 0], np.int32), np.ones(2, np.float32))
     assert B.dadam_slot_uses_tile_mode(h, 2) is True                       # rows read each other's buffer: needs the tile
-    # launching on a host-only handle is a state error, whatever the arguments
-    expect(B.DADAM_ESTATE, B.dadam_gossip_step, h, 0, [P(11), P(12)], 1)
-    expect(B.DADAM_ESTATE, B.dadam_accumulate, h, [P(11), P(12)], 1)
-    expect(B.DADAM_ESTATE, B.dadam_mix, h, 0)
-    expect(B.DADAM_ESTATE, B.dadam_mix_consensus, h, 0, P(13))
+    # a host-only handle validates a call like a device handle and then refuses to launch
+    assert "host-only" in expect(B.DADAM_ESTATE, B.dadam_gossip_step, h, 0, [P(11), P(12)], 1)
+    assert "host-only" in expect(B.DADAM_ESTATE, B.dadam_accumulate, h, [P(11), P(12)], 1)
+    assert "host-only" in expect(B.DADAM_ESTATE, B.dadam_mix, h, 0)
+    assert "host-only" in expect(B.DADAM_ESTATE, B.dadam_mix_consensus, h, 0, P(13))
     expect(B.DADAM_EINVAL, B.dadam_mix_consensus, h, 0, 0)
     expect(B.DADAM_EINVAL, B.dadam_mix_consensus, h, 0, P(13) + 4)
+    expect(B.DADAM_EINVAL, B.dadam_gossip_step, h, 0, [P(11), P(12)], 0)                 # iterations start at 1
+    expect(B.DADAM_EINVAL, B.dadam_gossip_step, h, 0, [P(11), P(12)], 1, 64)             # unknown flag
+    expect(B.DADAM_EINVAL, B.dadam_gossip_step, h, 0, [P(11), P(12)], 1, B.DADAM_FORCE_TILE | B.DADAM_FORCE_DIRECT)
+    expect(B.DADAM_ESTATE, B.dadam_gossip_step, h, 7, [P(11), P(12)], 1)                 # empty slot
+    expect(B.DADAM_EALIAS, B.dadam_gossip_step, h, 2, [P(11), P(12)], 1, B.DADAM_FUSE_ACCUM | B.DADAM_FORCE_DIRECT)
+    expect(B.DADAM_EINVAL, B.dadam_gossip_step_range, h, 0, [P(11), P(12)], 1, B.DADAM_FUSE_ACCUM, 1, 5)
+    B.dadam_destroy(h)
+
+
+def test_in_place_row_whose_buffer_is_listed_as_two_sources():
+    """Two source entries may name one buffer.  A row updated in place then overwrites both, so the
+    direct kernel is legal only if nobody else reads either of them (update template of eq. (2): every
+    row reads the PREVIOUS iterate)."""
+    h, L = host_handle(2, 3, accum_s=2)
+    nb = L.d * 4
+    P = lambda k: (1 << 20) + k * (nb + 256)
+    # x_src[2] is the same buffer as x_src[0], and row 0 is updated in place in it
+    B.dadam_bind(h, x_src=[P(0), P(1), P(0)], x_dst=[P(0), P(3)], m_hat=[P(5), P(6)], v_hat=[P(7), P(8)], acc=[P(9), P(10)])
+    half = np.full(4, 0.5, np.float32)
+    # row 1 reads source 2, i.e. row 0's buffer: the direct kernel would let it see a new value
+    B.dadam_set_topology(h, 0, np.array([0, 2, 4], np.int32), np.array([0, 1, 1, 2], np.int32), half)
+    assert B.dadam_slot_uses_tile_mode(h, 0) is True
+    expect(B.DADAM_EALIAS, B.dadam_gossip_step, h, 0, [P(11), P(12)], 1, B.DADAM_FUSE_ACCUM | B.DADAM_FORCE_DIRECT)
+    # the same with the entries the other way round (row 1 reads source 0)
+    B.dadam_set_topology(h, 1, np.array([0, 2, 4], np.int32), np.array([2, 1, 1, 0], np.int32), half)
+    assert B.dadam_slot_uses_tile_mode(h, 1) is True
+    expect(B.DADAM_EALIAS, B.dadam_gossip_step, h, 1, [P(11), P(12)], 1, B.DADAM_FUSE_ACCUM | B.DADAM_FORCE_DIRECT)
+    # only row 0 reads its own buffer, under either name: direct is fine
+    B.dadam_set_topology(h, 2, np.array([0, 2, 3], np.int32), np.array([0, 2, 1], np.int32), np.array([0.5, 0.5, 1.0], np.float32))
+    assert B.dadam_slot_uses_tile_mode(h, 2) is False
+    assert "host-only" in expect(B.DADAM_ESTATE, B.dadam_gossip_step, h, 2, [P(11), P(12)], 1, B.DADAM_FUSE_ACCUM | B.DADAM_FORCE_DIRECT)
+    B.dadam_destroy(h)
+
+
+def test_gradient_tables_are_checked_against_the_outputs_and_remembered():
+    """Gradients may not overlap anything a call writes.  A table that passed is remembered, but only
+    for the outputs it was checked against: binding other buffers or exchanging x_src and x_dst makes
+    the library look again."""
+    h, L = host_handle(2, 2, accum_s=2)
+    nb = L.d * 4
+    P = lambda k: (1 << 20) + k * (nb + 256)
+    B.dadam_set_topology(h, 0, *WL.ring(2))
+    bufs = dict(x_src=[P(0), P(1)], x_dst=[P(2), P(3)], m_hat=[P(4), P(5)], v_hat=[P(6), P(7)], acc=[P(8), P(9)])
+    B.dadam_bind(h, **bufs)
+    ok = lambda g, fn=B.dadam_gossip_step: "host-only" in expect(B.DADAM_ESTATE, fn, h, 0, g, 1)
+    for _ in range(3):
+        assert ok([P(10), P(11)])                     # checked once, then found in the cache
+    assert ok([P(0), P(1)])                           # gradients on top of the SOURCES: read-only, harmless
+    for k in (2, 3, 4, 5, 6, 7, 8, 9):                # on top of any output: refused
+        expect(B.DADAM_EALIAS, B.dadam_gossip_step, h, 0, [P(10), P(k)], 1)
+        expect(B.DADAM_EALIAS, B.dadam_gossip_step, h, 0, [P(k) + nb - 16, P(11)], 1)      # last 16 bytes overlap
+        expect(B.DADAM_EALIAS, B.dadam_accumulate, h, [P(10), P(k)], 1)
+    assert ok([P(9) + nb, P(11)])                     # starting exactly where an output ends is fine
+    expect(B.DADAM_EALIGN, B.dadam_gossip_step, h, 0, [P(10) + 8, P(11)], 1)
+    expect(B.DADAM_EINVAL, B.dadam_gossip_step, h, 0, [P(10), 0], 1)
+    # after the exchange the old sources are outputs: the remembered table [P(0), P(1)] must be refused
+    B.dadam_swap_x(h)
+    expect(B.DADAM_EALIAS, B.dadam_gossip_step, h, 0, [P(0), P(1)], 1)
+    assert ok([P(2), P(3)]) and ok([P(10), P(11)])
+    B.dadam_swap_x(h)
+    assert ok([P(0), P(1)])
+    expect(B.DADAM_EALIAS, B.dadam_gossip_step, h, 0, [P(2), P(3)], 1)
+    # many different tables: the memory of checked tables is bounded and stays correct
+    for k in range(40):
+        assert ok([P(20 + k), P(70 + k)])
+    assert ok([P(10), P(11)])
+    # new outputs on top of a remembered gradient table
+    B.dadam_bind(h, **{**bufs, "m_hat": [P(10), P(5)]})
+    expect(B.DADAM_EALIAS, B.dadam_gossip_step, h, 0, [P(10), P(11)], 1)
     B.dadam_destroy(h)
 
 
@@ -321,13 +420,6 @@ def test_bench_byte_accounting_matches_the_workload_table():
         for p in loop:
             assert bench.path_bytes_per_replica_param(wl, p, "fused") == bench.algorithmic_bytes_per_replica_param(wl, p)
             assert bench.path_bytes_per_replica_param(wl, p, "unfused") > bench.algorithmic_bytes_per_replica_param(wl, p)
-    # the quoted traffic table agrees with the algorithmic bytes to a tenth of a percent
-    for name, table in bench.MEASURED_TRAFFIC_BYTES.items():
-        cfg = int(name[3])
-        wl = WL.workload(cfg)
-        n = wl.n_rows * wl.layout().d
-        for phase, measured in table.items():
-            assert abs(measured / (n * bench.algorithmic_bytes_per_replica_param(wl, phase)) - 1.0) < 1e-3
 
 
 def test_host_code_under_address_and_ub_sanitizers(tmp_path):
@@ -428,16 +520,18 @@ def test_c99_client_compiles_links_and_agrees_with_the_binding(tmp_path):
 def test_two_region_placement_policy():
     """Placement advice for device buffers (memory management, no GPU needed): two regions either
     side of the boundary between the first two thirds of the device memory, buffers dealt alternately
-    and staggered inside their gaps."""
+    and staggered inside their gaps; the flag says when the advice could not be applied."""
     from paper_2410_11998_amd import arena as A
     GIB = 1 << 30
     total = 288 * GIB - (20 << 20)
     sizes = [476 << 20] * 112                                   # configuration 2 with two gradient sets
-    regs = A.two_thirds_regions(sizes, 275 * GIB, total)
-    assert regs == [(30 * GIB, 94 * GIB), (98 * GIB, 162 * GIB)]
-    off, used = B.dadam_place_offsets(sizes, 275 * GIB, total)
-    assert used == regs and (off, used) == B.dadam_place_offsets(sizes, 275 * GIB, total)      # deterministic
-    even = A.deal_offsets(sizes, regs)                          # the same regions at equal distances
+    off, regs, advice = B.dadam_place_offsets(sizes, 275 * GIB, 0, total)
+    assert advice == B.DADAM_PLACE_TWO_REGIONS and regs == [(30 * GIB, 94 * GIB), (98 * GIB, 162 * GIB)]
+    assert (off, regs, advice) == B.dadam_place_offsets(sizes, 275 * GIB, 0, total)      # deterministic
+    even = [0] * len(sizes)                                     # the same regions at equal distances
+    for r, (lo, hi) in enumerate(regs):
+        for k, o in zip(range(r, len(sizes), 2), B.dadam_spread_offsets(sizes[r::2], hi - lo)):
+            even[k] = lo + o
     for k, o in enumerate(off):
         lo, hi = regs[k % 2]
         assert lo <= o and o + sizes[k] <= hi and o % (2 << 20) == 0
@@ -451,18 +545,33 @@ def test_two_region_placement_policy():
     for start, count in ((0, 16), (16, 16), (0, 32), (80, 32)):
         n_below = sum(1 for k in range(start, start + count) if off[k] < 96 * GIB)
         assert n_below == count // 2
-    # large buffers widen the regions; what cannot fit two thirds falls back (None)
-    big = [2 * GIB] * 56
-    regs = A.two_thirds_regions(big, 275 * GIB, total)
-    assert regs is not None and regs[0][1] - regs[0][0] >= int(28 * 2 * GIB * 1.2) and regs[0][0] >= 0 and regs[1][1] <= 192 * GIB
-    assert A.two_thirds_regions([3 * GIB] * 56, 275 * GIB, total) is None
-    # an arena that does not cover the device gives no physical positions: equal distances over all of it
-    assert A.two_thirds_regions(sizes, 200 * GIB, total) is None
-    placed, used = B.dadam_place_offsets(sizes, 200 * GIB, total)
-    assert used == [(0, 200 * GIB)] and placed == B.dadam_spread_offsets(sizes, 200 * GIB)
-    assert B.lib.dadam_place_offsets(None, 1, 100, 100, None, None) == B.DADAM_EINVAL
+    # memory already in use shifts the arena: the same physical regions, smaller offsets
+    base = 40 * GIB + (300 << 20)
+    off2, regs2, advice = B.dadam_place_offsets(sizes, 200 * GIB, base, total)
+    assert advice == B.DADAM_PLACE_TWO_REGIONS
+    assert [(lo + base, hi + base) for lo, hi in regs2] == [(40 * GIB + (300 << 20), 94 * GIB), (98 * GIB, 162 * GIB)]
+    assert all(o % (2 << 20) == 0 for o in off2) and max(o + n for o, n in zip(off2, sizes)) <= 200 * GIB
+    # a compact arena: just the stretch the two regions need
+    lo, hi = A.compact_extent(sizes, total)
+    assert lo < 94 * GIB - 56 * (476 << 20) and hi > 98 * GIB + 56 * (476 << 20) and hi - lo < 75 * GIB
+    off3, regs3, advice = B.dadam_place_offsets(sizes, hi - lo, lo, total)
+    assert advice == B.DADAM_PLACE_TWO_REGIONS and regs3[0][0] == 0 and regs3[1][1] == hi - lo
+    assert max(o + n for o, n in zip(off3, sizes)) <= hi - lo
+    # large buffers widen the regions up to the room there is
+    off4, regs4, advice = B.dadam_place_offsets([3 * GIB] * 56, 275 * GIB, 0, total)
+    assert advice == B.DADAM_PLACE_TWO_REGIONS and regs4 == [(0, 94 * GIB), (98 * GIB, 190 * GIB)]
+    # what cannot fit either side of the boundary, or an arena that does not reach across it: equal
+    # distances over the whole arena, and the flag says which
+    placed, used, advice = B.dadam_place_offsets([4 * GIB] * 56, 275 * GIB, 0, total)
+    assert advice == B.DADAM_PLACE_TOO_LARGE and used == [(0, 275 * GIB)] and placed == B.dadam_spread_offsets([4 * GIB] * 56, 275 * GIB)
+    for arena_bytes, base in ((90 * GIB, 0), (100 * GIB, 100 * GIB), (60 * GIB, 80 * GIB)):
+        placed, used, advice = B.dadam_place_offsets(sizes, arena_bytes, base, total)
+        assert advice == B.DADAM_PLACE_ARENA_ELSEWHERE and used == [(0, arena_bytes)]
+        assert placed == B.dadam_spread_offsets(sizes, arena_bytes)
+    assert B.dadam_place_offsets([1 << 30], 275 * GIB, 0, total)[2] == 0          # one buffer: nothing to deal
+    assert B.lib.dadam_place_offsets(None, 1, 100, 0, 100, None, None, None) == B.DADAM_EINVAL
     with pytest.raises(B.DadamError):
-        B.dadam_place_offsets([5 << 20, 5 << 20], 8 << 20, 288 * GIB)
+        B.dadam_place_offsets([5 << 20, 5 << 20], 8 << 20, 0, 288 * GIB)
 
 
 def test_device_access_helpers_on_the_cpu_under_sanitizers(tmp_path):

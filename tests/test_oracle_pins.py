@@ -665,3 +665,118 @@ def test_random_doubly_stochastic_matrices_properties():
                 assert all(np.all(b == 0) for b in st_.b)
 
     check()
+
+
+# ---------------------------------------------------------------------------------------
+# the error scales every relative tolerance of the parity tests is relative to
+# ---------------------------------------------------------------------------------------
+
+def test_error_scales_on_the_hand_worked_trace():
+    """tests/golden/hand_worked_error_scales.txt: the scales of x, b, m_hat, v_hat on the hand-worked
+    trace, in exact fractions (the scale of b and m_hat at t = 2 does not cancel where b itself does)."""
+    rows = {}
+    with open(os.path.join(GOLDEN, "hand_worked_error_scales.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            t, q, a, b = line.split()
+            rows[(int(t), q)] = (float(Fraction(a)), float(Fraction(b)))
+    hp = O.Hyper(lr=1.0, beta1=0.5, beta2=0.75, eps=1.0, s=2)
+    csr = O.Csr(np.array([0, 2, 4]), np.array([0, 1, 0, 1]), np.array([0.5, 0.5, 0.5, 0.5]))
+    st = zeros_state([np.array([1.0]), np.array([3.0])])
+    G = {1: (2.0, -2.0), 2: (4.0, 1.0), 3: (3.0, -0.5)}
+    for t in (1, 2, 3):
+        g = [np.array([G[t][0]]), np.array([G[t][1]])]
+        sx = O.magnitude_scale(st, g, csr, t, hp)
+        sb, sm, sv = O.state_magnitude_scales(st, g, t, hp)
+        for q, arr in (("S_x", sx), ("S_b", sb), ("S_m", sm), ("S_v", sv)):
+            np.testing.assert_allclose([arr[0][0], arr[1][0]], rows[(t, q)], rtol=1e-15, atol=1e-16, err_msg=f"t={t} {q}")
+        st.x_src = O.dadam_step(st, g, csr, t, hp, mode="O64")
+    # weight decay adds lr * |lambda x_own| to the scale of x
+    st = zeros_state([np.array([1.0]), np.array([3.0])])
+    g = [np.array([2.0]), np.array([-2.0])]
+    with_decay = O.magnitude_scale(st, g, csr, 1, hp, weight_decay=0.25)
+    np.testing.assert_allclose([with_decay[0][0], with_decay[1][0]], [8 / 3 + 0.25, 8 / 3 + 0.75], rtol=1e-15)
+
+
+def _float32_iteration(x_src, m_hat, v_hat, b, g, csr, t, hp):
+    """One iteration evaluated the way a float32 implementation does: every operation rounded to
+    float32 (NumPy float32 arithmetic, no fused operations), neighbour sum in list order."""
+    f = np.float32
+    th = O.t_hat(t, hp.s)
+    inv_c1, inv_c2 = f(1.0 / (1.0 - hp.beta1 ** th)), f(1.0 / (1.0 - hp.beta2 ** th))
+    b1, b2, bv, eps, lr, inv_s = f(hp.beta1), f(hp.beta2), f(hp.bv()), f(hp.eps), f(hp.lr), f(1.0 / hp.s)
+    omb1, omb2, ombv = f(1.0 - hp.beta1), f(1.0 - hp.beta2), f(1.0 - hp.bv())
+    xs, ms, vs, bs = [], [], [], []
+    for i in range(csr.n_rows):
+        mix = None
+        for k in range(int(csr.row_ptr[i]), int(csr.row_ptr[i + 1])):
+            term = f(csr.w[k]) * x_src[int(csr.col[k])].astype(f)
+            mix = term if mix is None else mix + term
+        gi, mh, vh, bi = g[i].astype(f), m_hat[i].astype(f), v_hat[i].astype(f), b[i].astype(f)
+        m = b1 * mh + omb1 * gi
+        v = b2 * vh + omb2 * (gi * gi)
+        xs.append(mix - lr * ((m * inv_c1) / (np.sqrt(v * inv_c2) + eps)))
+        bi = bi + gi * inv_s
+        if t % hp.s == 0:
+            mh = b1 * mh + omb1 * bi
+            vh = bv * vh + ombv * (bi * bi)
+            bi = np.zeros_like(bi)
+        ms.append(mh); vs.append(vh); bs.append(bi)
+    return xs, ms, vs, bs
+
+
+@pytest.mark.parametrize("shared_init", [True, False])
+def test_error_scales_bound_a_float32_evaluation_but_not_a_planted_error(shared_init):
+    """What the tolerance 1e-6 x scale has to do: a float32 evaluation of an iteration (about a dozen
+    roundings of 2^-24) stays inside it at every element of every iteration of two accumulation loops,
+    with room to spare but not more than a factor of ten; a relative error of 2^-18 (3.8e-6) planted in
+    x falls outside almost everywhere and one of 2^-19 (1.9e-6) still at nine elements in ten when the
+    replicas are close together (as they are in a real run; elements whose terms cancel have a scale
+    above their value, which is the point of the scale); in the moments and the accumulator, where
+    the terms of a fold cancel more often, at six in ten at least.  A scale too small by a factor of
+    five fails the first half, one too large by a factor of two the second."""
+    n, d, s, T = 8, 4096, 4, 9
+    hp = O.Hyper(lr=float(np.float32(1e-3)), beta1=float(np.float32(0.9)), beta2=float(np.float32(0.999)),
+                 eps=float(np.float32(1e-8)), s=s)
+    csr = csr_of(WL.ring(n))
+    rng = np.random.default_rng(2410)
+    common = rng.standard_normal(d) * 0.02
+    x0 = [O.round_to_f32(common + (0.0 if not shared_init else 1e-4) * rng.standard_normal(d)) if shared_init
+          else O.round_to_f32(rng.standard_normal(d) * 0.02) for _ in range(n)]
+    st = zeros_state(x0)
+    worst = {"x": 0.0, "m": 0.0, "v": 0.0, "b": 0.0}
+    outside18 = {k: 1.0 for k in worst}
+    outside19_x = 1.0
+    for t in range(1, T + 1):
+        g = [O.round_to_f32(rng.standard_normal(d) * 1e-2) for _ in range(n)]
+        sx = O.magnitude_scale(st, g, csr, t, hp)
+        sb, sm, sv = O.state_magnitude_scales(st, g, t, hp)
+        f32 = _float32_iteration(st.x_src, st.m_hat, st.v_hat, st.b, g, csr, t, hp)
+        ref_x = O.dadam_step(st, g, csr, t, hp, mode="O32m")          # advances st's moments and accumulator
+        refs = {"x": ref_x, "m": st.m_hat, "v": st.v_hat, "b": st.b}
+        for key, got, scale in (("x", f32[0], sx), ("m", f32[1], sm), ("v", f32[2], sv), ("b", f32[3], sb)):
+            for i in range(n):
+                ref, sc = refs[key][i], scale[i]
+                live = sc > 0
+                ratio = np.abs(got[i].astype(np.float64) - ref)[live] / (1e-6 * sc[live])
+                worst[key] = max(worst[key], float(ratio.max(initial=0.0)))
+                assert np.all(got[i][~live] == ref[~live])             # a zero scale means an exact zero
+                if live.any():
+                    planted = np.abs(ref * 2.0 ** -18)[live] / (1e-6 * sc[live])
+                    changed = ref[live] != 0
+                    outside18[key] = min(outside18[key], float(np.mean(planted[changed] > 1.0))) if changed.any() else outside18[key]
+                    if key == "x":
+                        outside19_x = min(outside19_x, float(np.mean(np.abs(ref * 2.0 ** -19)[live] / (1e-6 * sc[live]) > 1.0)))
+        st.x_src = ref_x
+    print("float32 evaluation, worst error / (1e-6 x scale):", worst, "planted 2^-18 outside:", outside18, "2^-19 (x):", outside19_x)
+    for key, v in worst.items():
+        assert v <= 1.0, f"{key}: a float32 evaluation is {v:.2f} x the tolerance away: the scale is too small"
+        assert v >= 0.1 or key == "b", f"{key}: the worst float32 error is only {v:.3f} of the tolerance: the scale is too large"
+    assert min(outside18["m"], outside18["v"], outside18["b"]) > 0.6, outside18
+    if shared_init:
+        # replicas close together: nothing cancels in the mixing sum, the scale of x is |x| plus the update
+        assert outside18["x"] > 0.95 and outside19_x > 0.9, (outside18, outside19_x)
+    else:
+        # independent replicas: the mixing sum cancels in part, the scale is larger than |x| there
+        assert outside18["x"] > 0.5, outside18
