@@ -284,8 +284,9 @@ class Workload:
         raise ValueError(self.topology)
 
     def slot_of_step(self, t: int) -> int:
-        """Iteration t (1-based) of a time-varying topology uses slot (t-1) mod n_slots."""
-        return (t - 1) % self.n_slots()
+        """Iteration t of a time-varying topology uses slot t mod n_slots: configuration 4 pairs replica i
+        with i + 2^(t mod 6) at step t.  Any log2(n) consecutive iterations visit every hop once."""
+        return t % self.n_slots()
 
     def bytes_per_replica_param(self) -> float:
         """Algorithmic HBM bytes per updated element, averaged over an accumulation

@@ -247,7 +247,8 @@ def test_one_peer_exponential_reaches_exact_mean_after_log2n_slots(n):
 def test_workload_slot_schedule():
     wl = WL.workload(4)
     assert wl.n_slots() == 6
-    assert [wl.slot_of_step(t) for t in (1, 2, 6, 7, 30)] == [0, 1, 5, 0, 5]
+    assert [wl.slot_of_step(t) for t in (1, 2, 5, 6, 7, 30)] == [1, 2, 5, 0, 1, 0]       # hop 2^(t mod 6) at step t
+    assert sorted(wl.slot_of_step(t) for t in range(11, 17)) == list(range(6))             # any 6 in a row: every hop once
     rp, col, w = wl.csr(3)
     assert list(col[:2]) == [0, 8] and np.all(w == np.float32(0.5))
     rp, col, w = WL.workload(2).csr()
