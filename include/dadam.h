@@ -218,6 +218,20 @@ int dadam_mix(dadam_handle* h, uint32_t slot, uint32_t flags, void* hip_stream);
 int dadam_mix_consensus(dadam_handle* h, uint32_t slot, uint32_t flags, double* consensus_out,
                         void* hip_stream);
 
+/* dadam_mix_consensus for callers that cannot allocate device memory or tolerate a library that does:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same results; the partial sums of the consensus error live in an array of DADAM_STATIC_SCRATCH_BYTES
+ * bytes inside the library's own device image (every GPU holds its copy from the moment the library is
+ * loaded until the process ends) instead of the handle's allocated buffer.  The call itself allocates and
+ * frees nothing and clears the array with a kernel before use (it keeps the previous call's contents).
+ * ALL handles and calls on one GPU share that one array: two such calls must not overlap in time on a
+ * GPU, whatever their streams or handles.  A pass that needed more partial sums than the array holds
+ * would be refused with DADAM_EINVAL (today every pass needs exactly DADAM_STATIC_SCRATCH_BYTES / 8).
+ * Other errors as dadam_mix_consensus. */
+#define DADAM_STATIC_SCRATCH_BYTES 8192u
+int dadam_mix_consensus_static(dadam_handle* h, uint32_t slot, uint32_t flags, double* consensus_out,
+                               void* hip_stream);
+
 /* Change the step size used by later calls (learning-rate schedules). */
 int dadam_set_lr(dadam_handle* h, float lr);
 

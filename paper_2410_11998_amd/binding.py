@@ -23,6 +23,7 @@ LIB_PATH = os.path.join(_HERE, "libdadam.so")
 DADAM_ABI_VERSION = 2
 DADAM_MAX_ROWS = 64
 DADAM_MAX_SLOTS = 16
+DADAM_STATIC_SCRATCH_BYTES = 8192
 DADAM_DEVICE_NONE = -1
 DADAM_F32, DADAM_BF16 = 0, 1
 DADAM_OK, DADAM_EINVAL, DADAM_EALIGN, DADAM_ETOPO, DADAM_EALIAS, DADAM_ESTATE, DADAM_EHIP = 0, -1, -2, -3, -4, -5, -6
@@ -32,7 +33,7 @@ DADAM_PLACE_TWO_REGIONS, DADAM_PLACE_ARENA_ELSEWHERE, DADAM_PLACE_TOO_LARGE = 1,
 
 EXPORTS = [
     "dadam_init", "dadam_set_topology", "dadam_bind", "dadam_swap_x", "dadam_gossip_step",
-    "dadam_gossip_step_range", "dadam_accumulate", "dadam_mix", "dadam_mix_consensus", "dadam_set_lr", "dadam_get_plan_info",
+    "dadam_gossip_step_range", "dadam_accumulate", "dadam_mix", "dadam_mix_consensus", "dadam_mix_consensus_static", "dadam_set_lr", "dadam_get_plan_info",
     "dadam_slot_uses_tile_mode", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_place_offsets", "dadam_last_error",
     "dadam_destroy",
 ]
@@ -82,6 +83,7 @@ def _load() -> C.CDLL:
     lib.dadam_accumulate.argtypes = [H, C.POINTER(C.c_void_p), C.c_uint64, C.c_void_p]
     lib.dadam_mix.argtypes = [H, C.c_uint32, C.c_uint32, C.c_void_p]
     lib.dadam_mix_consensus.argtypes = [H, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]
+    lib.dadam_mix_consensus_static.argtypes = [H, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]
     lib.dadam_set_lr.argtypes = [H, C.c_float]
     lib.dadam_get_plan_info.argtypes = [H, C.POINTER(dadam_plan_info)]
     lib.dadam_slot_uses_tile_mode.argtypes = [H, C.c_uint32]
@@ -263,6 +265,15 @@ def dadam_mix_consensus(h, slot: int, out, flags: int = 0, stream: int = 0) -> N
             raise ValueError("consensus output must hold one float64")
         out = out.data_ptr()
     _check(h, lib.dadam_mix_consensus(h, slot, flags, C.c_void_p(out), C.c_void_p(stream)))
+
+
+def dadam_mix_consensus_static(h, slot: int, out, flags: int = 0, stream: int = 0) -> None:
+    """out: a device tensor holding one float64 (or an integer device address)."""
+    if not isinstance(out, int):
+        if out.numel() < 1 or out.element_size() != 8:
+            raise ValueError("consensus output must hold one float64")
+        out = out.data_ptr()
+    _check(h, lib.dadam_mix_consensus_static(h, slot, flags, C.c_void_p(out), C.c_void_p(stream)))
 
 
 def dadam_set_lr(h, lr: float) -> None:

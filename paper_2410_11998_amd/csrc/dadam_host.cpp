@@ -59,6 +59,8 @@ struct dadam_handle {
   std::vector<Segment> segs;
   Segment* d_segs = nullptr;
   double* d_partials = nullptr;  // kConsensusPartials doubles of scratch for the consensus error
+  double* d_static_partials = nullptr;  // the same in the library's device image (dadam_mix_consensus_static)
+  uint32_t static_capacity = 0;         // doubles it holds
   TileShape shape{4, 1, false};
   TileShape mix_shape{4, 1, false};  // shape of the mixing-only launch (more bytes in flight per wavefront)
   uint32_t mix_tile_elems = 0, mix_lds_bytes = 0;
@@ -334,7 +336,8 @@ int resolve_range(const dadam_handle* h, uint32_t tb, uint32_t te, bool whole, u
 }
 
 int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint64_t t, uint32_t flags,
-              bool whole, uint32_t tb, uint32_t te, bool mix_only, void* stream, double* consensus_out = nullptr) {
+              bool whole, uint32_t tb, uint32_t te, bool mix_only, void* stream, double* consensus_out = nullptr,
+              double* partials = nullptr) {
   if (!h) return DADAM_EINVAL;
   int rc = check_bound(h);
   if (rc) return rc;
@@ -368,14 +371,15 @@ int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint6
   if (rc) return rc;
   rc = check_device(h);
   if (rc) return rc;
+  if (!partials) partials = h->d_partials;
   DeviceGuard guard(h->cfg.device);
   if (guard.err != hipSuccess) return fail(h, DADAM_EHIP, "hipSetDevice: %s", hipGetErrorString(guard.err));
   if (consensus_out) {
-    int e0 = launch_consensus_zero(h->d_partials, stream);
+    int e0 = launch_consensus_zero(partials, stream);
     if (e0 != (int)hipSuccess) return fail(h, DADAM_EHIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)e0));
   }
   if (empty) {
-    if (consensus_out) (void)launch_consensus_sum(h->d_partials, consensus_out, stream);
+    if (consensus_out) (void)launch_consensus_sum(partials, consensus_out, stream);
     return DADAM_OK;
   }
   uint32_t w0 = 0, w1 = 0;
@@ -387,7 +391,7 @@ int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint6
   a.work_begin = w0;
   a.clip_lo = lo;
   a.clip_hi = hi;
-  a.partials = h->d_partials;
+  a.partials = partials;
   fill_scalars(h, mix_only ? 1 : t, &a.s);
   int e = tile_mode
               ? launch_tile((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase, mix_only ? h->mix_shape : h->shape, a, w1 - w0,
@@ -395,7 +399,7 @@ int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint6
               : launch_direct((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase,
                               // where rows share sources the re-reads must find them in the cache
                               h->nontemporal && !slot.reuse, a, w1 - w0, stream);
-  if (e == (int)hipSuccess && consensus_out) e = launch_consensus_sum(h->d_partials, consensus_out, stream);
+  if (e == (int)hipSuccess && consensus_out) e = launch_consensus_sum(partials, consensus_out, stream);
   if (e != (int)hipSuccess)
     return fail(h, DADAM_EHIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)e));
   return DADAM_OK;
@@ -535,6 +539,8 @@ int dadam_init(const dadam_config* cfg, dadam_handle** out) {
         e = hipMemcpy(h->d_segs, h->segs.data(), h->segs.size() * sizeof(Segment), hipMemcpyHostToDevice);
     }
     if (e == hipSuccess) e = hipMalloc((void**)&h->d_partials, kConsensusPartials * sizeof(double));
+    // the array in the device image: its address on THIS device (the guard has made it current)
+    if (e == hipSuccess) e = (hipError_t)static_partials(&h->d_static_partials, &h->static_capacity);
     if (e != hipSuccess) {
       if (h->d_segs) (void)hipFree(h->d_segs);
       if (h->d_partials) (void)hipFree(h->d_partials);
@@ -697,6 +703,20 @@ int dadam_mix_consensus(dadam_handle* h, uint32_t slot, uint32_t flags, double* 
   if (!consensus_out || (reinterpret_cast<uintptr_t>(consensus_out) & 7u))
     return fail(h, DADAM_EINVAL, "consensus_out must be a non-null, 8-byte aligned device pointer");
   return step_impl(h, slot, nullptr, 1, flags, true, 0, 0, true, hip_stream, consensus_out);
+}
+
+int dadam_mix_consensus_static(dadam_handle* h, uint32_t slot, uint32_t flags, double* consensus_out, void* hip_stream) {
+  if (!h) return DADAM_EINVAL;
+  if (flags & DADAM_FUSE_ACCUM) return fail(h, DADAM_EINVAL, "dadam_mix_consensus_static takes only the FORCE flags");
+  if (!consensus_out || (reinterpret_cast<uintptr_t>(consensus_out) & 7u))
+    return fail(h, DADAM_EINVAL, "consensus_out must be a non-null, 8-byte aligned device pointer");
+  if (h->cfg.device != DADAM_DEVICE_NONE) {
+    if (!h->d_static_partials) return fail(h, DADAM_ESTATE, "the static scratch array was not resolved on this device");
+    if (kConsensusPartials > h->static_capacity)
+      return fail(h, DADAM_EINVAL, "the pass needs %u partial sums, the static scratch array holds %u (DADAM_STATIC_SCRATCH_BYTES = %u)",
+                  kConsensusPartials, h->static_capacity, DADAM_STATIC_SCRATCH_BYTES);
+  }
+  return step_impl(h, slot, nullptr, 1, flags, true, 0, 0, true, hip_stream, consensus_out, h->d_static_partials);
 }
 
 int dadam_accumulate(dadam_handle* h, const void* const* grads, uint64_t t, void* hip_stream) {

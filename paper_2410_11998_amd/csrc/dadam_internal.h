@@ -49,6 +49,7 @@ enum Phase : int {
 };
 
 constexpr uint32_t kConsensusPartials = 1024;  // partial sums the tiles scatter their contributions over
+static_assert(kConsensusPartials * sizeof(double) == DADAM_STATIC_SCRATCH_BYTES, "the header states the static scratch size");
 
 // Kernel argument block (passed by value; about 3.2 KB of the 4 KB kernarg segment).
 struct StepArgs {
@@ -91,6 +92,10 @@ int launch_accumulate(int gdt, Phase phase, bool nontemporal, const StepArgs& a,
 // Consensus error: clear the partial sums / add them up in a fixed order into *out (device).
 int launch_consensus_zero(double* partials, void* stream);
 int launch_consensus_sum(const double* partials, double* out, void* stream);
+
+// The partial-sum array that lives in the library's device image (no allocation): its address on the
+// current device and its capacity in doubles.  Returns a hipError_t as int.
+int static_partials(double** out, uint32_t* capacity);
 
 // Geometry the host planner needs.
 int vec_elems(int xdt);              // elements per 16-byte parameter vector: 4 (f32) or 8 (bf16)

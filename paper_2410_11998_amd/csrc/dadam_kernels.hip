@@ -27,6 +27,15 @@
 
 #include "dadam_internal.h"
 
+// Scratch memory of the entry point that may not allocate (dadam_mix_consensus_static): the partial sums
+// of the consensus error, in the library's own image instead of a hipMalloc'ed buffer.  Every GPU the
+// library runs on holds its own copy at its own address; host code never uses this name as an
+// address, only what hipGetSymbolAddress returned for the current device (static_partials below).
+// The compiler makes a static device variable visible to the runtime only once it has seen host code
+// refer to it, at the end of the translation unit: nothing may force it out earlier (no `used`
+// attribute), or the symbol stays local to the code object and the look-up by name aborts.
+static __device__ __align__(256) double scratch[dadam::kConsensusPartials];
+
 namespace dadam {
 namespace {
 
@@ -907,6 +916,29 @@ int launch(KernelFn fn, uint32_t grid, uint32_t block, uint32_t lds, const StepA
 static_assert(sizeof(StepArgs) <= 4096, "kernel argument block must fit the kernarg segment");
 
 }  // namespace
+
+// Address and capacity (in doubles) of `scratch` on the CURRENT device, resolved once per device.
+int static_partials(double** out, uint32_t* capacity) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static double* addr[kMaxDevices] = {};
+  *out = nullptr;
+  *capacity = (uint32_t)(sizeof(scratch) / sizeof(double));
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!p) return (int)hipErrorInvalidSymbol;
+    addr[dev] = static_cast<double*>(p);
+  }
+  *out = addr[dev];
+  return (int)hipSuccess;
+}
 
 int launch_consensus_zero(double* partials, void* stream) {
   hipLaunchKernelGGL(k_consensus_zero, dim3(1), dim3(256), 0, reinterpret_cast<hipStream_t>(stream), partials);

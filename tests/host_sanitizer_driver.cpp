@@ -16,6 +16,7 @@ int launch_direct(int, int, Phase, bool, const StepArgs&, uint32_t, void*) { ret
 int launch_accumulate(int, Phase, bool, const StepArgs&, uint32_t, void*, int) { return 0; }
 int launch_consensus_zero(double*, void*) { return 0; }
 int launch_consensus_sum(const double*, double*, void*) { return 0; }
+int static_partials(double** out, uint32_t* capacity) { *out = nullptr; *capacity = kConsensusPartials; return 0; }
 int vec_elems(int xdt) { return xdt == DADAM_BF16 ? 8 : 4; }
 int direct_unroll() { return 2; }
 bool tile_shape_supported(TileShape s) { return (s.waves == 4 || s.waves == 8) && (s.ut == 1 || s.ut == 2); }

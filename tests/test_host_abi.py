@@ -346,7 +346,7 @@ def test_spread_offsets_properties():
 
 
 def test_kernels_use_no_scratch_memory_and_load_neighbour_lists_with_all_lanes(tmp_path):
-    """Two properties of the compiled device code, read from the compiler's own output.
+    """Three properties of the compiled device code, read from the compiler's own output.
 
     (1) Every kernel keeps its state in registers: a struct copied to private memory once cost 8 %
     of the step's bandwidth without any test noticing (resource-usage remarks, scratch size 0).
@@ -374,6 +374,12 @@ def test_kernels_use_no_scratch_memory_and_load_neighbour_lists_with_all_lanes(t
     sizes = [int(x) for x in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", r.stderr)]
     assert len(sizes) > 100, "no resource remarks found"
     assert max(sizes) == 0, f"{sum(1 for s in sizes if s)} kernels spill or copy to scratch"
+
+    # (3) the scratch array of the entry point that does not allocate is looked up by name at run time: the
+    # code object must export it (a symbol left local makes the runtime abort in dadam_init)
+    asm_text = open(asm).read()
+    assert re.search(r"^\s*\.globl\s+_ZL7scratch\s*$", asm_text, flags=re.M), "static scratch array is not visible to the runtime"
+    assert re.search(r"^_ZL7scratch:", asm_text, flags=re.M) and ".local\t_ZL7scratch" not in asm_text
 
     name, depth, loads, checked, bad = None, 0, {}, 0, []
     with open(asm) as f:
