@@ -38,7 +38,12 @@
  *     and unmodified until that work has finished.
  *   - All validation happens on the host before anything is launched; a failed call launches
  *     nothing.
- *   - At most DADAM_MAX_ROWS rows and DADAM_MAX_ROWS source buffers per handle.
+ *   - At most DADAM_MAX_ROWS rows and DADAM_MAX_ROWS source buffers per handle (tile mode needs 1 KB of
+ *     LDS per source buffer: 160 KB for 160).  Up to 64 of each, every launch carries its own copy of the
+ *     pointer tables.  Beyond that the tables of the bound buffers live in device memory, one immutable
+ *     copy per dadam_bind; the library keeps the last DADAM_BINDINGS_KEPT of them, so work launched under
+ *     a binding must have finished before that many further dadam_bind calls are made, and dadam_bind
+ *     then copies to the device (it may wait for work in flight; not for use under stream capture).
  *   - A handle is not thread-safe: calls on one handle must come from one thread at a time.  Launches
  *     on different streams may be in flight together (every launch carries its own copy of the pointer
  *     tables and scalars), except dadam_mix_consensus, whose calls share scratch memory of the handle.
@@ -53,8 +58,9 @@ extern "C" {
 #endif
 
 #define DADAM_ABI_VERSION 2u
-#define DADAM_MAX_ROWS 64u
+#define DADAM_MAX_ROWS 160u
 #define DADAM_MAX_SLOTS 16u
+#define DADAM_BINDINGS_KEPT 8u
 #define DADAM_DEVICE_NONE (-1) /* host-only handle: validation and planning work, launches fail */
 
 /* element types of parameters and gradients; m_hat, v_hat and b are always float32 */

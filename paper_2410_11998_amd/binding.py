@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdadam.so")
 
 DADAM_ABI_VERSION = 2
-DADAM_MAX_ROWS = 64
+DADAM_MAX_ROWS = 160
 DADAM_MAX_SLOTS = 16
 DADAM_STATIC_SCRATCH_BYTES = 8192
 DADAM_DEVICE_NONE = -1

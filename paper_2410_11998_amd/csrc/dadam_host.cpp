@@ -59,6 +59,11 @@ struct dadam_handle {
   std::vector<Segment> segs;
   Segment* d_segs = nullptr;
   double* d_partials = nullptr;  // kConsensusPartials doubles of scratch for the consensus error
+  // Handles with more than kInlineRows rows or sources: device copies of the bound pointer tables, two per
+  // binding (as bound, and with x_src / x_dst exchanged), DADAM_BINDINGS_KEPT bindings in a ring.
+  BoundTables* d_tables = nullptr;
+  uint32_t binding = 0;  // ring position of the current binding
+  bool swapped = false;  // dadam_swap_x flips between the binding's two copies
   double* d_static_partials = nullptr;  // the same in the library's device image (dadam_mix_consensus_static)
   uint32_t static_capacity = 0;         // doubles it holds
   TileShape shape{4, 1, false};
@@ -237,14 +242,18 @@ int check_grads(dadam_handle* h, const void* const* grads) {
 void fill_args(const dadam_handle* h, const Slot* slot, const void* const* grads, StepArgs* a) {
   memset(a, 0, sizeof(*a));
   const uint32_t R = h->cfg.n_rows, C = h->cfg.n_cols;
-  for (uint32_t c = 0; c < C; ++c) a->x_src[c] = h->x_src[c];
-  for (uint32_t i = 0; i < R; ++i) {
-    a->x_dst[i] = h->x_dst[i];
-    a->m_hat[i] = h->m_hat[i];
-    a->v_hat[i] = h->v_hat[i];
-    a->acc[i] = h->acc[i];
-    a->grad[i] = grads ? grads[i] : nullptr;
+  if (h->d_tables) {
+    a->ext = h->d_tables + 2 * h->binding + (h->swapped ? 1 : 0);
+  } else if (R <= (uint32_t)kInlineRows && C <= (uint32_t)kInlineRows) {
+    for (uint32_t c = 0; c < C; ++c) a->x_src[c] = h->x_src[c];
+    for (uint32_t i = 0; i < R; ++i) {
+      a->x_dst[i] = h->x_dst[i];
+      a->m_hat[i] = h->m_hat[i];
+      a->v_hat[i] = h->v_hat[i];
+      a->acc[i] = h->acc[i];
+    }
   }
+  for (uint32_t i = 0; i < R; ++i) a->grad[i] = grads ? grads[i] : nullptr;
   if (slot) {
     a->row_ptr = slot->d_row_ptr;
     a->col = slot->d_col;
@@ -538,12 +547,15 @@ int dadam_init(const dadam_config* cfg, dadam_handle** out) {
       if (e == hipSuccess)
         e = hipMemcpy(h->d_segs, h->segs.data(), h->segs.size() * sizeof(Segment), hipMemcpyHostToDevice);
     }
+    if (e == hipSuccess && (cfg->n_rows > (uint32_t)kInlineRows || cfg->n_cols > (uint32_t)kInlineRows))
+      e = hipMalloc((void**)&h->d_tables, 2 * DADAM_BINDINGS_KEPT * sizeof(BoundTables));
     if (e == hipSuccess) e = hipMalloc((void**)&h->d_partials, kConsensusPartials * sizeof(double));
     // the array in the device image: its address on THIS device (the guard has made it current)
     if (e == hipSuccess) e = (hipError_t)static_partials(&h->d_static_partials, &h->static_capacity);
     if (e != hipSuccess) {
       if (h->d_segs) (void)hipFree(h->d_segs);
       if (h->d_partials) (void)hipFree(h->d_partials);
+      if (h->d_tables) (void)hipFree(h->d_tables);
       delete h;
       return fail(nullptr, DADAM_EHIP, "device set-up failed: %s", hipGetErrorString(e));
     }
@@ -655,6 +667,35 @@ int dadam_bind(dadam_handle* h, const dadam_buffers* b) {
       return fail(h, DADAM_EALIAS, "buffers overlap: kind %d index %d and kind %d index %d (0 x_src, 1 x_dst, 2 state)",
                   a.kind, a.index, c.kind, c.index);
     }
+  if (h->d_tables) {
+    // The tables do not fit the kernel arguments: two immutable device copies for this binding (as bound,
+    // and as dadam_swap_x would leave it), in the ring slot after the current one, so that launches in
+    // flight keep reading the copies they were given.
+    std::vector<BoundTables> t(2);
+    memset(t.data(), 0, 2 * sizeof(BoundTables));
+    for (int v = 0; v < 2; ++v) {
+      for (uint32_t c = 0; c < C; ++c) t[v].x_src[c] = (uint64_t)(uintptr_t)b->x_src[c];
+      for (uint32_t i = 0; i < R; ++i) {
+        t[v].x_dst[i] = (uint64_t)(uintptr_t)b->x_dst[i];
+        t[v].m_hat[i] = (uint64_t)(uintptr_t)b->m_hat[i];
+        t[v].v_hat[i] = (uint64_t)(uintptr_t)b->v_hat[i];
+        t[v].acc[i] = b->acc ? (uint64_t)(uintptr_t)b->acc[i] : 0;
+      }
+    }
+    if (R == C)
+      for (uint32_t i = 0; i < R; ++i)
+        if (inplace[i].empty()) {  // what dadam_swap_x does
+          t[1].x_src[i] = (uint64_t)(uintptr_t)b->x_dst[i];
+          t[1].x_dst[i] = (uint64_t)(uintptr_t)b->x_src[i];
+        }
+    const uint32_t next = h->bound ? (h->binding + 1) % DADAM_BINDINGS_KEPT : h->binding;
+    DeviceGuard guard(h->cfg.device);
+    hipError_t e = guard.err;
+    if (e == hipSuccess) e = hipMemcpy(h->d_tables + 2 * next, t.data(), 2 * sizeof(BoundTables), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail(h, DADAM_EHIP, "copying the pointer tables to the device failed: %s", hipGetErrorString(e));
+    h->binding = next;
+  }
+  h->swapped = false;
   for (uint32_t c = 0; c < C; ++c) h->x_src[c] = b->x_src[c];
   for (uint32_t i = 0; i < R; ++i) {
     h->x_dst[i] = b->x_dst[i];
@@ -679,6 +720,7 @@ int dadam_swap_x(dadam_handle* h) {
     h->x_dst[i] = s;
   }
   h->outputs_gen ^= 1u;
+  h->swapped = !h->swapped;
   return DADAM_OK;
 }
 
@@ -899,6 +941,7 @@ void dadam_destroy(dadam_handle* h) {
     for (Slot& s : h->slots) free_slot(s);
     if (h->d_segs) (void)hipFree(h->d_segs);
     if (h->d_partials) (void)hipFree(h->d_partials);
+    if (h->d_tables) (void)hipFree(h->d_tables);
   }
   delete h;
 }

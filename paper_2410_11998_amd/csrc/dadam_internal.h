@@ -9,7 +9,8 @@
 
 namespace dadam {
 
-constexpr int kMaxRows = DADAM_MAX_ROWS;
+constexpr int kMaxRows = DADAM_MAX_ROWS;  // rows / source buffers a handle may have
+constexpr int kInlineRows = 64;           // up to this many, every pointer table travels in the kernel arguments
 constexpr int kWave = 64;            // gfx950 wavefront
 constexpr int kDirectThreads = 256;  // workgroup of the direct and accumulate kernels
 
@@ -51,14 +52,29 @@ enum Phase : int {
 constexpr uint32_t kConsensusPartials = 1024;  // partial sums the tiles scatter their contributions over
 static_assert(kConsensusPartials * sizeof(double) == DADAM_STATIC_SCRATCH_BYTES, "the header states the static scratch size");
 
-// Kernel argument block (passed by value; about 3.2 KB of the 4 KB kernarg segment).
+// Pointer tables of the bound buffers of a handle with more than kInlineRows rows or sources: they do not
+// fit the 4 KB kernel-argument segment and live in device memory, one immutable copy per binding and
+// exchange state (see dadam_bind).
+// Addresses are held as 64-bit integers on purpose: see the kernels' table helpers.
+struct BoundTables {
+  uint64_t x_src[kMaxRows];
+  uint64_t x_dst[kMaxRows];
+  uint64_t m_hat[kMaxRows];
+  uint64_t v_hat[kMaxRows];
+  uint64_t acc[kMaxRows];
+};
+
+// Kernel argument block (passed by value; 3.9 KB of the 4 KB kernarg segment).  The tables of the bound
+// buffers are used when `ext` is null (at most kInlineRows rows and sources); otherwise `ext` holds them.
+// The gradient pointers change from call to call and always travel here.
 struct StepArgs {
-  const void* x_src[kMaxRows];
-  void* x_dst[kMaxRows];
-  float* m_hat[kMaxRows];
-  float* v_hat[kMaxRows];
-  float* acc[kMaxRows];
+  const void* x_src[kInlineRows];
+  void* x_dst[kInlineRows];
+  float* m_hat[kInlineRows];
+  float* v_hat[kInlineRows];
+  float* acc[kInlineRows];
   const void* grad[kMaxRows];
+  const BoundTables* ext;
   const int32_t* row_ptr;  // device CSR of the slot
   const int32_t* col;
   const float* w;

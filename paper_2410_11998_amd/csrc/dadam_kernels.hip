@@ -278,51 +278,101 @@ __device__ __forceinline__ void locate(const StepArgs& a, uint32_t work, uint64_
   weight_decay = seg[s].weight_decay;
 }
 
-// Row i's slice of the neighbour list, one entry per lane, and its bounds as wave-uniform values.
+// Pointers of the bound buffers: from the argument block, or from the device-resident tables of a handle
+// with more rows or sources than the block holds (a wave-uniform choice).  The read from the argument
+// block is unconditional (index wrapped into the array), the other one sits under the branch and reads
+// an integer: were both reads of the same type, the compiler would fold them into one read through a
+// chosen address, could then no longer keep the argument block out of private memory, and would copy
+// all 4 KB of it to scratch in every thread (the compile test checks that no kernel uses scratch).
+enum TableOf : int { kSrc = 0, kDst = 1, kMHat = 2, kVHat = 3, kAcc = 4 };  // order of BoundTables' members
+static_assert(sizeof(BoundTables) == 5 * kMaxRows * sizeof(uint64_t), "BoundTables is five arrays of addresses");
+template <typename P>
+__device__ __forceinline__ P table_entry(P from_args, const BoundTables* ext, TableOf which, int index) {
+  uint64_t v = reinterpret_cast<uint64_t>(from_args);
+  if (ext) v = reinterpret_cast<const uint64_t*>(ext)[which * kMaxRows + index];
+  return reinterpret_cast<P>(v);
+}
+__device__ __forceinline__ const void* src_of(const StepArgs& a, int c) {
+  return table_entry(a.x_src[c & (kInlineRows - 1)], a.ext, kSrc, c);
+}
+__device__ __forceinline__ void* dst_of(const StepArgs& a, int i) {
+  return table_entry(a.x_dst[i & (kInlineRows - 1)], a.ext, kDst, i);
+}
+__device__ __forceinline__ float* m_hat_of(const StepArgs& a, int i) {
+  return table_entry(a.m_hat[i & (kInlineRows - 1)], a.ext, kMHat, i);
+}
+__device__ __forceinline__ float* v_hat_of(const StepArgs& a, int i) {
+  return table_entry(a.v_hat[i & (kInlineRows - 1)], a.ext, kVHat, i);
+}
+__device__ __forceinline__ float* acc_of(const StepArgs& a, int i) {
+  return table_entry(a.acc[i & (kInlineRows - 1)], a.ext, kAcc, i);
+}
+
+// Up to 64 entries of row i's neighbour list, one per lane (a row with more entries is walked in chunks
+// of 64), the row's length and where its list starts, as wave-uniform values.
 struct RowList {
   int32_t col_v;
   float w_v;
-  int deg;
+  int deg;  // entries of the whole row
+  int k0;   // index of the row's first entry in col / w
 };
+
+// Entries [k0 + first, k0 + first + 64) of a row of `deg` entries, one per lane.
+__device__ __forceinline__ void load_list_chunk(const StepArgs& a, RowList& r, int first, int lane) {
+  const int left = r.deg - first;  // >= 1
+  const int idx = r.k0 + first + (lane < left ? lane : 0);
+  r.col_v = a.col[idx];
+  r.w_v = a.w[idx];
+}
 
 __device__ __forceinline__ RowList load_row_list(const StepArgs& a, int row, int lane) {
   // row_ptr entries are read by every lane from the same address (one broadcast transaction)
   int k0 = __builtin_amdgcn_readfirstlane(a.row_ptr[row]);
   int k1 = __builtin_amdgcn_readfirstlane(a.row_ptr[row + 1]);
   RowList r;
-  r.deg = k1 - k0;  // host guarantees 1 <= deg <= n_cols <= 64
-  int idx = k0 + (lane < r.deg ? lane : 0);
-  r.col_v = a.col[idx];
-  r.w_v = a.w[idx];
+  r.deg = k1 - k0;  // host guarantees 1 <= deg <= n_cols
+  r.k0 = k0;
+  load_list_chunk(a, r, 0, lane);
   return r;
 }
 
-// All of row_ptr in two registers per lane (lane l holds row_ptr[l] and row_ptr[l + 1]; at most 64
-// rows), so that a wavefront that walks several rows finds each row's bounds with two lane reads
-// instead of a load it would have to wait for behind its own earlier stores.
+// All of row_ptr in registers (lane l of pair j holds row_ptr[64 j + l] and row_ptr[64 j + l + 1]; three
+// pairs cover the 160 rows a handle may have), so that a wavefront that walks several rows finds each
+// row's bounds with two lane reads instead of a load it would have to wait for behind its own earlier
+// stores.
+constexpr int kRowPtrPairs = (kMaxRows + kWave - 1) / kWave;
 struct RowPtrs {
-  int32_t lo, hi;
+  int32_t lo[kRowPtrPairs], hi[kRowPtrPairs];
 };
 
 __device__ __forceinline__ RowPtrs load_row_ptrs(const StepArgs& a, int lane) {
-  const int r = lane < (int)a.n_rows ? lane : 0;
   RowPtrs p;
-  p.lo = a.row_ptr[r];
-  p.hi = a.row_ptr[r + 1];
+#pragma unroll
+  for (int j = 0; j < kRowPtrPairs; ++j) {
+    const int r = j * kWave + lane < (int)a.n_rows ? j * kWave + lane : 0;
+    p.lo[j] = a.row_ptr[r];
+    p.hi[j] = a.row_ptr[r + 1];
+  }
   return p;
 }
 
+// First chunk of row `row`'s list (row is wave-uniform).
 __device__ __forceinline__ RowList load_row_list(const StepArgs& a, const RowPtrs& p, int row, int lane) {
-  const int k0 = __builtin_amdgcn_readlane(p.lo, row);
-  const int k1 = __builtin_amdgcn_readlane(p.hi, row);
+  int k0 = 0, k1 = 0;
+#pragma unroll
+  for (int j = 0; j < kRowPtrPairs; ++j)
+    if (row >= j * kWave && row < (j + 1) * kWave) {  // wave-uniform: one of the pairs
+      k0 = __builtin_amdgcn_readlane(p.lo[j], row - j * kWave);
+      k1 = __builtin_amdgcn_readlane(p.hi[j], row - j * kWave);
+    }
   RowList r;
-  r.deg = k1 - k0;  // host guarantees 1 <= deg <= n_cols <= 64
-  const int idx = k0 + (lane < r.deg ? lane : 0);
-  r.col_v = a.col[idx];
-  r.w_v = a.w[idx];
+  r.deg = k1 - k0;  // host guarantees 1 <= deg <= n_cols
+  r.k0 = k0;
+  load_list_chunk(a, r, 0, lane);
   return r;
 }
 
+// Entry k (0 <= k < 64) of the chunk the list currently holds.
 __device__ __forceinline__ int list_col(const RowList& r, int k) {
   return __builtin_amdgcn_readlane(r.col_v, k);
 }
@@ -344,15 +394,15 @@ __device__ __forceinline__ void load_row_inputs(const StepArgs& a, int i, const 
     for (int u = 0; u < UT; ++u) load_vals<GT, VEC, kHalfWave, MASKED, NT>(gp, e[u], lo, hi, g[u]);
   }
   if constexpr (Needs<PHASE>::moments_in) {
-    const float* mp = a.m_hat[i];
-    const float* vp = a.v_hat[i];
+    const float* mp = m_hat_of(a, i);
+    const float* vp = v_hat_of(a, i);
 #pragma unroll
     for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, kHalfWave, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
     for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, kHalfWave, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
   if constexpr (Needs<PHASE>::acc_in) {
-    const float* bp = a.acc[i];
+    const float* bp = acc_of(a, i);
 #pragma unroll
     for (int u = 0; u < UT; ++u) load_vals<TF32, VEC, kHalfWave, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
@@ -360,7 +410,7 @@ __device__ __forceinline__ void load_row_inputs(const StepArgs& a, int i, const 
 
 // Mixing from LDS, the update of Algorithm 3 and the stores of one row of a tile.
 template <typename XT, int PHASE, int VEC, int UT, bool MASKED, bool NT>
-__device__ __forceinline__ void finish_row(const StepArgs& a, const u4* lds, int i, const RowList& rl,
+__device__ __forceinline__ void finish_row(const StepArgs& a, const u4* lds, int i, RowList rl,
                                            const uint64_t (&e)[UT], uint64_t lo, uint64_t hi, float wd, int lane,
                                            float (&g)[UT][VEC], float (&mh)[UT][VEC], float (&vh)[UT][VEC],
                                            float (&b)[UT][VEC]) {
@@ -378,9 +428,13 @@ __device__ __forceinline__ void finish_row(const StepArgs& a, const u4* lds, int
       for (int j = 0; j < VEC; ++j) mix[u][j] = w0 * xs[j];
     }
   }
-  for (int k = 1; k < rl.deg; ++k) {
-    const int c = list_col(rl, k);
-    const float wk = list_w(rl, k);
+  for (int k = 1, first = 0; k < rl.deg; ++k) {
+    if (k - first == kWave) {  // a row of more than 64 entries: the next 64 of them
+      first = k;
+      load_list_chunk(a, rl, first, lane);
+    }
+    const int c = list_col(rl, k - first);
+    const float wk = list_w(rl, k - first);
 #pragma unroll
     for (int u = 0; u < UT; ++u) {
       float xs[VEC];
@@ -413,17 +467,17 @@ __device__ __forceinline__ void finish_row(const StepArgs& a, const u4* lds, int
     for (int j = 0; j < VEC; ++j)
       xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j], decay[u][j]);
 
-  void* xd = a.x_dst[i];
+  void* xd = dst_of(a, i);
 #pragma unroll
   for (int u = 0; u < UT; ++u) store_vals<XT, VEC, kHalfWave, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
   if constexpr (Needs<PHASE>::acc_out) {
-    float* bp = a.acc[i];
+    float* bp = acc_of(a, i);
 #pragma unroll
     for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, kHalfWave, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   if constexpr (Needs<PHASE>::moments_out) {
-    float* mp = a.m_hat[i];
-    float* vp = a.v_hat[i];
+    float* mp = m_hat_of(a, i);
+    float* vp = v_hat_of(a, i);
 #pragma unroll
     for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, kHalfWave, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
@@ -455,7 +509,7 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
       for (int k = 0; k < KB; ++k) {
         const int c = c0 + k * W;
         if (c < n_cols) {
-          const void* src = a.x_src[c];
+          const void* src = src_of(a, c);
 #pragma unroll
           for (int u = 0; u < UT; ++u) r[k][u] = load_raw<XT, kHalfWave, MASKED, NT>(src, e[u], lo, hi);
         }
@@ -471,7 +525,7 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
     }
   } else {
     for (int c = wave; c < n_cols; c += W) {
-      const void* src = a.x_src[c];
+      const void* src = src_of(a, c);
       u4 r[UT];
 #pragma unroll
       for (int u = 0; u < UT; ++u) r[u] = load_raw<XT, kHalfWave, MASKED, NT>(src, e[u], lo, hi);
@@ -572,7 +626,7 @@ constexpr int kUD = 2;  // 16-byte parameter vectors per thread (1 and 4 measure
 
 // Neighbour sum with all loads of DEG sources issued before the first use.  DEG == 0: any degree.
 template <typename XT, int DEG, bool MASKED, bool NT>
-__device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
+__device__ __forceinline__ void mix_direct(const StepArgs& a, RowList rl, int lane,
                                            const uint64_t (&e)[kUD], uint64_t lo, uint64_t hi,
                                            float (&mix)[kUD][XT::vec]) {
   constexpr int VEC = XT::vec;
@@ -581,7 +635,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
     float wk[DEG];
 #pragma unroll
     for (int k = 0; k < DEG; ++k) {
-      const void* src = a.x_src[list_col(rl, k)];
+      const void* src = src_of(a, list_col(rl, k));
       wk[k] = list_w(rl, k);
 #pragma unroll
       for (int u = 0; u < kUD; ++u) r[k][u] = load_raw<XT, kHalfGroup, MASKED, NT>(src, e[u], lo, hi);
@@ -597,7 +651,7 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
       }
   } else {
     {
-      const void* src = a.x_src[list_col(rl, 0)];
+      const void* src = src_of(a, list_col(rl, 0));
       const float w0 = list_w(rl, 0);
 #pragma unroll
       for (int u = 0; u < kUD; ++u) {
@@ -607,9 +661,13 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, const RowList& rl,
         for (int j = 0; j < VEC; ++j) mix[u][j] = w0 * xs[j];
       }
     }
-    for (int k = 1; k < rl.deg; ++k) {
-      const void* src = a.x_src[list_col(rl, k)];
-      const float wk = list_w(rl, k);
+    for (int k = 1, first = 0; k < rl.deg; ++k) {
+      if (k - first == kWave) {  // a row of more than 64 entries: the next 64 of them
+        first = k;
+        load_list_chunk(a, rl, first, lane);
+      }
+      const void* src = src_of(a, list_col(rl, k - first));
+      const float wk = list_w(rl, k - first);
 #pragma unroll
       for (int u = 0; u < kUD; ++u) {
         float xs[VEC];
@@ -642,26 +700,26 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
     for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, kHalfGroup, MASKED, NT>(gp, e[u], lo, hi, g[u]);
   }
   if constexpr (Needs<PHASE>::moments_in) {
-    const float* mp = a.m_hat[row];
-    const float* vp = a.v_hat[row];
+    const float* mp = m_hat_of(a, row);
+    const float* vp = v_hat_of(a, row);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
   if constexpr (Needs<PHASE>::acc_in) {
-    const float* bp = a.acc[row];
+    const float* bp = acc_of(a, row);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   float mix[kUD][VEC];
   switch (rl.deg) {
-    case 1: mix_direct<XT, 1, MASKED, NT>(a, rl, e, lo, hi, mix); break;
-    case 2: mix_direct<XT, 2, MASKED, NT>(a, rl, e, lo, hi, mix); break;
-    case 3: mix_direct<XT, 3, MASKED, NT>(a, rl, e, lo, hi, mix); break;
-    case 4: mix_direct<XT, 4, MASKED, NT>(a, rl, e, lo, hi, mix); break;
-    case 5: mix_direct<XT, 5, MASKED, NT>(a, rl, e, lo, hi, mix); break;
-    default: mix_direct<XT, 0, MASKED, NT>(a, rl, e, lo, hi, mix); break;
+    case 1: mix_direct<XT, 1, MASKED, NT>(a, rl, lane, e, lo, hi, mix); break;
+    case 2: mix_direct<XT, 2, MASKED, NT>(a, rl, lane, e, lo, hi, mix); break;
+    case 3: mix_direct<XT, 3, MASKED, NT>(a, rl, lane, e, lo, hi, mix); break;
+    case 4: mix_direct<XT, 4, MASKED, NT>(a, rl, lane, e, lo, hi, mix); break;
+    case 5: mix_direct<XT, 5, MASKED, NT>(a, rl, lane, e, lo, hi, mix); break;
+    default: mix_direct<XT, 0, MASKED, NT>(a, rl, lane, e, lo, hi, mix); break;
   }
   // decoupled weight decay acts on the row's own previous parameters: source buffer `row` (the
   // load repeats one the mixing sum has just made, so it is served by the cache)
@@ -671,7 +729,7 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
 #pragma unroll
     for (int j = 0; j < VEC; ++j) decay[u][j] = 0.0f;
   if (!Needs<PHASE>::mixing_only && wd != 0.0f) {
-    const void* own = a.x_src[row];
+    const void* own = src_of(a, row);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) {
       float xs[VEC];
@@ -686,17 +744,17 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
 #pragma unroll
     for (int j = 0; j < VEC; ++j)
       xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j], decay[u][j]);
-  void* xd = a.x_dst[row];
+  void* xd = dst_of(a, row);
 #pragma unroll
   for (int u = 0; u < kUD; ++u) store_vals<XT, VEC, kHalfGroup, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
   if constexpr (Needs<PHASE>::acc_out) {
-    float* bp = a.acc[row];
+    float* bp = acc_of(a, row);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, kHalfGroup, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   if constexpr (Needs<PHASE>::moments_out) {
-    float* mp = a.m_hat[row];
-    float* vp = a.v_hat[row];
+    float* mp = m_hat_of(a, row);
+    float* vp = v_hat_of(a, row);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, kHalfGroup, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
@@ -751,15 +809,15 @@ __device__ __forceinline__ void acc_body(const StepArgs& a, int row, uint64_t tb
 #pragma unroll
   for (int u = 0; u < kUD; ++u) load_vals<GT, VEC, kHalfGroup, MASKED, NT>(gp, e[u], lo, hi, g[u]);
   if constexpr (Needs<PHASE>::moments_out) {
-    const float* mp = a.m_hat[row];
-    const float* vp = a.v_hat[row];
+    const float* mp = m_hat_of(a, row);
+    const float* vp = v_hat_of(a, row);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
   }
   if constexpr (Needs<PHASE>::acc_in) {
-    const float* bp = a.acc[row];
+    const float* bp = acc_of(a, row);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) load_vals<TF32, VEC, kHalfGroup, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
@@ -768,13 +826,13 @@ __device__ __forceinline__ void acc_body(const StepArgs& a, int row, uint64_t tb
 #pragma unroll
     for (int j = 0; j < VEC; ++j) acc_step<PHASE>(a.s, g[u][j], mh[u][j], vh[u][j], b[u][j]);
   if constexpr (Needs<PHASE>::acc_out) {
-    float* bp = a.acc[row];
+    float* bp = acc_of(a, row);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, kHalfGroup, MASKED, NT>(bp, e[u], lo, hi, b[u]);
   }
   if constexpr (Needs<PHASE>::moments_out) {
-    float* mp = a.m_hat[row];
-    float* vp = a.v_hat[row];
+    float* mp = m_hat_of(a, row);
+    float* vp = v_hat_of(a, row);
 #pragma unroll
     for (int u = 0; u < kUD; ++u) store_vals<TF32, VEC, kHalfGroup, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
 #pragma unroll

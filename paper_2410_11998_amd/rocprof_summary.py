@@ -2,7 +2,8 @@
 
     python -m paper_2410_11998_amd.rocprof_summary fused --kt DIR --fetch DIR --write DIR --out profiles/NAME.txt
                                                           [--traffic profiles/hbm_traffic.txt]
-    python -m paper_2410_11998_amd.rocprof_summary counters --run LABEL=DIR [--run LABEL=DIR ...] --out profiles/NAME.txt
+    python -m paper_2410_11998_amd.rocprof_summary counters --run LABEL=DIR[,DIR...] [--run ...] --out profiles/NAME.txt
+    python -m paper_2410_11998_amd.rocprof_summary trace --run DIR [--run DIR ...] --out profiles/NAME.txt
 
 Every DIR is the -d directory of ONE rocprofv3 run whose program was `python3 bench.py ...`, with the
 program's output saved as DIR/bench.out (its JSON line is read from there):
@@ -10,7 +11,10 @@ program's output saved as DIR/bench.out (its JSON line is read from there):
 * --kt     rocprofv3 --kernel-trace --stats --output-format csv        (kernel durations)
 * --fetch  rocprofv3 --pmc FETCH_SIZE --output-format csv, bench.py --copy-calibration
 * --write  rocprofv3 --pmc WRITE_SIZE --output-format csv, bench.py --copy-calibration
-* --run    rocprofv3 --pmc <any counters> --output-format csv          (averaged per kernel)
+* --run    counters: rocprofv3 --pmc <any counters> --output-format csv (averaged per kernel; the hardware
+           holds few counters at a time, so a label may take several runs of the same command);
+           trace: rocprofv3 --kernel-trace --stats --output-format csv   (one section per run: the bench
+           line's figures and the durations of the library's kernels)
 
 The byte counters are scaled by what they read for the plain 1 GiB device copies bench.py
 --copy-calibration runs last (the last four copy kernels of the run).  `fused` also rewrites the lines of
@@ -164,23 +168,65 @@ def cmd_counters(a) -> int:
     table = collections.defaultdict(dict)      # (kernel, phase, counter) -> {label: value}
     labels = []
     for spec in a.run:
-        label, directory = spec.split("=", 1)
+        label, directories = spec.split("=", 1)
         labels.append(label)
-        vals = counter_values(directory)
-        names = sorted({c for v in vals.values() for c in v})
-        j = bench_line(directory)
-        lines.append(f"  {label}: rocprofv3 --pmc {' '.join(names)} --output-format csv -d OUT -- {bench_command(directory)}")
-        lines.append(f"      {j['config']['workload']}, {j['config']['hbm_layout']}: {j['ms_per_step']:.3f} ms per step, "
-                     f"roofline fraction {j['roofline']['frac']:.3f}")
-        for (shape, phase), cs in vals.items():
-            if shape == "copy":
-                continue
-            for c, v in cs.items():
-                table[(shape, phase, c)][label] = mean(v)
+        for directory in directories.split(","):
+            vals = counter_values(directory)
+            names = sorted({c for v in vals.values() for c in v})
+            j = bench_line(directory)
+            lines.append(f"  {label}: rocprofv3 --pmc {' '.join(names)} --output-format csv -d OUT -- {bench_command(directory)}")
+            lines.append(f"      {j['config']['workload']}, {j['config']['hbm_layout']}: {j['ms_per_step']:.3f} ms per step, "
+                         f"roofline fraction {j['roofline']['frac']:.3f}")
+            for (shape, phase), cs in vals.items():
+                if shape == "copy":
+                    continue
+                for c, v in cs.items():
+                    table[(shape, phase, c)][label] = mean(v)
     lines += ["", f"  {'kernel':30s} {'phase':10s} {'counter':44s} " + " ".join(f"{l:>14s}" for l in labels)]
     for (shape, phase, c) in sorted(table):
         row = table[(shape, phase, c)]
         lines.append(f"  {shape:30s} {phase:10s} {c:44s} " + " ".join(f"{row[l]:14.5g}" if l in row else f"{'-':>14s}" for l in labels))
+    derived = [("mean read latency at the L2-to-memory interface, L2 cycles", "TCC_EA0_RDREQ_LEVEL_sum", "TCC_EA0_RDREQ_sum"),
+               ("mean write latency at the L2-to-memory interface, L2 cycles", "TCC_EA0_WRREQ_LEVEL_sum", "TCC_EA0_WRREQ_sum"),
+               ("reads in flight per L2 channel (level / channel-cycles)", "TCC_EA0_RDREQ_LEVEL_sum", "TCC_CYCLE_sum"),
+               ("read credit stalls, share of L2 channel-cycles", "TCC_EA0_RDREQ_DRAM_CREDIT_STALL_sum", "TCC_CYCLE_sum"),
+               ("write credit stalls, share of L2 channel-cycles", "TCC_EA0_WRREQ_DRAM_CREDIT_STALL_sum", "TCC_CYCLE_sum"),
+               ("L2 tag stalls, share of L2 channel-cycles", "TCC_TAG_STALL_sum", "TCC_CYCLE_sum"),
+               ("mean read latency seen from the L1, cycles", "TCP_TCC_READ_REQ_LATENCY_sum", "TCP_TCC_READ_REQ_sum"),
+               ("mean write latency seen from the L1, cycles", "TCP_TCC_WRITE_REQ_LATENCY_sum", "TCP_TCC_WRITE_REQ_sum"),
+               ("L1 address-translation miss rate", "TCP_UTCL1_TRANSLATION_MISS_sum", "TCP_UTCL1_REQUEST_sum"),
+               ("wavefront cycles waiting on any instruction, share", "SQ_WAIT_INST_ANY", "SQ_WAVE_CYCLES")]
+    keys = sorted({(shape, phase) for (shape, phase, _c) in table})
+    lines += ["", "Derived (ratio of two counters above):",
+              f"  {'kernel':30s} {'phase':10s} {'quantity':62s} " + " ".join(f"{l:>14s}" for l in labels)]
+    for shape, phase in keys:
+        for text, num, den in derived:
+            n_, d_ = table.get((shape, phase, num)), table.get((shape, phase, den))
+            if n_ and d_:
+                lines.append(f"  {shape:30s} {phase:10s} {text:62s} " +
+                             " ".join(f"{n_[l] / d_[l]:14.5g}" if l in n_ and l in d_ and d_[l] else f"{'-':>14s}" for l in labels))
+    with open(a.out, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print("\n".join(lines))
+    return 0
+
+
+def cmd_trace(a) -> int:
+    lines = ["rocprofv3 kernel-trace summary of further bench.py runs (other entry points and call sequences), one MI355X", "",
+             "Each section: rocprofv3 --kernel-trace --stats --output-format csv -d OUT -- <command> (from /tmp with TMPDIR=/tmp;",
+             "written by python -m paper_2410_11998_amd.rocprof_summary trace).  Calls include warm-up steps and every timed region.",
+             "Kernel shape = <param type, grad type, [waves, vectors per lane,] non-temporal>."]
+    for directory in a.run:
+        j = bench_line(directory)
+        ro, c = j["roofline"], j["config"]
+        lines += ["", f"{bench_command(directory)}",
+                  f"  {c['workload']}, path {c['path']}, {c['launches_per_step']} launch(es) per step"
+                  + (f" on {c['bucket_streams']} stream(s)" if c.get("bucket_streams") else "")
+                  + f": {j['ms_per_step']:.3f} ms per step, {j['value']:.4g} replica-params/s, "
+                  f"{ro['achieved']:.0f} GB/s = {ro['frac']:.3f} of peak on the bytes this path moves; host {j.get('host_us_per_call') or 0:.1f} us per call",
+                  f"  {'kernel':34s} {'phase':13s} {'calls':>6s} {'avg ms':>9s} {'min ms':>9s} {'max ms':>9s}"]
+        for shape, phase, calls, avg, lo, hi in kernel_stats(directory):
+            lines.append(f"  {shape:34s} {phase:13s} {calls:6d} {avg:9.3f} {lo:9.3f} {hi:9.3f}")
     with open(a.out, "w") as f:
         f.write("\n".join(lines) + "\n")
     print("\n".join(lines))
@@ -197,8 +243,11 @@ def main() -> int:
     c = sub.add_parser("counters")
     c.add_argument("--run", action="append", required=True, metavar="LABEL=DIR")
     c.add_argument("--out", required=True)
+    t = sub.add_parser("trace")
+    t.add_argument("--run", action="append", required=True, metavar="DIR")
+    t.add_argument("--out", required=True)
     a = ap.parse_args()
-    return cmd_fused(a) if a.cmd == "fused" else cmd_counters(a)
+    return {"fused": cmd_fused, "counters": cmd_counters, "trace": cmd_trace}[a.cmd](a)
 
 
 if __name__ == "__main__":

@@ -25,7 +25,7 @@ int main() {
   std::mt19937_64 rng(1);
   int n_ok = 0, n_err = 0;
   for (int iter = 0; iter < 3000; ++iter) {
-    uint32_t R = 1 + rng() % 64, C = 1 + rng() % 64;
+    uint32_t R = 1 + rng() % (iter % 4 == 0 ? DADAM_MAX_ROWS : 64), C = 1 + rng() % (iter % 4 == 0 ? DADAM_MAX_ROWS : 64);
     uint32_t nt = 1 + rng() % 40;
     std::vector<dadam_tensor_desc> ts(nt);
     uint64_t cur = 0;

@@ -971,3 +971,84 @@ def test_64_sources_with_and_without_room_for_the_tile(lds_limit, dtype):
     w = H.run_parity(f"onepeer64-lds{lds_limit}-{dtype}", n, n, layout, H.HyperF32(s=2), csrs, lambda t: (t - 1) % 3, 3, seed=130,
                      param_dtype=dtype, grad_dtype=dtype, flags=B.DADAM_FUSE_ACCUM, pad_fill=None, lds_limit_bytes=lds_limit)
     say("worst error / tolerance:", w)
+
+
+# ---------------------------------------------------------------------------------------------
+# more than 64 rows / sources: pointer tables in device memory, neighbour lists longer than a wavefront
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("case", ["aer96-tile", "aer96-direct", "complete96-tile", "complete96-direct", "ring160-tile-bf16",
+                                  "share-1x100-direct", "rect-70x130-tile"])
+def test_more_than_64_rows_or_sources(case):
+    """Beyond 64 rows or sources the tables of the bound buffers live in device memory (one immutable copy
+    per binding) and a row may list more neighbours than a wavefront has lanes.  An Alternating
+    Exponential Ring over 4 nodes of 24 (loops of 24 and 48), the complete graph of 96 (rows of 96 entries),
+    a ring of 160 in tile mode (160 KB of LDS, all the device has), one row with 99 receive buffers, and a
+    70 x 130 rectangular case with random rows, all against the oracle, ping-pong with dadam_swap_x."""
+    say("case", case)
+    layout = WL.pack([("a", (3001,)), ("b", (7,)), ("c", (515,))])
+    rng = np.random.default_rng(77)
+    dtype, mode, inplace, refresh = "f32", "tile" if "tile" in case else "direct", False, False
+    slot_of_t = lambda t: 0
+    if case.startswith("aer96"):
+        R = C = 96
+        csrs = [WL.aer(24, ph) for ph in range(4)]
+        slot_of_t = lambda t: (t - 1) % 4
+    elif case.startswith("complete96"):
+        R = C = 96
+        csrs = [WL.complete(96)]
+    elif case.startswith("ring160"):
+        R = C = 160
+        csrs, dtype = [WL.ring(160)], "bf16"
+    elif case.startswith("share"):
+        R, C = 1, 100
+        csrs, inplace, refresh = [WL._uniform_rows([list(range(100))])], True, True
+    else:
+        R, C = 70, 130
+        row_ptr, col, w = [0], [], []
+        for i in range(R):
+            deg = int(rng.integers(1, 100))
+            cols = rng.permutation(C)[:deg]
+            ww = (rng.random(deg) + 0.05).astype(np.float32)
+            ww = (ww / ww.sum(dtype=np.float32)).astype(np.float32)
+            col += list(cols); w += list(ww); row_ptr.append(len(col))
+        csrs, refresh = [(np.array(row_ptr, np.int32), np.array(col, np.int32), np.array(w, np.float32))], True
+    T = 5 if len(csrs) > 1 else 3
+    w_ = H.run_parity(case, R, C, layout, H.HyperF32(lr=2e-3, s=2), csrs, slot_of_t, T, seed=140, param_dtype=dtype,
+                      grad_dtype=dtype, grad_std=1e-2, flags=B.DADAM_FUSE_ACCUM | MODES[mode], inplace=inplace,
+                      refresh_extra_sources=refresh, pad_fill=None)
+    say("worst error / tolerance:", w_)
+
+
+def test_bindings_of_a_large_handle_are_kept_while_work_is_in_flight():
+    """A handle with more than 64 rows keeps the device copies of its last DADAM_BINDINGS_KEPT bindings: a step
+    launched under one binding is not disturbed by rebinding other buffers right behind it, the consensus
+    by-product and the mixing-only pass work with the device tables, and selection stays bit-exact."""
+    n = 80
+    layout = flat_layout(2500)
+    d = layout.d
+    perm = list(np.random.default_rng(5).permutation(n))
+    sim = H.GpuSim(n, n, layout, H.HyperF32(s=1), [WL.permutation(perm), WL.ring(n)], pad_fill=None)
+    other = [torch.full((d,), -7.0, device=DEV) for _ in range(n)]
+    for c in range(n):
+        sim.x_src[c].copy_(torch.arange(d, dtype=torch.float32, device=DEV) + 4096.0 * c)
+    keep_dst = list(sim.x_dst)
+    sim.mix(0)                                   # launched under the first binding
+    for k in range(3):                           # three further bindings right behind it, outputs elsewhere
+        B.dadam_bind(sim.h, sim.x_src, other, sim.m, sim.v, None)
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert torch.equal(keep_dst[i][:2500].view(torch.int32), sim.x_src[perm[i]][:2500].view(torch.int32))
+        assert bool(torch.all(other[i] == -7.0)), "a later binding's buffers were written by the earlier launch"
+    sim.mix(0)                                   # now under the last binding
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert torch.equal(other[i][:2500].view(torch.int32), sim.x_src[perm[i]][:2500].view(torch.int32))
+    # consensus error through the device tables
+    out = torch.zeros(1, dtype=torch.float64, device=DEV)
+    B.dadam_bind(sim.h, sim.x_src, keep_dst, sim.m, sim.v, None)
+    sim.mix_consensus(out, 1)
+    torch.cuda.synchronize()
+    want = O.consensus_error([x[:2500] for x in sim._get(sim.x_src, None)])
+    assert abs(float(out.item()) - want) <= 2e-5 * want
+    sim.close()

@@ -57,7 +57,7 @@ def test_init_rejects_bad_configurations():
     L = WL.pack([("a", (100,)), ("b", (50,))])
     ok = dict(n_rows=2, n_cols=2, d=L.d, offsets=L.offsets, numels=L.numels, device=B.DADAM_DEVICE_NONE)
     B.dadam_destroy(B.dadam_init(**ok))
-    for bad in (dict(n_rows=0), dict(n_rows=65), dict(n_cols=0), dict(n_cols=65), dict(d=0), dict(accum_s=0),
+    for bad in (dict(n_rows=0), dict(n_rows=161), dict(n_cols=0), dict(n_cols=161), dict(d=0), dict(accum_s=0),
                 dict(param_dtype=2), dict(grad_dtype=7), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=-1.0),
                 dict(lr=float("inf")), dict(abi_version=99), dict(beta_vhat=1.5), dict(device=-3),
                 dict(offsets=[0, 50]), dict(offsets=[104, 0]), dict(d=120), dict(offsets=[], numels=[]),
