@@ -265,25 +265,25 @@ int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_byte
  * the same bytes sustains 0.62-0.66 of peak bandwidth when the buffers it streams together all lie
  * inside one third (96 GiB) of the device's physical memory - which is where a fresh process's
  * allocations land - and 0.78-0.79 when every group of buffers that is streamed together lies half
- * in one third and half in another.  The library cannot see physical addresses; what it can use is
- * that a process's allocations fill the device memory from the bottom, so that a byte at offset o of
- * an allocation made when arena_base_bytes of device memory were already in use (device total minus
- * free, read just before allocating) sits near physical position arena_base_bytes + o.  The caller
- * makes ONE allocation of arena_bytes that reaches across the boundary between the first two thirds
- * (e.g. nearly all free memory); this helper deals the buffers alternately over two regions, one ending
- * 2 GiB below and one starting 2 GiB above that boundary: buffers 0, 2, 4, ... below, 1, 3, 5, ...
- * above, spread over each region (64 GiB wide where the arena allows, never narrower than the buffers
- * of that side need) and staggered inside their gaps by a fixed pseudo-random number of 2 MiB steps, so
- * that the bases do not form an arithmetic progression (for some distances between bases that costs
- * 3-4 %).  Any run of consecutive buffers - all sources, all outputs, one kind of state - is then split
- * evenly.  nbytes[n] in, offsets[n] out (host), offsets relative to the arena, every one a multiple of
- * 2 MiB.  regions_out (may be null) receives lo0, hi0, lo1, hi1 of the two regions as arena offsets, or
- * 0, arena_bytes, 0, 0 for the fall-back.  *advice_out (may be null) says what was done:
- *   DADAM_PLACE_TWO_REGIONS     the rule above was applied; it is as good as arena_base_bytes is;
- *   DADAM_PLACE_ARENA_ELSEWHERE the arena does not reach across the boundary with room for each side's
- *                               buffers: offsets in it say nothing useful about physical positions, and
- *                               the buffers are placed at equal distances over the whole arena instead
- *                               (expect the lower level if the arena lies inside one third);
+ * in one third and half in another.  Nobody outside the driver sees physical addresses, and where the
+ * driver puts one allocation relative to another is not predictable (measured: an arena pushed into
+ * place by an allocation made before it, or placed by the amount of memory in use, lands elsewhere and
+ * runs at 0.64-0.72).  What does hold is that ONE allocation of nearly the whole device (within 16 GiB of
+ * device_total_bytes) covers the physical memory in order, so that offsets inside it are physical
+ * positions to within what it leaves out.  For such an arena this helper deals the buffers alternately
+ * over two regions, one ending 2 GiB below and one starting 2 GiB above the boundary between the first
+ * two thirds: buffers 0, 2, 4, ... below, 1, 3, 5, ... above, spread over each region (64 GiB wide, wider
+ * when the buffers need it) and staggered inside their gaps by a fixed pseudo-random number of 2 MiB
+ * steps, so that the bases do not form an arithmetic progression (for some distances between bases that
+ * costs 3-4 %).  Any run of consecutive buffers - all sources, all outputs, one kind of state - is then
+ * split evenly.  nbytes[n] in, offsets[n] out (host), every offset a multiple of 2 MiB.  regions_out (may
+ * be null) receives lo0, hi0, lo1, hi1 of the two regions, or 0, arena_bytes, 0, 0 for the fall-back.
+ * *advice_out (may be null) says what was done:
+ *   DADAM_PLACE_TWO_REGIONS     the rule above was applied;
+ *   DADAM_PLACE_ARENA_ELSEWHERE the arena does not cover the device: offsets in it say nothing about
+ *                               physical positions, and the buffers are placed at equal distances over
+ *                               the whole arena instead (0.70-0.77 measured for arenas of 230-275 GiB,
+ *                               the packed level if the arena happens to lie inside one third);
  *   DADAM_PLACE_TOO_LARGE       half of the buffers do not fit below the boundary or the other half
  *                               between it and the next one: equal distances over the whole arena.
  * The caller hands `arena + offsets[k]` to dadam_bind and may use the space between the buffers for
@@ -292,9 +292,8 @@ int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_byte
 #define DADAM_PLACE_TWO_REGIONS 1u
 #define DADAM_PLACE_ARENA_ELSEWHERE 2u
 #define DADAM_PLACE_TOO_LARGE 4u
-int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t arena_base_bytes,
-                        uint64_t device_total_bytes, uint64_t* offsets, uint64_t* regions_out,
-                        uint32_t* advice_out);
+int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t device_total_bytes,
+                        uint64_t* offsets, uint64_t* regions_out, uint32_t* advice_out);
 
 /* Text of the last error recorded on this handle ("" if none).  With h == NULL: the text of the
  * last dadam_init failure of the calling thread.  The pointer stays valid until the next call on

@@ -4,25 +4,17 @@ On MI355X a streaming step that touches many arrays at once sustains about 0.65 
 bandwidth when those arrays all lie inside one third (96 GiB) of the device's physical memory -
 where a fresh process's consecutive allocations land - and 0.78-0.79 when half of them lie in one
 third and half in another (measured; which arrays does not matter as long as every group that is
-streamed together is split).  Nobody outside the driver sees physical addresses; what can be used
-is that allocations fill the device memory from the bottom, so a byte at offset o of an allocation
-made when B bytes were in use sits near physical position B + o.  ``SpreadArena`` makes ONE
-allocation that reaches across the boundary between the first two thirds and carves the buffers
-out of two regions either side of it by the library's advice (``dadam_place_offsets``): buffers
-0, 2, 4, ... below, 1, 3, 5, ... above, so that any run of consecutive buffers - all sources, all
-outputs, one kind of state - is split evenly.
+streamed together is split).  Nobody outside the driver sees physical addresses, and where the
+driver puts one allocation relative to another is not predictable; what holds is that ONE
+allocation of nearly the whole device covers the physical memory in order.  ``SpreadArena`` makes
+that allocation (free memory minus ``keep_free_bytes``) and carves the buffers out of two regions
+either side of the boundary between the first two thirds by the library's advice
+(``dadam_place_offsets``): buffers 0, 2, 4, ... below, 1, 3, 5, ... above, so that any run of
+consecutive buffers - all sources, all outputs, one kind of state - is split evenly.  The space
+between the buffers stays untouched and can be handed out as views for anything else.
 
-Two ways to make that allocation:
-
-* ``compact=False`` (default): nearly all free memory.  The space between the buffers stays
-  untouched and can be handed out as views for anything else.
-* ``compact=True``: only the stretch the two regions need (1.2 x the buffers plus 4 GiB).  If less
-  memory is in use than where that stretch begins, a throw-away allocation ("ballast") is made
-  first to push the arena up to it and is released afterwards, so everything outside the arena is
-  free again for the rest of the job.
-
-When the arena cannot reach across the boundary (too much memory already in use, or the buffers
-too large) the buffers are spread evenly over whatever arena there is, and ``advice`` says so.
+When the arena cannot cover the device (memory already in use, or a span given by the caller) the
+buffers are spread at equal distances over whatever arena there is, and ``advice`` says so.
 Memory management only - nothing of the method is computed here.
 """
 
@@ -42,38 +34,18 @@ def _round_up(n: int, unit: int = UNIT) -> int:
     return -(-int(n) // unit) * unit
 
 
-def compact_extent(nbytes: Sequence[int], total: int):
-    """Physical stretch [lo, hi) a compact arena should cover: 1.2 x the even-numbered buffers below
-    the boundary between the first two thirds of ``total`` bytes (minus a 2 GiB margin), 1.2 x the odd-numbered
-    ones above it (plus the margin)."""
-    third = (total + 3 * GIB // 2) // (3 * GIB) * GIB
-    need = [sum(_round_up(n) for n in nbytes[r::2]) for r in (0, 1)]
-    room = [_round_up(n + n // 5) for n in need]
-    return third - 2 * GIB - room[0], third + 2 * GIB + room[1]
-
-
 class SpreadArena:
     def __init__(self, nbytes: Sequence[int], device, span_bytes: Optional[int] = None, keep_free_bytes: int = 12 << 30,
-                 two_regions: bool = True, compact: bool = False, offsets: Optional[Sequence[int]] = None):
+                 two_regions: bool = True, offsets: Optional[Sequence[int]] = None):
         """nbytes: sizes of the buffers, in the order they are laid out.  span_bytes: size of the
-        arena; default is the free device memory minus ``keep_free_bytes`` (compact: the stretch the
-        two regions need), never less than the packed size.  two_regions=False: equal distances over
-        the whole arena.  offsets: an explicit placement (one offset per buffer, multiples of 2 MiB)."""
+        arena; default is the free device memory minus ``keep_free_bytes``, never less than the packed
+        size.  two_regions=False: equal distances over the whole arena.  offsets: an explicit
+        placement (one offset per buffer, multiples of 2 MiB)."""
         self.device = torch.device(device)
         self.nbytes = [int(n) for n in nbytes]
         packed = sum(_round_up(n) for n in self.nbytes)
         free, total = torch.cuda.mem_get_info(self.device)
-        self.base_bytes = total - free          # device memory in use before the arena: where it will start
-        ballast = None
-        if compact and span_bytes is None and offsets is None:
-            lo, hi = compact_extent(self.nbytes, total)
-            if lo > self.base_bytes + UNIT:
-                try:
-                    ballast = torch.empty(lo - self.base_bytes, dtype=torch.uint8, device=self.device)
-                    self.base_bytes = lo
-                except torch.OutOfMemoryError:
-                    ballast = None
-            span_bytes = hi - self.base_bytes if hi > self.base_bytes + packed else packed
+        self.in_use_before = total - free
         if span_bytes is None:
             span_bytes = max(packed, free - keep_free_bytes)
         span_bytes = max(int(span_bytes), packed)
@@ -86,9 +58,6 @@ class SpreadArena:
                 if span_bytes == packed:
                     raise
                 span_bytes = max(packed, span_bytes - (8 << 30))
-        if ballast is not None:
-            del ballast
-            torch.cuda.empty_cache()            # hands the ballast back to the driver; the arena stays where it is
         self.base_offset = (-self.storage.data_ptr()) % UNIT            # start on a 2 MiB boundary
         self.span_bytes = span_bytes
         self.advice = 0
@@ -96,12 +65,12 @@ class SpreadArena:
             self.policy, self.offsets = "given offsets", [int(o) for o in offsets]
             self.regions_used = [(min(self.offsets), max(o + n for o, n in zip(self.offsets, self.nbytes)))]
         elif two_regions:
-            self.offsets, self.regions_used, self.advice = B.dadam_place_offsets(self.nbytes, span_bytes, self.base_bytes, total)
+            self.offsets, self.regions_used, self.advice = B.dadam_place_offsets(self.nbytes, span_bytes, total)
             self.policy = {B.DADAM_PLACE_TWO_REGIONS: "two regions across the first boundary",
-                           B.DADAM_PLACE_ARENA_ELSEWHERE: "whole arena (it does not reach across the boundary)",
-                           B.DADAM_PLACE_TOO_LARGE: "whole arena (buffers too large for two regions)"}.get(self.advice, "whole arena")
+                           B.DADAM_PLACE_ARENA_ELSEWHERE: "equal distances (the arena does not cover the device)",
+                           B.DADAM_PLACE_TOO_LARGE: "equal distances (buffers too large for two regions)"}.get(self.advice, "equal distances")
         else:
-            self.policy, self.offsets = "whole arena", B.dadam_spread_offsets(self.nbytes, span_bytes)
+            self.policy, self.offsets = "equal distances", B.dadam_spread_offsets(self.nbytes, span_bytes)
             self.regions_used = [(0, span_bytes)]
         taken = sorted(zip(self.offsets, self.nbytes))
         for k, (o, n) in enumerate(taken):
@@ -111,9 +80,9 @@ class SpreadArena:
 
     def describe(self) -> str:
         gib = lambda v: f"{v / GIB:.1f}"
-        regs = " + ".join(f"[{gib(self.base_bytes + lo)}, {gib(self.base_bytes + hi)})" for lo, hi in self.regions_used)
-        return (f"{self.policy}: {regs} GiB (estimated physical) of a {gib(self.span_bytes)} GiB allocation made with "
-                f"{gib(self.base_bytes)} GiB in use")
+        regs = " + ".join(f"[{gib(lo)}, {gib(hi)})" for lo, hi in self.regions_used)
+        return (f"{self.policy}: {regs} GiB of a {gib(self.span_bytes)} GiB allocation made with "
+                f"{gib(self.in_use_before)} GiB in use")
 
     def view(self, k: int, dtype: torch.dtype) -> torch.Tensor:
         o = self.base_offset + self.offsets[k]

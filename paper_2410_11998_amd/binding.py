@@ -89,7 +89,7 @@ def _load() -> C.CDLL:
     lib.dadam_slot_uses_tile_mode.argtypes = [H, C.c_uint32]
     lib.dadam_pack_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
     lib.dadam_spread_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.POINTER(C.c_uint64)]
-    lib.dadam_place_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64,
+    lib.dadam_place_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64,
                                         C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
     lib.dadam_last_error.argtypes = [H]
     lib.dadam_last_error.restype = C.c_char_p
@@ -170,7 +170,7 @@ def dadam_spread_offsets(nbytes: Sequence[int], arena_bytes: int):
     return [int(x) for x in o]
 
 
-def dadam_place_offsets(nbytes: Sequence[int], arena_bytes: int, arena_base_bytes: int, device_total_bytes: int):
+def dadam_place_offsets(nbytes: Sequence[int], arena_bytes: int, device_total_bytes: int):
     """Returns (offsets, regions, advice) with regions = [(lo0, hi0), (lo1, hi1)], or [(0, arena_bytes)] for the
     fall-back, and advice the DADAM_PLACE_* flag the library reports."""
     n = len(nbytes)
@@ -178,7 +178,7 @@ def dadam_place_offsets(nbytes: Sequence[int], arena_bytes: int, arena_base_byte
     o = (C.c_uint64 * n)()
     r = (C.c_uint64 * 4)()
     adv = C.c_uint32(0)
-    rc = lib.dadam_place_offsets(a, n, int(arena_bytes), int(arena_base_bytes), int(device_total_bytes), o, r, C.byref(adv))
+    rc = lib.dadam_place_offsets(a, n, int(arena_bytes), int(device_total_bytes), o, r, C.byref(adv))
     if rc < 0:
         raise DadamError(rc, f"dadam_place_offsets: {n} buffers of {sum(int(x) for x in nbytes)} bytes do not fit in {arena_bytes}")
     regions = [(int(r[0]), int(r[1]))] + ([(int(r[2]), int(r[3]))] if r[3] else [])

@@ -859,8 +859,8 @@ int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_byte
   return DADAM_OK;
 }
 
-int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t arena_base_bytes,
-                        uint64_t device_total_bytes, uint64_t* offsets, uint64_t* regions_out, uint32_t* advice_out) {
+int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t device_total_bytes,
+                        uint64_t* offsets, uint64_t* regions_out, uint32_t* advice_out) {
   if (!nbytes || !offsets || n == 0) return DADAM_EINVAL;
   const uint64_t unit = 2ull << 20, gib = 1ull << 30;
   std::vector<uint64_t> side[2];
@@ -870,28 +870,25 @@ int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes
     side[k & 1].push_back(nbytes[k]);
     need[k & 1] += (nbytes[k] + unit - 1) / unit * unit;
   }
-  if (arena_bytes > (1ull << 50) || arena_base_bytes > (1ull << 50) || device_total_bytes > (1ull << 50)) return DADAM_EINVAL;
+  if (arena_bytes > (1ull << 50) || device_total_bytes > (1ull << 50)) return DADAM_EINVAL;
   const uint64_t third = (device_total_bytes + 3 * gib / 2) / (3 * gib) * gib;  // a third, to the nearest GiB
   const uint64_t margin = 2 * gib;
-  // Physical positions [p_lo, p_hi) the arena is taken to cover (its start rounded up to 2 MiB: offset 0
-  // of the answer is that point), and the two regions in the same terms: region 0 ends `margin` below
-  // the boundary between the first two thirds, region 1 starts `margin` above it and ends no later than
-  // `margin` below the next boundary.
-  const uint64_t p_lo = (arena_base_bytes + unit - 1) / unit * unit;
-  const uint64_t p_hi = arena_base_bytes + arena_bytes;
+  // Region 0 ends `margin` below the boundary between the first two thirds, region 1 starts `margin`
+  // above it and ends no later than `margin` below the next boundary (or where the arena ends).
+  const uint64_t top = arena_bytes < 2 * third - margin ? arena_bytes : 2 * third - margin;
   uint32_t advice = 0;
   uint64_t lo[2] = {0, 0}, width[2] = {0, 0};
   if (n < 2 || third <= 2 * margin) {
     advice = 0;  // nothing to deal over two sides
-  } else if (need[0] > third - margin || need[1] > third - 2 * margin) {
-    advice = DADAM_PLACE_TOO_LARGE;
-  } else if (p_lo + need[0] > third - margin || third + margin + need[1] > p_hi) {
+  } else if (arena_bytes + 16 * gib < device_total_bytes) {
     advice = DADAM_PLACE_ARENA_ELSEWHERE;
+  } else if (need[0] > third - margin || third + margin + need[1] > top) {
+    advice = DADAM_PLACE_TOO_LARGE;
   } else {
     for (int r = 0; r < 2; ++r) {
       uint64_t want = (need[r] + need[r] / 5 + unit - 1) / unit * unit;  // 20 % of room for the stagger
       if (want < 64 * gib) want = 64 * gib;
-      const uint64_t room = r == 0 ? third - margin - p_lo : (p_hi < 2 * third - margin ? p_hi : 2 * third - margin) - (third + margin);
+      const uint64_t room = r == 0 ? third - margin : top - (third + margin);
       width[r] = (want < room ? want : room) / unit * unit;  // >= need[r] by the tests above
       lo[r] = r == 0 ? third - margin - width[r] : third + margin;
     }
@@ -916,12 +913,11 @@ int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes
         z ^= z >> 31;
         if (slots > 1) off[j] += z % slots * unit;
       }
-      // from physical positions to offsets inside the arena
-      for (size_t j = 0; j < off.size(); ++j) offsets[2 * j + r] = lo[r] - p_lo + off[j];
+      for (size_t j = 0; j < off.size(); ++j) offsets[2 * j + r] = lo[r] + off[j];
     }
     if (regions_out) {
-      regions_out[0] = lo[0] - p_lo; regions_out[1] = lo[0] - p_lo + width[0];
-      regions_out[2] = lo[1] - p_lo; regions_out[3] = lo[1] - p_lo + width[1];
+      regions_out[0] = lo[0]; regions_out[1] = lo[0] + width[0];
+      regions_out[2] = lo[1]; regions_out[3] = lo[1] + width[1];
     }
     return DADAM_OK;
   }

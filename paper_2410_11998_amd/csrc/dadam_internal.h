@@ -89,6 +89,8 @@ struct StepArgs {
   Scalars s;
 };
 
+typedef void (*KernelFn)(const StepArgs);
+
 struct TileShape {
   int waves;  // wavefronts per workgroup (rows are dealt round-robin to them)
   int ut;     // 16-byte vectors per lane and row

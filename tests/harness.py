@@ -72,7 +72,13 @@ class GpuSim:
             from paper_2410_11998_amd.arena import SpreadArena
             sizes = [d * (2 if dt == torch.bfloat16 else 4) for dt in dts]
             keep = 48 << 30                                         # room for the gradients and temporaries of the test
-            self.arena = SpreadArena(sizes, self.dev, keep_free_bytes=keep)
+            free, total = torch.cuda.mem_get_info(self.dev)
+            # the benchmark's placement (computed for an arena over the whole device), as far as the
+            # smaller arena of the test reaches
+            placed, _regions, _advice = B.dadam_place_offsets(sizes, total, total)
+            if max(o + n for o, n in zip(placed, sizes)) > free - keep:
+                placed = None
+            self.arena = SpreadArena(sizes, self.dev, keep_free_bytes=keep, offsets=placed)
             bufs = self.arena.views(dts)
             for t in bufs:
                 t.zero_()

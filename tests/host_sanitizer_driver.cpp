@@ -92,8 +92,7 @@ int main() {
     const uint64_t arena = (rng() % 3 == 0) ? total - ((uint64_t)(rng() % 12) << 30) : (uint64_t)(1 + rng() % 300) << 30;
     uint64_t reg[4];
     uint32_t advice = 99;
-    const uint64_t base = (rng() % 2 == 0) ? 0 : (uint64_t)(rng() % 120) << 29;
-    if (dadam_place_offsets(sz.data(), n, arena, base, total, o.data(), (rng() & 1) ? reg : nullptr, (rng() & 1) ? &advice : nullptr) != DADAM_OK) { ++n_err; continue; }
+    if (dadam_place_offsets(sz.data(), n, arena, total, o.data(), (rng() & 1) ? reg : nullptr, (rng() & 1) ? &advice : nullptr) != DADAM_OK) { ++n_err; continue; }
     ++n_ok;
     if (advice != 99 && advice != 0 && advice != DADAM_PLACE_TWO_REGIONS && advice != DADAM_PLACE_ARENA_ELSEWHERE && advice != DADAM_PLACE_TOO_LARGE) { printf("unknown advice\n"); return 1; }
     std::vector<std::pair<uint64_t, uint64_t>> iv;
