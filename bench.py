@@ -192,9 +192,10 @@ def measure(args, want_cpu_sample: bool):
     esize = {torch.float32: 4, torch.bfloat16: 2}
     arena = None
     placement_advice = None
-    if args.layout in ("spread", "whole"):
+    if args.layout in ("spread", "rule", "whole"):
         from paper_2410_11998_amd.arena import SpreadArena
-        arena = SpreadArena([d * esize[dt] for _, dt in kinds], dev, two_regions=(args.layout != "whole"))
+        arena = SpreadArena([d * esize[dt] for _, dt in kinds], dev, two_regions=(args.layout != "whole"),
+                            calibrate=(args.layout == "spread"))
         bufs = arena.views([dt for _, dt in kinds])
         hbm_layout = arena.describe()
         placement_advice = {B.DADAM_PLACE_TWO_REGIONS: "two regions", B.DADAM_PLACE_ARENA_ELSEWHERE: "arena elsewhere",
@@ -512,10 +513,11 @@ def main() -> int:
                          "stand-in for that bucket's backward pass; with --bucket-streams >= 2 the updates go to side "
                          "streams and overlap the next stand-in (the value then is not the benchmark's metric)")
     ap.add_argument("--standin-only", action="store_true", help="with --standin-backward: skip the updates (the stand-in alone)")
-    ap.add_argument("--layout", choices=["spread", "whole", "packed"], default="spread",
-                    help="spread: one arena over most of the free HBM, buffers dealt alternately over two regions either "
-                         "side of the boundary between the first two thirds of the memory when the arena covers the device, "
-                         "at equal distances otherwise (see paper_2410_11998_amd/arena.py); whole: the same arena, always "
+    ap.add_argument("--layout", choices=["spread", "rule", "whole", "packed"], default="spread",
+                    help="spread: one arena over most of the free HBM, buffers dealt alternately over two stretches of it "
+                         "that a timing probe finds to lie in different thirds of the memory (see "
+                         "paper_2410_11998_amd/arena.py); rule: no probe, the two regions either side of the arena's 96 GiB "
+                         "mark when the arena covers the device, equal distances otherwise; whole: the same arena, always "
                          "equal distances; packed: one ordinary allocation per buffer")
     ap.add_argument("--prealloc-gib", type=int, default=0,
                     help="allocate that much device memory first and keep it (stands for a job's weights and activations)")

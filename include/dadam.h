@@ -295,6 +295,16 @@ int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_byte
 int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t device_total_bytes,
                         uint64_t* offsets, uint64_t* regions_out, uint32_t* advice_out);
 
+/* Layout advice for HBM, part 3: the dealing itself, for a caller that knows two
+ * regions [lo0, hi0) and [lo1, hi1) of one arena to lie in different thirds of the physical memory - e.g.
+ * because it has timed a streaming probe over pairs of chunks of its arena, which tells same third from
+ * different third reliably (paper_2410_11998_amd/arena.py does that).  dadam_deal_offsets places buffers
+ * 0, 2, 4, ... in the first region and 1, 3, 5, ... in the second, spread over each region and staggered as
+ * described under dadam_place_offsets.  Region bounds are multiples of 2 MiB and the regions do not overlap.
+ * Errors: DADAM_EINVAL (null, n == 0, bounds unaligned or overlapping, a side's buffers do not fit). */
+int dadam_deal_offsets(const uint64_t* nbytes, uint32_t n, uint64_t lo0, uint64_t hi0, uint64_t lo1, uint64_t hi1,
+                       uint64_t* offsets);
+
 /* Text of the last error recorded on this handle ("" if none).  With h == NULL: the text of the
  * last dadam_init failure of the calling thread.  The pointer stays valid until the next call on
  * the same handle (thread). */

@@ -5,22 +5,28 @@ bandwidth when those arrays all lie inside one third (96 GiB) of the device's ph
 where a fresh process's consecutive allocations land - and 0.78-0.79 when half of them lie in one
 third and half in another (measured; which arrays does not matter as long as every group that is
 streamed together is split).  Nobody outside the driver sees physical addresses, and where the
-driver puts one allocation relative to another is not predictable; what holds is that ONE
-allocation of nearly the whole device covers the physical memory in order.  ``SpreadArena`` makes
-that allocation (free memory minus ``keep_free_bytes``) and carves the buffers out of two regions
-either side of the boundary between the first two thirds by the library's advice
-(``dadam_place_offsets``): buffers 0, 2, 4, ... below, 1, 3, 5, ... above, so that any run of
-consecutive buffers - all sources, all outputs, one kind of state - is split evenly.  The space
-between the buffers stays untouched and can be handed out as views for anything else.
+driver puts an allocation is not predictable from what was allocated before.  What can be done is
+to MEASURE: a mixing pass over sixteen 64 MiB buffers runs at 0.79 of peak when half of them sit in
+one third and half in another, and at 0.65-0.73 when all sit in the same third (0.34 against
+0.37-0.41 ms, repeatable to 1 %), so timing that pass over pairs of 1 GiB chunks of an arena tells
+which chunks share a third.
 
-When the arena cannot cover the device (memory already in use, or a span given by the caller) the
-buffers are spread at equal distances over whatever arena there is, and ``advice`` says so.
+``SpreadArena`` makes ONE allocation (by default: free memory minus ``keep_free_bytes``), finds the
+thirds inside it that way (``calibrate=True``, a few hundred milliseconds, before anything is stored
+in the arena), and deals the buffers alternately over the two largest stretches that lie in
+different thirds (``dadam_deal_offsets``): buffers 0, 2, 4, ... in one, 1, 3, 5, ... in the other, so
+that any run of consecutive buffers - all sources, all outputs, one kind of state - is split
+evenly.  The space between the buffers stays untouched and can be handed out as views for
+anything else.  This works whatever was allocated before, as long as the arena reaches into two
+thirds with room for half of the buffers in each; otherwise (or with ``calibrate=False``) the
+library's rule for an arena over the whole device applies (``dadam_place_offsets``), which falls
+back to equal distances over whatever arena there is; ``advice`` / ``policy`` say what was done.
 Memory management only - nothing of the method is computed here.
 """
 
 from __future__ import annotations
 
-from typing import List, Optional, Sequence
+from typing import List, Optional, Sequence, Tuple
 
 import torch
 
@@ -28,19 +34,128 @@ from . import binding as B
 
 UNIT = 2 << 20
 GIB = 1 << 30
+HBM_PEAK = 8.0e12
+
+# the timing probe: sixteen sources and sixteen outputs of 64 MiB, half of each in one 1 GiB chunk
+PROBE_ROWS = 16
+PROBE_ELEMS = 16 << 20
+PROBE_CHUNK = 2 * (PROBE_ROWS // 2) * PROBE_ELEMS * 4          # bytes of one chunk: 8 sources + 8 outputs
+PROBE_STEP = 4 * GIB
 
 
 def _round_up(n: int, unit: int = UNIT) -> int:
     return -(-int(n) // unit) * unit
 
 
+class ThirdsProbe:
+    """Times the library's mixing pass over two 1 GiB chunks of a device allocation."""
+
+    def __init__(self, storage: torch.Tensor, base_offset: int):
+        from . import workloads as WL
+        self.storage, self.base = storage, base_offset
+        dev = storage.device
+        self.state = [torch.empty(PROBE_ELEMS, dtype=torch.float32, device=dev) for _ in range(2 * PROBE_ROWS)]
+        self.h = B.dadam_init(PROBE_ROWS, PROBE_ROWS, PROBE_ELEMS, [0], [PROBE_ELEMS], device=dev.index or 0)
+        B.dadam_set_topology(self.h, 0, *WL.ring(PROBE_ROWS))
+
+    def _view(self, off: int) -> torch.Tensor:
+        nb = PROBE_ELEMS * 4
+        return self.storage[self.base + off:self.base + off + nb].view(torch.float32)
+
+    def rate(self, off_a: int, off_b: int, reps: int = 6) -> float:
+        """Fraction of the HBM peak the pass sustains with half of its buffers at off_a and half at off_b."""
+        nb, half = PROBE_ELEMS * 4, PROBE_ROWS // 2
+        xs = [self._view(off_a + k * nb) for k in range(half)] + [self._view(off_b + k * nb) for k in range(half)]
+        xd = [self._view(off_a + (half + k) * nb) for k in range(half)] + [self._view(off_b + (half + k) * nb) for k in range(half)]
+        B.dadam_bind(self.h, xs, xd, self.state[:PROBE_ROWS], self.state[PROBE_ROWS:], None)
+        st = B.current_stream()
+        for _ in range(2):
+            B.dadam_mix(self.h, 0, 0, st)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            B.dadam_mix(self.h, 0, 0, st)
+        e1.record()
+        torch.cuda.synchronize()
+        seconds = e0.elapsed_time(e1) / reps / 1e3
+        return 2 * PROBE_ROWS * nb / seconds / HBM_PEAK
+
+    def close(self):
+        torch.cuda.synchronize()
+        B.dadam_destroy(self.h)
+        self.h, self.state = None, None
+
+
+def stretches_in_different_thirds(span_bytes: int, rate) -> List[Tuple[int, int, int]]:
+    """Stretches (third id, lo, hi) of an arena of span_bytes, found by timing: ``rate(off_a, off_b)`` is the
+    fraction of peak a streaming pass sustains over the chunks at those offsets.  Chunks every PROBE_STEP bytes
+    are compared with a reference chunk; those that run fast with it (>= 0.95 of the fastest pairing, which
+    itself must reach 0.75 of peak) lie in another third.  A second reference taken from those separates the
+    other two thirds.  Pure bookkeeping around the timings (tested on the CPU with a model of the memory)."""
+    offs = list(range(0, span_bytes - PROBE_CHUNK + 1, PROBE_STEP))
+    if len(offs) < 3:
+        return []
+
+    def same_third_as(ref_index: int) -> Optional[List[bool]]:
+        rates = [None if k == ref_index else rate(offs[ref_index], offs[k]) for k in range(len(offs))]
+        best = max(r for r in rates if r is not None)
+        if best < 0.75:                 # no pairing reaches the two-thirds level: everything shares the reference's third
+            return [True] * len(offs)
+        return [r is None or r < 0.95 * best for r in rates]
+
+    third = [-1] * len(offs)
+    with_a = same_third_as(0)
+    for k, s in enumerate(with_a):
+        if s:
+            third[k] = 0
+    rest = [k for k in range(len(offs)) if third[k] < 0]
+    if rest:
+        with_b = same_third_as(rest[0])
+        for k in rest:
+            third[k] = 1 if with_b[k] else 2
+    for k in range(1, len(offs) - 1):      # one chunk at odds with two neighbours that agree: a timing outlier
+        if third[k - 1] == third[k + 1] != third[k]:
+            third[k] = third[k - 1]
+    runs, k = [], 0
+    while k < len(offs):
+        j = k
+        while j + 1 < len(offs) and third[j + 1] == third[k]:
+            j += 1
+        # a run covers its first chunk's start to its last chunk's end: every byte in between lies in chunks that
+        # were classified alike on both sides
+        runs.append((third[k], offs[k], offs[j] + PROBE_CHUNK))
+        k = j + 1
+    return runs
+
+
+def two_regions_from_stretches(runs: Sequence[Tuple[int, int, int]], need: Sequence[int]) -> Optional[List[Tuple[int, int]]]:
+    """The two regions to deal buffers over: the two longest stretches that lie in different thirds and hold
+    need[0] / need[1] bytes, each cut down to at most max(64 GiB, 1.2 x need) on the side nearest the other."""
+    best = None
+    for a in runs:
+        for b in runs:
+            if a[0] == b[0] or a[1] >= b[1]:
+                continue
+            if a[2] - a[1] >= need[0] and b[2] - b[1] >= need[1]:
+                size = min(a[2] - a[1], 96 * GIB) + min(b[2] - b[1], 96 * GIB)
+                if best is None or size > best[0]:
+                    best = (size, a, b)
+    if best is None:
+        return None
+    _, a, b = best
+    w0 = min(a[2] - a[1], max(64 * GIB, _round_up(need[0] * 6 // 5)))
+    w1 = min(b[2] - b[1], max(64 * GIB, _round_up(need[1] * 6 // 5)))
+    return [(a[2] - w0, a[2]), (b[1], b[1] + w1)]      # a lies below b: a's top end, b's bottom end
+
+
 class SpreadArena:
     def __init__(self, nbytes: Sequence[int], device, span_bytes: Optional[int] = None, keep_free_bytes: int = 12 << 30,
-                 two_regions: bool = True, offsets: Optional[Sequence[int]] = None):
+                 two_regions: bool = True, calibrate: bool = True, offsets: Optional[Sequence[int]] = None):
         """nbytes: sizes of the buffers, in the order they are laid out.  span_bytes: size of the
         arena; default is the free device memory minus ``keep_free_bytes``, never less than the packed
-        size.  two_regions=False: equal distances over the whole arena.  offsets: an explicit
-        placement (one offset per buffer, multiples of 2 MiB)."""
+        size.  two_regions=False: equal distances over the whole arena.  calibrate=False: no timing,
+        the library's rule for a whole-device arena.  offsets: an explicit placement (one offset per
+        buffer, multiples of 2 MiB)."""
         self.device = torch.device(device)
         self.nbytes = [int(n) for n in nbytes]
         packed = sum(_round_up(n) for n in self.nbytes)
@@ -61,17 +176,35 @@ class SpreadArena:
         self.base_offset = (-self.storage.data_ptr()) % UNIT            # start on a 2 MiB boundary
         self.span_bytes = span_bytes
         self.advice = 0
+        self.stretches: List[Tuple[int, int, int]] = []
+        placed = None
         if offsets is not None:
-            self.policy, self.offsets = "given offsets", [int(o) for o in offsets]
-            self.regions_used = [(min(self.offsets), max(o + n for o, n in zip(self.offsets, self.nbytes)))]
-        elif two_regions:
-            self.offsets, self.regions_used, self.advice = B.dadam_place_offsets(self.nbytes, span_bytes, total)
-            self.policy = {B.DADAM_PLACE_TWO_REGIONS: "two regions across the first boundary",
-                           B.DADAM_PLACE_ARENA_ELSEWHERE: "equal distances (the arena does not cover the device)",
+            self.policy, placed = "given offsets", [int(o) for o in offsets]
+            self.regions_used = [(min(placed), max(o + n for o, n in zip(placed, self.nbytes)))]
+        elif two_regions and calibrate and len(self.nbytes) >= 2 and span_bytes >= 2 * PROBE_STEP + PROBE_CHUNK:
+            need = [sum(_round_up(n) for n in self.nbytes[r::2]) for r in (0, 1)]
+            try:
+                probe = ThirdsProbe(self.storage, self.base_offset)
+            except torch.OutOfMemoryError:
+                probe = None                      # no room for the probe's 2 GiB of state: fall through to the rule
+            if probe is not None:
+                try:
+                    self.stretches = stretches_in_different_thirds(span_bytes // UNIT * UNIT, probe.rate)
+                finally:
+                    probe.close()
+                regions = two_regions_from_stretches(self.stretches, need)
+                if regions is not None:
+                    placed = B.dadam_deal_offsets(self.nbytes, regions[0], regions[1])
+                    self.policy, self.regions_used, self.advice = "two regions found by timing", regions, B.DADAM_PLACE_TWO_REGIONS
+        if placed is None and two_regions:
+            placed, self.regions_used, self.advice = B.dadam_place_offsets(self.nbytes, span_bytes, total)
+            self.policy = {B.DADAM_PLACE_TWO_REGIONS: "two regions across the first boundary (whole-device rule)",
+                           B.DADAM_PLACE_ARENA_ELSEWHERE: "equal distances (no two thirds found, arena does not cover the device)",
                            B.DADAM_PLACE_TOO_LARGE: "equal distances (buffers too large for two regions)"}.get(self.advice, "equal distances")
-        else:
-            self.policy, self.offsets = "equal distances", B.dadam_spread_offsets(self.nbytes, span_bytes)
+        elif placed is None:
+            self.policy, placed = "equal distances", B.dadam_spread_offsets(self.nbytes, span_bytes)
             self.regions_used = [(0, span_bytes)]
+        self.offsets = placed
         taken = sorted(zip(self.offsets, self.nbytes))
         for k, (o, n) in enumerate(taken):
             assert o % UNIT == 0 and self.base_offset + o + n <= self.storage.numel(), (k, o, n)
@@ -81,8 +214,11 @@ class SpreadArena:
     def describe(self) -> str:
         gib = lambda v: f"{v / GIB:.1f}"
         regs = " + ".join(f"[{gib(lo)}, {gib(hi)})" for lo, hi in self.regions_used)
+        found = ""
+        if self.stretches:
+            found = "; thirds seen at " + ", ".join(f"[{gib(lo)}, {gib(hi)})" for _t, lo, hi in self.stretches)
         return (f"{self.policy}: {regs} GiB of a {gib(self.span_bytes)} GiB allocation made with "
-                f"{gib(self.in_use_before)} GiB in use")
+                f"{gib(self.in_use_before)} GiB in use{found}")
 
     def view(self, k: int, dtype: torch.dtype) -> torch.Tensor:
         o = self.base_offset + self.offsets[k]

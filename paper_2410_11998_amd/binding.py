@@ -34,7 +34,8 @@ DADAM_PLACE_TWO_REGIONS, DADAM_PLACE_ARENA_ELSEWHERE, DADAM_PLACE_TOO_LARGE = 1,
 EXPORTS = [
     "dadam_init", "dadam_set_topology", "dadam_bind", "dadam_swap_x", "dadam_gossip_step",
     "dadam_gossip_step_range", "dadam_accumulate", "dadam_mix", "dadam_mix_consensus", "dadam_mix_consensus_static", "dadam_set_lr", "dadam_get_plan_info",
-    "dadam_slot_uses_tile_mode", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_place_offsets", "dadam_last_error",
+    "dadam_slot_uses_tile_mode", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_place_offsets", "dadam_deal_offsets",
+    "dadam_last_error",
     "dadam_destroy",
 ]
 
@@ -91,6 +92,8 @@ def _load() -> C.CDLL:
     lib.dadam_spread_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.POINTER(C.c_uint64)]
     lib.dadam_place_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64,
                                         C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
+    lib.dadam_deal_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64,
+                                       C.POINTER(C.c_uint64)]
     lib.dadam_last_error.argtypes = [H]
     lib.dadam_last_error.restype = C.c_char_p
     lib.dadam_destroy.argtypes = [H]
@@ -183,6 +186,17 @@ def dadam_place_offsets(nbytes: Sequence[int], arena_bytes: int, device_total_by
         raise DadamError(rc, f"dadam_place_offsets: {n} buffers of {sum(int(x) for x in nbytes)} bytes do not fit in {arena_bytes}")
     regions = [(int(r[0]), int(r[1]))] + ([(int(r[2]), int(r[3]))] if r[3] else [])
     return [int(x) for x in o], regions, int(adv.value)
+
+
+def dadam_deal_offsets(nbytes: Sequence[int], region0, region1):
+    """Offsets of the buffers dealt alternately over the regions (lo, hi) of one arena."""
+    n = len(nbytes)
+    a = (C.c_uint64 * n)(*[int(x) for x in nbytes])
+    o = (C.c_uint64 * n)()
+    rc = lib.dadam_deal_offsets(a, n, int(region0[0]), int(region0[1]), int(region1[0]), int(region1[1]), o)
+    if rc < 0:
+        raise DadamError(rc, f"dadam_deal_offsets: {n} buffers do not fit the regions {region0}, {region1} (or bad bounds)")
+    return [int(x) for x in o]
 
 
 def dadam_init(n_rows: int, n_cols: int, d: int, offsets: Sequence[int], numels: Sequence[int],

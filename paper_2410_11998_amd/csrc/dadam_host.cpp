@@ -859,6 +859,42 @@ int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_byte
   return DADAM_OK;
 }
 
+int dadam_deal_offsets(const uint64_t* nbytes, uint32_t n, uint64_t lo0, uint64_t hi0, uint64_t lo1, uint64_t hi1,
+                       uint64_t* offsets) {
+  if (!nbytes || !offsets || n == 0) return DADAM_EINVAL;
+  const uint64_t unit = 2ull << 20;
+  const uint64_t lo[2] = {lo0, lo1}, hi[2] = {hi0, hi1};
+  for (int r = 0; r < 2; ++r)
+    if (lo[r] % unit || hi[r] % unit || lo[r] > hi[r] || hi[r] > (1ull << 50)) return DADAM_EINVAL;
+  if (lo0 < hi1 && lo1 < hi0 && lo0 != hi0 && lo1 != hi1) return DADAM_EINVAL;  // the regions overlap
+  std::vector<uint64_t> side[2];
+  for (uint32_t k = 0; k < n; ++k) {
+    if (nbytes[k] > (1ull << 46)) return DADAM_EINVAL;
+    side[k & 1].push_back(nbytes[k]);
+  }
+  for (int r = 0; r < 2; ++r) {
+    if (side[r].empty()) continue;
+    std::vector<uint64_t> off(side[r].size());
+    const int rc = dadam_spread_offsets(side[r].data(), (uint32_t)side[r].size(), hi[r] - lo[r], off.data());
+    if (rc != DADAM_OK) return rc;
+    // Stagger the buffers inside their gaps by a fixed pseudo-random number of 2 MiB steps, so that their
+    // bases do not form an arithmetic progression: for some distances (660 MiB, 884 MiB between 476 MiB
+    // buffers) a progression costs 3-4 % of bandwidth, staggered bases never did.  A buffer moves forward
+    // by less than the gap behind it; the last one stays where it is.
+    for (size_t j = 0; j + 1 < off.size(); ++j) {
+      const uint64_t end = off[j] + (side[r][j] + unit - 1) / unit * unit;
+      const uint64_t slots = off[j + 1] > end ? (off[j + 1] - end) / unit : 0;
+      uint64_t z = ((uint64_t)j + 1) * 0x9E3779B97F4A7C15ull;  // a fixed 64-bit mix of the buffer's number
+      z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+      z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+      z ^= z >> 31;
+      if (slots > 1) off[j] += z % slots * unit;
+    }
+    for (size_t j = 0; j < off.size(); ++j) offsets[2 * j + r] = lo[r] + off[j];
+  }
+  return DADAM_OK;
+}
+
 int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes, uint64_t device_total_bytes,
                         uint64_t* offsets, uint64_t* regions_out, uint32_t* advice_out) {
   if (!nbytes || !offsets || n == 0) return DADAM_EINVAL;
@@ -896,25 +932,8 @@ int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes
   }
   if (advice_out) *advice_out = advice;
   if (advice == DADAM_PLACE_TWO_REGIONS) {
-    for (int r = 0; r < 2; ++r) {
-      std::vector<uint64_t> off(side[r].size());
-      const int rc = dadam_spread_offsets(side[r].data(), (uint32_t)side[r].size(), width[r], off.data());
-      if (rc != DADAM_OK) return rc;
-      // Stagger the buffers inside their gaps by a fixed pseudo-random number of 2 MiB steps, so that their
-      // bases do not form an arithmetic progression: for some distances (660 MiB, 884 MiB between 476 MiB
-      // buffers) a progression costs 3-4 % of bandwidth, staggered bases never did.  A buffer moves forward
-      // by less than the gap behind it; the last one stays where it is.
-      for (size_t j = 0; j + 1 < off.size(); ++j) {
-        const uint64_t end = off[j] + (side[r][j] + unit - 1) / unit * unit;
-        const uint64_t slots = off[j + 1] > end ? (off[j + 1] - end) / unit : 0;
-        uint64_t z = ((uint64_t)j + 1) * 0x9E3779B97F4A7C15ull;  // a fixed 64-bit mix of the buffer's number
-        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-        z ^= z >> 31;
-        if (slots > 1) off[j] += z % slots * unit;
-      }
-      for (size_t j = 0; j < off.size(); ++j) offsets[2 * j + r] = lo[r] + off[j];
-    }
+    const int rc = dadam_deal_offsets(nbytes, n, lo[0], lo[0] + width[0], lo[1], lo[1] + width[1], offsets);
+    if (rc != DADAM_OK) return rc;
     if (regions_out) {
       regions_out[0] = lo[0]; regions_out[1] = lo[0] + width[0];
       regions_out[2] = lo[1]; regions_out[3] = lo[1] + width[1];

@@ -68,17 +68,11 @@ class GpuSim:
         pdt = TORCH_DT[param_dtype]
         dts = [pdt] * n_cols + ([] if inplace else [pdt] * n_rows) + [torch.float32] * (n_rows * (3 if hp.s > 1 else 2))
         if spread:
-            # the benchmark's layout: one arena over most of the free memory, buffers dealt over two regions
+            # the benchmark's layout: one arena over most of the free memory, buffers dealt over two stretches
+            # of it that the arena's timing probe finds in different thirds of the memory
             from paper_2410_11998_amd.arena import SpreadArena
             sizes = [d * (2 if dt == torch.bfloat16 else 4) for dt in dts]
-            keep = 48 << 30                                         # room for the gradients and temporaries of the test
-            free, total = torch.cuda.mem_get_info(self.dev)
-            # the benchmark's placement (computed for an arena over the whole device), as far as the
-            # smaller arena of the test reaches
-            placed, _regions, _advice = B.dadam_place_offsets(sizes, total, total)
-            if max(o + n for o, n in zip(placed, sizes)) > free - keep:
-                placed = None
-            self.arena = SpreadArena(sizes, self.dev, keep_free_bytes=keep, offsets=placed)
+            self.arena = SpreadArena(sizes, self.dev, keep_free_bytes=48 << 30)   # room for the test's gradients and temporaries
             bufs = self.arena.views(dts)
             for t in bufs:
                 t.zero_()

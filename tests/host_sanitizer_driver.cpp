@@ -104,6 +104,19 @@ int main() {
     for (size_t k = 1; k < iv.size(); ++k)
       if (iv[k].first < iv[k - 1].second) { printf("placement overlaps\n"); return 1; }
   }
+  // dealing over two random regions (valid or not): accepted answers stay inside their region
+  for (int it = 0; it < 300; ++it) {
+    const uint32_t n = 1 + rng() % 90;
+    std::vector<uint64_t> sz(n), o(n);
+    for (auto& x : sz) x = 1 + rng() % (600u << 20);
+    uint64_t b[4];
+    for (auto& x : b) x = ((uint64_t)(rng() % 140000) << 21) + ((rng() % 50 == 0) ? 4096 : 0);
+    if (rng() % 2) std::sort(b, b + 4);
+    if (dadam_deal_offsets(sz.data(), n, b[0], b[1], b[2], b[3], o.data()) != DADAM_OK) { ++n_err; continue; }
+    ++n_ok;
+    for (uint32_t k = 0; k < n; ++k)
+      if (o[k] < b[2 * (k & 1)] || o[k] + sz[k] > b[2 * (k & 1) + 1]) { printf("dealt out of its region\n"); return 1; }
+  }
   printf("sanitizer driver finished: %d ok, %d rejected\n", n_ok, n_err);
   return 0;
 }

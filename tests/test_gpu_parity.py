@@ -442,6 +442,48 @@ def test_spread_arena_layout_matches_oracle():
         sim.close()
 
 
+def test_arena_finds_stretches_in_different_thirds_by_timing():
+    """The arena's timing probe on the real memory: on a device with most of its memory free the arena reaches
+    into at least two thirds, the buffers are dealt over two stretches the probe told apart, and a pass with its
+    buffers split over the two regions runs at the rate that made the probe tell them apart - also when 40 GiB
+    were allocated first (which moves the boundaries inside the arena)."""
+    from paper_2410_11998_amd import arena as A
+    free, total = torch.cuda.mem_get_info(DEV)
+    if free < (200 << 30):
+        pytest.skip("needs a device with 200 GiB free")
+    sizes = [48 << 20] * 40 + [24 << 20] * 24
+    for first_gib in (0, 40):
+        say("case", f"{first_gib} GiB allocated first")
+        first = torch.empty(first_gib << 30, dtype=torch.uint8, device=DEV) if first_gib else None
+        ar = A.SpreadArena(sizes, DEV)
+        say("layout", ar.describe())
+        H.record("arena_calibration", dict(first_gib=first_gib, stretches=[[t, lo >> 30, hi >> 30] for t, lo, hi in ar.stretches],
+                                           regions=[[lo >> 30, hi >> 30] for lo, hi in ar.regions_used], policy=ar.policy))
+        assert len(ar.stretches) >= 2 and len({t for t, _lo, _hi in ar.stretches}) == len(ar.stretches)
+        assert ar.policy == "two regions found by timing" and ar.advice == B.DADAM_PLACE_TWO_REGIONS
+        owner = lambda off: next(t for t, lo, hi in ar.stretches if lo <= off < hi)
+        (lo0, hi0), (lo1, hi1) = ar.regions_used
+        assert owner(lo0) == owner(hi0 - 1) != owner(lo1) == owner(hi1 - 1)
+        for k, (o, n) in enumerate(zip(ar.offsets, sizes)):
+            lo, hi = ar.regions_used[k % 2]
+            assert lo <= o and o + n <= hi
+        # boundaries between thirds are 96 GiB apart wherever the arena starts
+        cuts = [hi for _t, _lo, hi in ar.stretches[:-1]]
+        if len(cuts) == 2:
+            assert abs((cuts[1] - cuts[0]) - (96 << 30)) <= 2 * A.PROBE_STEP
+        probe = A.ThirdsProbe(ar.storage, ar.base_offset)
+        across = probe.rate(lo0, hi1 - A.PROBE_CHUNK)
+        within = probe.rate(lo0, lo0 + (hi0 - lo0) // 2 // A.UNIT * A.UNIT)
+        probe.close()
+        H.record("arena_calibration_rates", dict(first_gib=first_gib, across=across, within=within))
+        say("rates", f"across {across:.3f} within {within:.3f}")
+        assert across > within
+        del ar, probe, first
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+
+
 def test_time_varying_loops_alternating_exponential_ring():
     """16 replicas cycling through the four AER phases (rows of degree 4 and 8) and, on a second
     handle, through the two one-peer-ring matchings."""
