@@ -298,12 +298,16 @@ int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes
 /* Layout advice for HBM, part 3: the dealing itself, for a caller that knows two
  * regions [lo0, hi0) and [lo1, hi1) of one arena to lie in different thirds of the physical memory - e.g.
  * because it has timed a streaming probe over pairs of chunks of its arena, which tells same third from
- * different third reliably (paper_2410_11998_amd/arena.py does that).  dadam_deal_offsets places buffers
- * 0, 2, 4, ... in the first region and 1, 3, 5, ... in the second, spread over each region and staggered as
- * described under dadam_place_offsets.  Region bounds are multiples of 2 MiB and the regions do not overlap.
- * Errors: DADAM_EINVAL (null, n == 0, bounds unaligned or overlapping, a side's buffers do not fit). */
+ * different third reliably (paper_2410_11998_amd/arena.py does that).  dadam_deal_offsets places every
+ * `every`-th buffer (numbers every-1, 2*every-1, ...) in the second region and the others in the first, spread
+ * over each region and staggered as described under dadam_place_offsets.  every = 2 deals alternately (the
+ * layout measured at 0.79 of peak); every = 4 puts a quarter of the buffers in the second region, for a second
+ * region with little room (a 16-source mixing pass dealt 3:1 still ran at 0.79).  2 <= every <= 8.  Region
+ * bounds are multiples of 2 MiB and the regions do not overlap.
+ * Errors: DADAM_EINVAL (null, n == 0, every out of range, bounds unaligned or overlapping, a side's buffers do
+ * not fit). */
 int dadam_deal_offsets(const uint64_t* nbytes, uint32_t n, uint64_t lo0, uint64_t hi0, uint64_t lo1, uint64_t hi1,
-                       uint64_t* offsets);
+                       uint32_t every, uint64_t* offsets);
 
 /* Text of the last error recorded on this handle ("" if none).  With h == NULL: the text of the
  * last dadam_init failure of the calling thread.  The pointer stays valid until the next call on

@@ -87,66 +87,78 @@ class ThirdsProbe:
         self.h, self.state = None, None
 
 
-def stretches_in_different_thirds(span_bytes: int, rate) -> List[Tuple[int, int, int]]:
+def stretches_in_different_thirds(span_bytes: int, rate, attempts: int = 2) -> List[Tuple[int, int, int]]:
     """Stretches (third id, lo, hi) of an arena of span_bytes, found by timing: ``rate(off_a, off_b)`` is the
     fraction of peak a streaming pass sustains over the chunks at those offsets.  Chunks every PROBE_STEP bytes
     are compared with a reference chunk; those that run fast with it (>= 0.95 of the fastest pairing, which
-    itself must reach 0.75 of peak) lie in another third.  A second reference taken from those separates the
-    other two thirds.  Pure bookkeeping around the timings (tested on the CPU with a model of the memory)."""
+    itself must reach 0.75 of peak; measured: 0.78-0.80 across thirds, 0.61-0.73 inside one) lie in another
+    third.  A second reference taken from those separates the other two thirds.  An answer with more than
+    three stretches, or with two stretches of one third, is not believed: the timing is repeated, and an empty
+    list returned if that does not help.  Pure bookkeeping around the timings (tested on the CPU with a model
+    of the memory)."""
     offs = list(range(0, span_bytes - PROBE_CHUNK + 1, PROBE_STEP))
     if len(offs) < 3:
         return []
 
-    def same_third_as(ref_index: int) -> Optional[List[bool]]:
+    def same_third_as(ref_index: int) -> List[bool]:
         rates = [None if k == ref_index else rate(offs[ref_index], offs[k]) for k in range(len(offs))]
         best = max(r for r in rates if r is not None)
         if best < 0.75:                 # no pairing reaches the two-thirds level: everything shares the reference's third
             return [True] * len(offs)
         return [r is None or r < 0.95 * best for r in rates]
 
-    third = [-1] * len(offs)
-    with_a = same_third_as(0)
-    for k, s in enumerate(with_a):
-        if s:
-            third[k] = 0
-    rest = [k for k in range(len(offs)) if third[k] < 0]
-    if rest:
-        with_b = same_third_as(rest[0])
-        for k in rest:
-            third[k] = 1 if with_b[k] else 2
-    for k in range(1, len(offs) - 1):      # one chunk at odds with two neighbours that agree: a timing outlier
-        if third[k - 1] == third[k + 1] != third[k]:
-            third[k] = third[k - 1]
-    runs, k = [], 0
-    while k < len(offs):
-        j = k
-        while j + 1 < len(offs) and third[j + 1] == third[k]:
-            j += 1
-        # a run covers its first chunk's start to its last chunk's end: every byte in between lies in chunks that
-        # were classified alike on both sides
-        runs.append((third[k], offs[k], offs[j] + PROBE_CHUNK))
-        k = j + 1
-    return runs
+    for _attempt in range(attempts):
+        third = [-1] * len(offs)
+        for k, s in enumerate(same_third_as(0)):
+            if s:
+                third[k] = 0
+        rest = [k for k in range(len(offs)) if third[k] < 0]
+        if rest:
+            with_b = same_third_as(rest[min(2, len(rest) - 1)])     # not the first: that chunk may lie across a boundary
+            for k in rest:
+                third[k] = 1 if with_b[k] else 2
+        for k in range(1, len(offs) - 1):      # one chunk at odds with two neighbours that agree: a timing outlier
+            if third[k - 1] == third[k + 1] != third[k]:
+                third[k] = third[k - 1]
+        runs, k = [], 0
+        while k < len(offs):
+            j = k
+            while j + 1 < len(offs) and third[j + 1] == third[k]:
+                j += 1
+            # a run covers its first chunk's start to its last chunk's end: every byte in between lies in chunks
+            # that were classified alike on both sides
+            runs.append((third[k], offs[k], offs[j] + PROBE_CHUNK))
+            k = j + 1
+        if len(runs) <= 3 and len({t for t, _lo, _hi in runs}) == len(runs):
+            return runs
+    return []
 
 
-def two_regions_from_stretches(runs: Sequence[Tuple[int, int, int]], need: Sequence[int]) -> Optional[List[Tuple[int, int]]]:
-    """The two regions to deal buffers over: the two longest stretches that lie in different thirds and hold
-    need[0] / need[1] bytes, each cut down to at most max(64 GiB, 1.2 x need) on the side nearest the other."""
-    best = None
-    for a in runs:
-        for b in runs:
-            if a[0] == b[0] or a[1] >= b[1]:
-                continue
-            if a[2] - a[1] >= need[0] and b[2] - b[1] >= need[1]:
+def two_regions_from_stretches(runs: Sequence[Tuple[int, int, int]], nbytes: Sequence[int]):
+    """The two regions to deal buffers over, and how: ((lo0, hi0), (lo1, hi1), every) for dadam_deal_offsets,
+    or None.  Alternate dealing (every = 2) over the two stretches of different thirds with the most room if
+    half of the buffers fit each; otherwise every 3rd, 4th, 6th or 8th buffer goes to the smaller stretch.  A
+    region is cut down to max(64 GiB, 1.2 x what it holds), at the end of its stretch nearest the other one."""
+    for every in (2, 3, 4, 6, 8):
+        minor = sum(_round_up(n) for k, n in enumerate(nbytes) if k % every == every - 1)
+        major = sum(_round_up(n) for n in nbytes) - minor
+        best = None
+        for a in runs:                  # a holds the larger share
+            for b in runs:
+                if a[0] == b[0] or a[2] - a[1] < major or b[2] - b[1] < minor:
+                    continue
                 size = min(a[2] - a[1], 96 * GIB) + min(b[2] - b[1], 96 * GIB)
                 if best is None or size > best[0]:
                     best = (size, a, b)
-    if best is None:
-        return None
-    _, a, b = best
-    w0 = min(a[2] - a[1], max(64 * GIB, _round_up(need[0] * 6 // 5)))
-    w1 = min(b[2] - b[1], max(64 * GIB, _round_up(need[1] * 6 // 5)))
-    return [(a[2] - w0, a[2]), (b[1], b[1] + w1)]      # a lies below b: a's top end, b's bottom end
+        if best is None:
+            continue
+        _, a, b = best
+        wa = min(a[2] - a[1], max(64 * GIB, _round_up(major * 6 // 5)))
+        wb = min(b[2] - b[1], max(64 * GIB, _round_up(minor * 6 // 5)))
+        if a[1] < b[1]:
+            return (a[2] - wa, a[2]), (b[1], b[1] + wb), every
+        return (a[1], a[1] + wa), (b[2] - wb, b[2]), every
+    return None
 
 
 class SpreadArena:
@@ -183,7 +195,6 @@ class SpreadArena:
             self.policy, placed = "given offsets", [int(o) for o in offsets]
             self.regions_used = [(min(placed), max(o + n for o, n in zip(placed, self.nbytes)))]
         elif two_regions and calibrate and len(self.nbytes) >= 2 and span_bytes >= 2 * PROBE_STEP + PROBE_CHUNK:
-            need = [sum(_round_up(n) for n in self.nbytes[r::2]) for r in (0, 1)]
             try:
                 probe = ThirdsProbe(self.storage, self.base_offset)
             except torch.OutOfMemoryError:
@@ -191,12 +202,22 @@ class SpreadArena:
             if probe is not None:
                 try:
                     self.stretches = stretches_in_different_thirds(span_bytes // UNIT * UNIT, probe.rate)
+                    found = two_regions_from_stretches(self.stretches, self.nbytes)
+                    if found is not None:
+                        # believed only if a pass over the two regions' far ends runs at the two-thirds level and a
+                        # pass inside each region does not
+                        (lo0, hi0), (lo1, hi1), every = found
+                        ends = [(lo, max(lo, (hi - PROBE_CHUNK) // UNIT * UNIT)) for lo, hi in ((lo0, hi0), (lo1, hi1))]
+                        across = probe.rate(ends[0][0] if lo0 < lo1 else ends[0][1], ends[1][1] if lo0 < lo1 else ends[1][0])
+                        inside = [probe.rate(lo, hi) for lo, hi in ends if hi - lo >= PROBE_CHUNK]
+                        if across < 0.75 or any(r >= 0.95 * across for r in inside):
+                            found = None
                 finally:
                     probe.close()
-                regions = two_regions_from_stretches(self.stretches, need)
-                if regions is not None:
-                    placed = B.dadam_deal_offsets(self.nbytes, regions[0], regions[1])
-                    self.policy, self.regions_used, self.advice = "two regions found by timing", regions, B.DADAM_PLACE_TWO_REGIONS
+                if found is not None:
+                    placed = B.dadam_deal_offsets(self.nbytes, found[0], found[1], every)
+                    self.regions_used, self.advice = [found[0], found[1]], B.DADAM_PLACE_TWO_REGIONS
+                    self.policy = "two regions found by timing" + ("" if every == 2 else f" (every {every}th buffer in the second)")
         if placed is None and two_regions:
             placed, self.regions_used, self.advice = B.dadam_place_offsets(self.nbytes, span_bytes, total)
             self.policy = {B.DADAM_PLACE_TWO_REGIONS: "two regions across the first boundary (whole-device rule)",

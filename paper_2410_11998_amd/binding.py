@@ -93,7 +93,7 @@ def _load() -> C.CDLL:
     lib.dadam_place_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64,
                                         C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
     lib.dadam_deal_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64,
-                                       C.POINTER(C.c_uint64)]
+                                       C.c_uint32, C.POINTER(C.c_uint64)]
     lib.dadam_last_error.argtypes = [H]
     lib.dadam_last_error.restype = C.c_char_p
     lib.dadam_destroy.argtypes = [H]
@@ -188,12 +188,12 @@ def dadam_place_offsets(nbytes: Sequence[int], arena_bytes: int, device_total_by
     return [int(x) for x in o], regions, int(adv.value)
 
 
-def dadam_deal_offsets(nbytes: Sequence[int], region0, region1):
-    """Offsets of the buffers dealt alternately over the regions (lo, hi) of one arena."""
+def dadam_deal_offsets(nbytes: Sequence[int], region0, region1, every: int = 2):
+    """Offsets of the buffers dealt over the regions (lo, hi) of one arena: every `every`-th one in region1."""
     n = len(nbytes)
     a = (C.c_uint64 * n)(*[int(x) for x in nbytes])
     o = (C.c_uint64 * n)()
-    rc = lib.dadam_deal_offsets(a, n, int(region0[0]), int(region0[1]), int(region1[0]), int(region1[1]), o)
+    rc = lib.dadam_deal_offsets(a, n, int(region0[0]), int(region0[1]), int(region1[0]), int(region1[1]), int(every), o)
     if rc < 0:
         raise DadamError(rc, f"dadam_deal_offsets: {n} buffers do not fit the regions {region0}, {region1} (or bad bounds)")
     return [int(x) for x in o]

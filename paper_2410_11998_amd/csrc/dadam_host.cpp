@@ -860,17 +860,20 @@ int dadam_spread_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_byte
 }
 
 int dadam_deal_offsets(const uint64_t* nbytes, uint32_t n, uint64_t lo0, uint64_t hi0, uint64_t lo1, uint64_t hi1,
-                       uint64_t* offsets) {
-  if (!nbytes || !offsets || n == 0) return DADAM_EINVAL;
+                       uint32_t every, uint64_t* offsets) {
+  if (!nbytes || !offsets || n == 0 || every < 2 || every > 8) return DADAM_EINVAL;
   const uint64_t unit = 2ull << 20;
   const uint64_t lo[2] = {lo0, lo1}, hi[2] = {hi0, hi1};
   for (int r = 0; r < 2; ++r)
     if (lo[r] % unit || hi[r] % unit || lo[r] > hi[r] || hi[r] > (1ull << 50)) return DADAM_EINVAL;
   if (lo0 < hi1 && lo1 < hi0 && lo0 != hi0 && lo1 != hi1) return DADAM_EINVAL;  // the regions overlap
   std::vector<uint64_t> side[2];
+  std::vector<uint32_t> number[2];  // which buffers a side holds
   for (uint32_t k = 0; k < n; ++k) {
     if (nbytes[k] > (1ull << 46)) return DADAM_EINVAL;
-    side[k & 1].push_back(nbytes[k]);
+    const int r = k % every == every - 1 ? 1 : 0;
+    side[r].push_back(nbytes[k]);
+    number[r].push_back(k);
   }
   for (int r = 0; r < 2; ++r) {
     if (side[r].empty()) continue;
@@ -890,7 +893,7 @@ int dadam_deal_offsets(const uint64_t* nbytes, uint32_t n, uint64_t lo0, uint64_
       z ^= z >> 31;
       if (slots > 1) off[j] += z % slots * unit;
     }
-    for (size_t j = 0; j < off.size(); ++j) offsets[2 * j + r] = lo[r] + off[j];
+    for (size_t j = 0; j < off.size(); ++j) offsets[number[r][j]] = lo[r] + off[j];
   }
   return DADAM_OK;
 }
@@ -932,7 +935,7 @@ int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes
   }
   if (advice_out) *advice_out = advice;
   if (advice == DADAM_PLACE_TWO_REGIONS) {
-    const int rc = dadam_deal_offsets(nbytes, n, lo[0], lo[0] + width[0], lo[1], lo[1] + width[1], offsets);
+    const int rc = dadam_deal_offsets(nbytes, n, lo[0], lo[0] + width[0], lo[1], lo[1] + width[1], 2, offsets);
     if (rc != DADAM_OK) return rc;
     if (regions_out) {
       regions_out[0] = lo[0]; regions_out[1] = lo[0] + width[0];

@@ -112,10 +112,13 @@ int main() {
     uint64_t b[4];
     for (auto& x : b) x = ((uint64_t)(rng() % 140000) << 21) + ((rng() % 50 == 0) ? 4096 : 0);
     if (rng() % 2) std::sort(b, b + 4);
-    if (dadam_deal_offsets(sz.data(), n, b[0], b[1], b[2], b[3], o.data()) != DADAM_OK) { ++n_err; continue; }
+    const uint32_t every = 1 + rng() % 9;
+    if (dadam_deal_offsets(sz.data(), n, b[0], b[1], b[2], b[3], every, o.data()) != DADAM_OK) { ++n_err; continue; }
     ++n_ok;
-    for (uint32_t k = 0; k < n; ++k)
-      if (o[k] < b[2 * (k & 1)] || o[k] + sz[k] > b[2 * (k & 1) + 1]) { printf("dealt out of its region\n"); return 1; }
+    for (uint32_t k = 0; k < n; ++k) {
+      const int r = k % every == every - 1;
+      if (o[k] < b[2 * r] || o[k] + sz[k] > b[2 * r + 1]) { printf("dealt out of its region\n"); return 1; }
+    }
   }
   printf("sanitizer driver finished: %d ok, %d rejected\n", n_ok, n_err);
   return 0;

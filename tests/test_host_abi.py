@@ -608,32 +608,44 @@ def test_thirds_are_found_from_timings_of_a_modelled_memory():
             return r * (1 + 0.01 * rng.uniform(-1, 1))
         return rate
 
-    need = [26 * GIB, 26 * GIB]
-    for base_gib, span_gib in ((0, 275), (40, 235), (70, 200), (100, 170), (190, 90), (3, 60), (50, 100)):
+    sizes = [476 << 20] * 112                                        # configuration 2 with two gradient sets: 26 GiB a side
+    half = sum(sizes) // 2
+    third_of = lambda off, base: (off + base) // (96 * GIB)
+    seen_every = set()
+    for base_gib, span_gib in ((0, 275), (40, 235), (70, 200), (100, 170), (190, 90), (3, 60), (50, 100), (75, 60), (20, 90)):
         base, span = base_gib * GIB, span_gib * GIB
         runs = A.stretches_in_different_thirds(span, model(base))
         assert runs and runs[0][1] == 0
         for t, lo, hi in runs:                                       # each stretch lies in one third (up to one chunk of overlap)
-            assert (lo + base) // (96 * GIB) == (hi - 1 - A.PROBE_CHUNK + base) // (96 * GIB), (base_gib, runs)
-        firsts = {(lo + base) // (96 * GIB) for _t, lo, _hi in runs}
-        lasts = (span - A.PROBE_CHUNK + base) // (96 * GIB)
-        assert len(runs) == len(firsts) == lasts - base // (96 * GIB) + 1, (base_gib, runs)
+            assert third_of(lo, base) == third_of(hi - 1 - A.PROBE_CHUNK, base), (base_gib, runs)
+        firsts = {third_of(lo, base) for _t, lo, _hi in runs}
+        assert len(runs) == len(firsts) == third_of(span - A.PROBE_CHUNK, base) - third_of(0, base) + 1, (base_gib, runs)
         assert len({t for t, _lo, _hi in runs}) == len(runs)
-        regions = A.two_regions_from_stretches(runs, need)
+        found = A.two_regions_from_stretches(runs, sizes)
         room = sorted(hi - lo for _t, lo, hi in runs)
-        if len(runs) >= 2 and room[-2] >= need[0]:
-            (lo0, hi0), (lo1, hi1) = regions
-            assert hi0 <= lo1 and hi0 - lo0 >= need[0] and hi1 - lo1 >= need[1]
-            assert (lo0 + base) // (96 * GIB) == (hi0 - 1 - A.PROBE_CHUNK + base) // (96 * GIB)
-            assert (lo1 + base + A.PROBE_CHUNK) // (96 * GIB) == (hi1 - 1 + base) // (96 * GIB)
-            assert (lo0 + base) // (96 * GIB) != (hi1 - 1 + base) // (96 * GIB)
+        if len(runs) >= 2 and room[-1] >= sum(sizes) * 7 // 8 + (1 << 30) and room[-2] >= sum(sizes) // 8 + (1 << 30):
+            (lo0, hi0), (lo1, hi1), every = found
+            seen_every.add(every)
+            off = B.dadam_deal_offsets(sizes, (lo0, hi0), (lo1, hi1), every)      # fits
+            assert third_of(lo0, base) == third_of(hi0 - 1 - A.PROBE_CHUNK, base) if lo0 < lo1 else third_of(lo0 + A.PROBE_CHUNK, base) == third_of(hi0 - 1, base)
+            assert third_of(lo1 + A.PROBE_CHUNK, base) == third_of(hi1 - 1, base) if lo0 < lo1 else third_of(lo1, base) == third_of(hi1 - 1 - A.PROBE_CHUNK, base)
+            assert third_of((lo0 + hi0) // 2, base) != third_of((lo1 + hi1) // 2, base)
             assert hi0 - lo0 <= 64 * GIB and hi1 - lo1 <= 64 * GIB
-        else:
-            assert regions is None
+            assert min(hi0, hi1) <= max(lo0, lo1)
+            if every == 2:
+                assert hi0 - lo0 >= half and hi1 - lo1 >= half
+            else:                                                    # the even split did not fit anywhere
+                assert room[-2] < half + (2 << 20) * len(sizes)
+        elif len(runs) < 2 or room[-2] < sum(sizes) // 8:
+            assert found is None
+    assert seen_every >= {2} and len(seen_every) >= 2, seen_every
     # a memory with no fast pairing at all: one stretch, no regions
     runs = A.stretches_in_different_thirds(100 * GIB, lambda a, b: 0.66)
-    assert len(runs) == 1 and A.two_regions_from_stretches(runs, need) is None
+    assert len(runs) == 1 and A.two_regions_from_stretches(runs, sizes) is None
     assert A.stretches_in_different_thirds(5 * GIB, lambda a, b: 0.79) == []
+    # timings that make no sense (a fast pairing here and there): nothing is believed
+    noisy = np.random.default_rng(1)
+    assert A.stretches_in_different_thirds(200 * GIB, lambda a, b: 0.79 if noisy.uniform() < 0.5 else 0.65) == []
 
 
 def test_device_access_helpers_on_the_cpu_under_sanitizers(tmp_path):
