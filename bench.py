@@ -443,6 +443,7 @@ def measure(args, want_cpu_sample: bool):
             "device_lds_limit": int(info.lds_limit_bytes), "device_xcds": int(info.n_xcds), "path": args.path,
             "launches_per_step": launches_per_step, "x_buffers": "in-place" if inplace else "ping-pong",
             "hbm_layout": hbm_layout, "placement_advice": placement_advice,
+            "placement_probe_launches": arena.probe_launches if arena is not None else 0,
             "grad_pool": len(pool),
             "issue": "eager" if graph is None else f"graph of {L} iterations, replayed",
             "bucket_streams": max(1, len(side)) if args.path == "buckets" else None,

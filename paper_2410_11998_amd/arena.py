@@ -54,6 +54,7 @@ class ThirdsProbe:
     def __init__(self, storage: torch.Tensor, base_offset: int):
         from . import workloads as WL
         self.storage, self.base = storage, base_offset
+        self.launches = 0
         dev = storage.device
         self.state = [torch.empty(PROBE_ELEMS, dtype=torch.float32, device=dev) for _ in range(2 * PROBE_ROWS)]
         self.h = B.dadam_init(PROBE_ROWS, PROBE_ROWS, PROBE_ELEMS, [0], [PROBE_ELEMS], device=dev.index or 0)
@@ -78,6 +79,7 @@ class ThirdsProbe:
             B.dadam_mix(self.h, 0, 0, st)
         e1.record()
         torch.cuda.synchronize()
+        self.launches += 2 + reps
         seconds = e0.elapsed_time(e1) / reps / 1e3
         return 2 * PROBE_ROWS * nb / seconds / HBM_PEAK
 
@@ -189,6 +191,7 @@ class SpreadArena:
         self.base_offset = (-self.storage.data_ptr()) % UNIT            # start on a 2 MiB boundary
         self.span_bytes = span_bytes
         self.advice = 0
+        self.probe_launches = 0                   # mixing passes launched by the timing probe (profiles set them apart)
         self.stretches: List[Tuple[int, int, int]] = []
         placed = None
         if offsets is not None:
@@ -213,6 +216,7 @@ class SpreadArena:
                         if across < 0.75 or any(r >= 0.95 * across for r in inside):
                             found = None
                 finally:
+                    self.probe_launches = probe.launches
                     probe.close()
                 if found is not None:
                     placed = B.dadam_deal_offsets(self.nbytes, found[0], found[1], every)
