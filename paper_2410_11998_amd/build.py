@@ -3,9 +3,9 @@
     python -m paper_2410_11998_amd.build [--incremental] [extra hipcc flags]
 
 Each translation unit is compiled to an object under _build/ (several at a time) and the objects
-are linked into libdadam.so beside this file.  The tile and direct kernels are compiled in eight
+are linked into libdadam.so beside this file.  The tile and direct kernels are compiled in sixteen
 parts from one source (csrc/dadam_kernels_part.hip: a pair of element types, with or without the
-streaming hint).  build() recompiles everything; --incremental skips units whose object is newer
+streaming hint, pointer tables in the argument block or in device memory).  build() recompiles everything; --incremental skips units whose object is newer
 than the source and every header.
 """
 
@@ -30,10 +30,12 @@ UNITS = [("dadam_host", "dadam_host.cpp", []), ("dadam_kernels", "dadam_kernels.
 for _x in ("f32", "bf16"):
     for _g in ("f32", "bf16"):
         for _nt in (True, False):
-            _name = f"{_x}_{_g}" + ("_nt" if _nt else "")
-            UNITS.append((f"dadam_kernels_part_{_name}", "dadam_kernels_part.hip",
-                          [f"-DDADAM_PART_XT={TYPES[_x]}", f"-DDADAM_PART_GT={TYPES[_g]}",
-                           f"-DDADAM_PART_NT={'true' if _nt else 'false'}", f"-DDADAM_PART_NAME={_name}"]))
+            for _ext in (False, True):
+                _name = f"{_x}_{_g}" + ("_nt" if _nt else "") + ("_ext" if _ext else "")
+                UNITS.append((f"dadam_kernels_part_{_name}", "dadam_kernels_part.hip",
+                              [f"-DDADAM_PART_XT={TYPES[_x]}", f"-DDADAM_PART_GT={TYPES[_g]}",
+                               f"-DDADAM_PART_NT={'true' if _nt else 'false'}",
+                               f"-DDADAM_PART_EXT={'true' if _ext else 'false'}", f"-DDADAM_PART_NAME={_name}"]))
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -164,6 +164,21 @@ __device__ __forceinline__ void store_vals(void* base, uint64_t e, uint64_t lo, 
   }
 }
 
+// The stores of a row's UT vectors.  With one vector per lane there must be no loop around the store: a loop
+// that runs once has a loop-invariant address, the compiler's loop-invariant code motion then "promotes" the
+// location to a register and re-creates the store behind the loop - without the non-temporal hint (seen with
+// the bfloat16 one-vector tile kernels: 1.2 % slower on the ring of 8; the compile test counts the hints).
+template <typename T, int VEC, int H, bool MASKED, bool NT, int UT>
+__device__ __forceinline__ void store_vectors(void* base, const uint64_t (&e)[UT], uint64_t lo, uint64_t hi,
+                                              const float (&in)[UT][VEC]) {
+  if constexpr (UT == 1) {
+    store_vals<T, VEC, H, MASKED, NT>(base, e[0], lo, hi, in[0]);
+  } else {
+#pragma unroll
+    for (int u = 0; u < UT; ++u) store_vals<T, VEC, H, MASKED, NT>(base, e[u], lo, hi, in[u]);
+  }
+}
+
 // The 16 raw bytes of a lane's parameter vector (4 float32, or 2 x 4 bfloat16 in the two groups
 // described above), as they are parked in LDS.
 template <typename XT, int H, bool MASKED, bool NT>
@@ -274,10 +289,12 @@ __device__ __forceinline__ void locate(const StepArgs& a, uint32_t work, uint64_
 }
 
 // Pointers of the bound buffers.  EXT = false: from the argument block (at most kInlineRows rows and
-// sources).  EXT = true: from the device-resident tables of a larger handle.  The kernels choose once, with
-// a wave-uniform branch around the whole body, so that the small case is exactly the code it was before
-// large handles existed (choosing per pointer cost 2.5 % with 64 rows, and a choice between two reads of
-// the same type even forced the whole argument block into scratch).  The tables hold addresses as
+// sources).  EXT = true: from the device-resident tables of a larger handle.  EXT is a parameter of the
+// kernels themselves and the launcher picks: the small case is exactly the code it was before large handles
+// existed, registers included (choosing per pointer inside the kernel cost 2.5 % with 64 rows, and a choice
+// between two reads of the same type even forced the whole argument block into scratch; one branch around
+// two bodies in one kernel gave the small case the large one's register count: bfloat16 plain phase 63 -> 71
+// vector registers, 8 -> 7 wavefronts per SIMD, 1.2 % slower on the ring of 8).  The tables hold addresses as
 // integers; the cast names global memory, or every access through the pointer would become a flat one
 // (slower, and counted with the LDS operations the row loop waits for).
 enum TableOf : int { kSrc = 0, kDst = 1, kMHat = 2, kVHat = 3, kAcc = 4 };  // order of BoundTables' members
@@ -483,21 +500,11 @@ __device__ __forceinline__ void finish_row(const StepArgs& a, const u4* lds, int
     for (int j = 0; j < VEC; ++j)
       xo[u][j] = element_step<PHASE>(a.s, mix[u][j], g[u][j], mh[u][j], vh[u][j], b[u][j], decay[u][j]);
 
-  void* xd = dst_of<EXT>(a, i);
-#pragma unroll
-  for (int u = 0; u < UT; ++u) store_vals<XT, VEC, kHalfWave, MASKED, NT>(xd, e[u], lo, hi, xo[u]);
-  if constexpr (Needs<PHASE>::acc_out) {
-    float* bp = acc_of<EXT>(a, i);
-#pragma unroll
-    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, kHalfWave, MASKED, NT>(bp, e[u], lo, hi, b[u]);
-  }
+  store_vectors<XT, VEC, kHalfWave, MASKED, NT>(dst_of<EXT>(a, i), e, lo, hi, xo);
+  if constexpr (Needs<PHASE>::acc_out) store_vectors<TF32, VEC, kHalfWave, MASKED, NT>(acc_of<EXT>(a, i), e, lo, hi, b);
   if constexpr (Needs<PHASE>::moments_out) {
-    float* mp = m_hat_of<EXT>(a, i);
-    float* vp = v_hat_of<EXT>(a, i);
-#pragma unroll
-    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, kHalfWave, MASKED, NT>(mp, e[u], lo, hi, mh[u]);
-#pragma unroll
-    for (int u = 0; u < UT; ++u) store_vals<TF32, VEC, kHalfWave, MASKED, NT>(vp, e[u], lo, hi, vh[u]);
+    store_vectors<TF32, VEC, kHalfWave, MASKED, NT>(m_hat_of<EXT>(a, i), e, lo, hi, mh);
+    store_vectors<TF32, VEC, kHalfWave, MASKED, NT>(v_hat_of<EXT>(a, i), e, lo, hi, vh);
   }
 }
 
@@ -606,7 +613,7 @@ __device__ __forceinline__ void tile_body(const StepArgs& a, u4* lds, uint64_t t
   }
 }
 
-template <typename XT, typename GT, int PHASE, int W, int UT, bool NT>
+template <typename XT, typename GT, int PHASE, int W, int UT, bool NT, bool EXT>
 __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
   constexpr int VEC = XT::vec;
   constexpr uint64_t TILE = (uint64_t)kWave * VEC * UT;
@@ -629,13 +636,8 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
   locate(a, a.work_begin + b, tile_index, lo, hi, wd);
   const uint64_t tbase = tile_index * TILE;
   const bool full = tbase >= lo && tbase + TILE <= hi;
-  if (a.ext == nullptr) {  // wave-uniform, the same for the whole launch
-    if (full) tile_body<XT, GT, PHASE, W, UT, false, NT, false>(a, lds, tbase, lo, hi, wd, b, lane, wave);
-    else tile_body<XT, GT, PHASE, W, UT, true, NT, false>(a, lds, tbase, lo, hi, wd, b, lane, wave);
-  } else {
-    if (full) tile_body<XT, GT, PHASE, W, UT, false, NT, true>(a, lds, tbase, lo, hi, wd, b, lane, wave);
-    else tile_body<XT, GT, PHASE, W, UT, true, NT, true>(a, lds, tbase, lo, hi, wd, b, lane, wave);
-  }
+  if (full) tile_body<XT, GT, PHASE, W, UT, false, NT, EXT>(a, lds, tbase, lo, hi, wd, b, lane, wave);
+  else tile_body<XT, GT, PHASE, W, UT, true, NT, EXT>(a, lds, tbase, lo, hi, wd, b, lane, wave);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -785,7 +787,7 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
 
 // Work items are numbered tile-major, row-minor, so that workgroups running at the same time work
 // on the same elements of different rows.
-template <typename XT, typename GT, int PHASE, bool NT>
+template <typename XT, typename GT, int PHASE, bool NT, bool EXT>
 __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
   constexpr int VEC = XT::vec;
   constexpr uint64_t TILE = (uint64_t)kDirectThreads * VEC * kUD;
@@ -798,13 +800,8 @@ __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
   locate(a, a.work_begin + t, tile_index, lo, hi, wd);
   const uint64_t tbase = tile_index * TILE;
   const bool full = tbase >= lo && tbase + TILE <= hi;
-  if (a.ext == nullptr) {  // wave-uniform, the same for the whole launch
-    if (full) direct_body<XT, GT, PHASE, false, NT, false>(a, row, tbase, lo, hi, wd, lane);
-    else direct_body<XT, GT, PHASE, true, NT, false>(a, row, tbase, lo, hi, wd, lane);
-  } else {
-    if (full) direct_body<XT, GT, PHASE, false, NT, true>(a, row, tbase, lo, hi, wd, lane);
-    else direct_body<XT, GT, PHASE, true, NT, true>(a, row, tbase, lo, hi, wd, lane);
-  }
+  if (full) direct_body<XT, GT, PHASE, false, NT, EXT>(a, row, tbase, lo, hi, wd, lane);
+  else direct_body<XT, GT, PHASE, true, NT, EXT>(a, row, tbase, lo, hi, wd, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -866,7 +863,7 @@ __device__ __forceinline__ void acc_body(const StepArgs& a, int row, uint64_t tb
 
 // VEC is the element count of a direct-mode parameter vector of this handle, so that the
 // accumulate kernel walks the same tile grid as the direct kernel.
-template <typename GT, int VEC, int PHASE, bool NT>
+template <typename GT, int VEC, int PHASE, bool NT, bool EXT>
 __global__ __launch_bounds__(kDirectThreads) void k_acc(const StepArgs a) {
   constexpr uint64_t TILE = (uint64_t)kDirectThreads * VEC * kUD;
   const uint32_t n_rows = a.n_rows;
@@ -877,58 +874,53 @@ __global__ __launch_bounds__(kDirectThreads) void k_acc(const StepArgs a) {
   locate(a, a.work_begin + t, tile_index, lo, hi, wd_unused);
   const uint64_t tbase = tile_index * TILE;
   const bool full = tbase >= lo && tbase + TILE <= hi;
-  if (a.ext == nullptr) {  // wave-uniform, the same for the whole launch
-    if (full) acc_body<GT, VEC, PHASE, false, NT, false>(a, row, tbase, lo, hi);
-    else acc_body<GT, VEC, PHASE, true, NT, false>(a, row, tbase, lo, hi);
-  } else {
-    if (full) acc_body<GT, VEC, PHASE, false, NT, true>(a, row, tbase, lo, hi);
-    else acc_body<GT, VEC, PHASE, true, NT, true>(a, row, tbase, lo, hi);
-  }
+  if (full) acc_body<GT, VEC, PHASE, false, NT, EXT>(a, row, tbase, lo, hi);
+  else acc_body<GT, VEC, PHASE, true, NT, EXT>(a, row, tbase, lo, hi);
 }
 
 // ---------------------------------------------------------------------------------------------
 // dispatch tables
 // ---------------------------------------------------------------------------------------------
 
-template <typename XT, typename GT, int W, int UT, bool NT>
+template <typename XT, typename GT, int W, int UT, bool NT, bool EXT>
 KernelFn tile_kernel_for_phase(int phase) {
   switch (phase) {
-    case kMixOnly: return k_tile<XT, GT, kMixOnly, W, UT, NT>;
-    case kMixConsensus: return k_tile<XT, GT, kMixConsensus, W, UT, NT>;
-    case kUpdateOnly: return k_tile<XT, GT, kUpdateOnly, W, UT, NT>;
-    case kPlain: return k_tile<XT, GT, kPlain, W, UT, NT>;
-    case kLoopStart: return k_tile<XT, GT, kLoopStart, W, UT, NT>;
-    case kFold: return k_tile<XT, GT, kFold, W, UT, NT>;
-    case kAlg1: return k_tile<XT, GT, kAlg1, W, UT, NT>;
+    case kMixOnly: return k_tile<XT, GT, kMixOnly, W, UT, NT, EXT>;
+    case kMixConsensus: return k_tile<XT, GT, kMixConsensus, W, UT, NT, EXT>;
+    case kUpdateOnly: return k_tile<XT, GT, kUpdateOnly, W, UT, NT, EXT>;
+    case kPlain: return k_tile<XT, GT, kPlain, W, UT, NT, EXT>;
+    case kLoopStart: return k_tile<XT, GT, kLoopStart, W, UT, NT, EXT>;
+    case kFold: return k_tile<XT, GT, kFold, W, UT, NT, EXT>;
+    case kAlg1: return k_tile<XT, GT, kAlg1, W, UT, NT, EXT>;
   }
   return nullptr;
 }
 
-template <typename XT, typename GT, bool NT>
+template <typename XT, typename GT, bool NT, bool EXT>
 KernelFn tile_kernel_for_shape_nt(int phase, TileShape s) {
-  if (s.waves == 4 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 4, 1, NT>(phase);
-  if (s.waves == 4 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 4, 2, NT>(phase);
-  if (s.waves == 8 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 8, 1, NT>(phase);
-  if (s.waves == 8 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 8, 2, NT>(phase);
+  if (s.waves == 4 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 4, 1, NT, EXT>(phase);
+  if (s.waves == 4 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 4, 2, NT, EXT>(phase);
+  if (s.waves == 8 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 8, 1, NT, EXT>(phase);
+  if (s.waves == 8 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 8, 2, NT, EXT>(phase);
 #ifdef DADAM_TUNING  // further shapes for measurements, same-type pairs only to bound the build time
   if constexpr (XT::bytes == GT::bytes) {
-    if (s.waves == 16 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 16, 1, NT>(phase);
-    if (s.waves == 16 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 16, 2, NT>(phase);
-    if (s.waves == 4 && s.ut == 4) return tile_kernel_for_phase<XT, GT, 4, 4, NT>(phase);
-    if (s.waves == 8 && s.ut == 4) return tile_kernel_for_phase<XT, GT, 8, 4, NT>(phase);
+    if (s.waves == 16 && s.ut == 1) return tile_kernel_for_phase<XT, GT, 16, 1, NT, EXT>(phase);
+    if (s.waves == 16 && s.ut == 2) return tile_kernel_for_phase<XT, GT, 16, 2, NT, EXT>(phase);
+    if (s.waves == 4 && s.ut == 4) return tile_kernel_for_phase<XT, GT, 4, 4, NT, EXT>(phase);
+    if (s.waves == 8 && s.ut == 4) return tile_kernel_for_phase<XT, GT, 8, 4, NT, EXT>(phase);
   }
 #endif
   return nullptr;
 }
-template <typename XT, typename GT, bool NT>
+template <typename XT, typename GT, bool NT, bool EXT>
 KernelFn direct_kernel_for_phase(int phase) {
   switch (phase) {
-    case kMixOnly: return k_direct<XT, GT, kMixOnly, NT>;
-    case kUpdateOnly: return k_direct<XT, GT, kUpdateOnly, NT>;
-    case kPlain: return k_direct<XT, GT, kPlain, NT>;
-    case kLoopStart: return k_direct<XT, GT, kLoopStart, NT>;
-    case kFold: return k_direct<XT, GT, kFold, NT>;
-    case kAlg1: return k_direct<XT, GT, kAlg1, NT>;
+    case kMixOnly: return k_direct<XT, GT, kMixOnly, NT, EXT>;
+    case kUpdateOnly: return k_direct<XT, GT, kUpdateOnly, NT, EXT>;
+    case kPlain: return k_direct<XT, GT, kPlain, NT, EXT>;
+    case kLoopStart: return k_direct<XT, GT, kLoopStart, NT, EXT>;
+    case kFold: return k_direct<XT, GT, kFold, NT, EXT>;
+    case kAlg1: return k_direct<XT, GT, kAlg1, NT, EXT>;
   }
   return nullptr;
 }

@@ -21,9 +21,11 @@ static __device__ __align__(256) double scratch[dadam::kConsensusPartials];
 namespace dadam {
 
 // what the parts define
-#define DADAM_PART(name)                                   \
-  KernelFn tile_kernel_##name(int phase, TileShape s);     \
-  KernelFn direct_kernel_##name(int phase)
+#define DADAM_PART(name)                                       \
+  KernelFn tile_kernel_##name(int phase, TileShape s);         \
+  KernelFn direct_kernel_##name(int phase);                    \
+  KernelFn tile_kernel_##name##_ext(int phase, TileShape s);   \
+  KernelFn direct_kernel_##name##_ext(int phase)
 DADAM_PART(f32_f32_nt);
 DADAM_PART(f32_f32);
 DADAM_PART(bf16_bf16_nt);
@@ -60,13 +62,13 @@ __global__ __launch_bounds__(256) void k_consensus_sum(const double* partials, d
 // ---------------------------------------------------------------------------------------------
 // dispatch tables
 // ---------------------------------------------------------------------------------------------
-template <typename GT, int VEC, bool NT>
+template <typename GT, int VEC, bool NT, bool EXT>
 KernelFn acc_kernel_for_phase(int phase) {
   switch (phase) {
-    case kPlain: return k_acc<GT, VEC, kPlain, NT>;
-    case kLoopStart: return k_acc<GT, VEC, kLoopStart, NT>;
-    case kFold: return k_acc<GT, VEC, kFold, NT>;
-    case kAlg1: return k_acc<GT, VEC, kAlg1, NT>;
+    case kPlain: return k_acc<GT, VEC, kPlain, NT, EXT>;
+    case kLoopStart: return k_acc<GT, VEC, kLoopStart, NT, EXT>;
+    case kFold: return k_acc<GT, VEC, kFold, NT, EXT>;
+    case kAlg1: return k_acc<GT, VEC, kAlg1, NT, EXT>;
   }
   return nullptr;
 }
@@ -146,28 +148,40 @@ bool tile_shape_supported(TileShape s) {
 
 int launch_tile(int xdt, int gdt, Phase phase, TileShape shape, const StepArgs& a, uint32_t n_work,
                 uint32_t lds_bytes, void* stream) {
+  // A handle with more than 64 rows or sources keeps its pointer tables in device memory and runs kernels
+  // compiled for that (kernels of their own, so that the small handles' register budget is not theirs).
   KernelFn fn = nullptr;
-  const bool nt = shape.nontemporal;
-  if (xdt == DADAM_F32 && gdt == DADAM_F32) fn = nt ? tile_kernel_f32_f32_nt(phase, shape) : tile_kernel_f32_f32(phase, shape);
-  if (xdt == DADAM_BF16 && gdt == DADAM_BF16) fn = nt ? tile_kernel_bf16_bf16_nt(phase, shape) : tile_kernel_bf16_bf16(phase, shape);
-  if (xdt == DADAM_BF16 && gdt == DADAM_F32) fn = nt ? tile_kernel_bf16_f32_nt(phase, shape) : tile_kernel_bf16_f32(phase, shape);
-  if (xdt == DADAM_F32 && gdt == DADAM_BF16) fn = nt ? tile_kernel_f32_bf16_nt(phase, shape) : tile_kernel_f32_bf16(phase, shape);
+  const bool nt = shape.nontemporal, ext = a.ext != nullptr;
+#define DADAM_PICK(name) (ext ? (nt ? tile_kernel_##name##_nt_ext(phase, shape) : tile_kernel_##name##_ext(phase, shape)) \
+                              : (nt ? tile_kernel_##name##_nt(phase, shape) : tile_kernel_##name(phase, shape)))
+  if (xdt == DADAM_F32 && gdt == DADAM_F32) fn = DADAM_PICK(f32_f32);
+  if (xdt == DADAM_BF16 && gdt == DADAM_BF16) fn = DADAM_PICK(bf16_bf16);
+  if (xdt == DADAM_BF16 && gdt == DADAM_F32) fn = DADAM_PICK(bf16_f32);
+  if (xdt == DADAM_F32 && gdt == DADAM_BF16) fn = DADAM_PICK(f32_bf16);
+#undef DADAM_PICK
   return launch(fn, n_work, (uint32_t)(kWave * shape.waves), lds_bytes, a, stream);
 }
 
 int launch_direct(int xdt, int gdt, Phase phase, bool nt, const StepArgs& a, uint32_t n_work_tiles, void* stream) {
   KernelFn fn = nullptr;
-  if (xdt == DADAM_F32 && gdt == DADAM_F32) fn = nt ? direct_kernel_f32_f32_nt(phase) : direct_kernel_f32_f32(phase);
-  if (xdt == DADAM_BF16 && gdt == DADAM_BF16) fn = nt ? direct_kernel_bf16_bf16_nt(phase) : direct_kernel_bf16_bf16(phase);
-  if (xdt == DADAM_BF16 && gdt == DADAM_F32) fn = nt ? direct_kernel_bf16_f32_nt(phase) : direct_kernel_bf16_f32(phase);
-  if (xdt == DADAM_F32 && gdt == DADAM_BF16) fn = nt ? direct_kernel_f32_bf16_nt(phase) : direct_kernel_f32_bf16(phase);
+  const bool ext = a.ext != nullptr;
+#define DADAM_PICK(name) (ext ? (nt ? direct_kernel_##name##_nt_ext(phase) : direct_kernel_##name##_ext(phase)) \
+                              : (nt ? direct_kernel_##name##_nt(phase) : direct_kernel_##name(phase)))
+  if (xdt == DADAM_F32 && gdt == DADAM_F32) fn = DADAM_PICK(f32_f32);
+  if (xdt == DADAM_BF16 && gdt == DADAM_BF16) fn = DADAM_PICK(bf16_bf16);
+  if (xdt == DADAM_BF16 && gdt == DADAM_F32) fn = DADAM_PICK(bf16_f32);
+  if (xdt == DADAM_F32 && gdt == DADAM_BF16) fn = DADAM_PICK(f32_bf16);
+#undef DADAM_PICK
   return launch(fn, n_work_tiles * a.n_rows, kDirectThreads, 0, a, stream);
 }
 
 int launch_accumulate(int gdt, Phase phase, bool nt, const StepArgs& a, uint32_t n_work_tiles, void* stream,
                       int vec) {
   KernelFn fn = nullptr;
-#define DADAM_PICK(GT, VEC) (nt ? acc_kernel_for_phase<GT, VEC, true>(phase) : acc_kernel_for_phase<GT, VEC, false>(phase))
+  const bool ext = a.ext != nullptr;
+#define DADAM_PICK(GT, VEC)                                                                                      \
+  (ext ? (nt ? acc_kernel_for_phase<GT, VEC, true, true>(phase) : acc_kernel_for_phase<GT, VEC, false, true>(phase)) \
+       : (nt ? acc_kernel_for_phase<GT, VEC, true, false>(phase) : acc_kernel_for_phase<GT, VEC, false, false>(phase)))
   if (gdt == DADAM_F32 && vec == 4) fn = DADAM_PICK(TF32, 4);
   if (gdt == DADAM_F32 && vec == 8) fn = DADAM_PICK(TF32, 8);
   if (gdt == DADAM_BF16 && vec == 4) fn = DADAM_PICK(TBF16, 4);

@@ -20,7 +20,7 @@ def readlanes_of_loads_under_narrowed_exec(asm_path, kernel_re=r"^(_ZN5dadam[A-Z
         name = m.group(1)
         j = i + 1
         body = []
-        while j < len(lines) and "s_endpgm" not in lines[j]:
+        while j < len(lines) and not lines[j].startswith(".Lfunc_end"):      # not s_endpgm: there may be several exits
             body.append(lines[j]); j += 1
         # split into blocks
         blocks, order, cur = {}, [], "__entry"
@@ -45,6 +45,7 @@ def readlanes_of_loads_under_narrowed_exec(asm_path, kernel_re=r"^(_ZN5dadam[A-Z
             stack = list(stack); loads = dict(loads)
             succ = []
             fall = True
+            snapshot = lambda: (tuple(stack), tuple(sorted(loads.items())))
             for t in blocks[b]:
                 m1 = re.match(r"s_and_saveexec_b64 (s\[\d+:\d+\])", t)
                 m0 = re.match(r"s_(or|andn2)_saveexec_b64 (s\[\d+:\d+\]), (s\[\d+:\d+\])", t)
@@ -63,8 +64,8 @@ def readlanes_of_loads_under_narrowed_exec(asm_path, kernel_re=r"^(_ZN5dadam[A-Z
                     stack.append(m0.group(2))
                 elif m2:
                     if m2.group(1) in stack: del stack[stack.index(m2.group(1)):]
-                elif m3: succ.append(m3.group(1))
-                elif m4: succ.append(m4.group(1)); fall = False
+                elif m3: succ.append((m3.group(1), snapshot()))        # the state at the branch, not at the block's end
+                elif m4: succ.append((m4.group(1), snapshot())); fall = False
                 elif m5: loads[m5.group(1)] = len(stack)
                 elif m6:
                     if m6.group(1) in loads:
@@ -75,9 +76,8 @@ def readlanes_of_loads_under_narrowed_exec(asm_path, kernel_re=r"^(_ZN5dadam[A-Z
                 elif m8 and not t.startswith(("global_store", "buffer_store", "ds_write", "v_cmp", "v_readfirstlane")):
                     regs = [m8.group(1)] if m8.group(2) is None else [f"v{k}" for k in range(int(m8.group(2)), int(m8.group(3)) + 1)]
                     for r in regs: loads.pop(r, None)
-            if fall and nxt[b]: succ.append(nxt[b])
-            out = (tuple(stack), tuple(sorted(loads.items())))
-            for s_ in succ:
+            if fall and nxt[b]: succ.append((nxt[b], snapshot()))
+            for s_, out in succ:
                 if s_ not in blocks: continue
                 if s_ not in state_in:
                     state_in[s_] = out; work.append(s_)
@@ -99,3 +99,25 @@ def readlanes_of_loads_under_narrowed_exec(asm_path, kernel_re=r"^(_ZN5dadam[A-Z
             if d > 0: bad.append(name)
         i = j
     return checked, bad
+
+
+def streaming_hints(asm_path):
+    """Per kernel of the library: (wide stores with the non-temporal hint, wide stores without, wide loads
+    with, wide loads without), wide = 8 or 16 bytes per lane, keyed by mangled kernel name."""
+    out, name = {}, None
+    for l in open(asm_path):
+        m = re.match(r"^(_ZN5dadam\w+):", l)
+        if m:
+            name = m.group(1)
+            out[name] = [0, 0, 0, 0]
+            continue
+        if name is None:
+            continue
+        t = l.split(";")[0].strip()
+        if re.match(r"global_store_dwordx[24]\b", t):
+            out[name][0 if " nt" in t else 1] += 1
+        elif re.match(r"global_load_dwordx[24]\b", t):
+            out[name][2 if " nt" in t else 3] += 1
+        elif l.startswith(".Lfunc_end"):          # not s_endpgm: a kernel may have several exits
+            name = None
+    return out

@@ -346,7 +346,7 @@ def test_spread_offsets_properties():
 
 
 def test_kernels_use_no_scratch_memory_and_load_neighbour_lists_with_all_lanes(tmp_path):
-    """Four properties of the compiled device code, read from the compiler's own output.
+    """Five properties of the compiled device code, read from the compiler's own output.
 
     (1) Every kernel keeps its state in registers: a struct copied to private memory once cost 8 %
     of the step's bandwidth without any test noticing (resource-usage remarks, scratch size 0).
@@ -398,6 +398,32 @@ def test_kernels_use_no_scratch_memory_and_load_neighbour_lists_with_all_lanes(t
     assert not re.search(r"^\s*flat_(load|store|atomic)", asm_text, flags=re.M), "flat memory instructions in the kernels"
 
     import asm_checks
+    # (5) kernels built for streaming carry the non-temporal hint on every vector store and on the vector loads
+    # of sources, gradients and state (the few plain ones read the neighbour-list bounds, the segment table
+    # and, in the kernels of large handles, the pointer tables).  The hint is metadata the optimiser may drop when it re-creates an access: a loop that ran once
+    # around the stores of the one-vector bfloat16 tile kernels lost it, and 1.2 % of the step with it.
+    hints = asm_checks.streaming_hints(str(asm))
+    import subprocess as sp
+    names = sorted(hints)
+    plain_names = sp.run(["c++filt"], input="\n".join(names), capture_output=True, text=True).stdout.split("\n")
+    streaming, other = 0, 0
+    for mangled, plain in zip(names, plain_names):
+        st_nt, st_plain, ld_nt, ld_plain = hints[mangled]
+        m = re.search(r"\b(k_tile|k_direct|k_acc)<(.*)>\(", plain)
+        if not m:
+            continue
+        targs = [x.strip() for x in m.group(2).split(",")]
+        nt, ext = targs[-2] == "true", targs[-1] == "true"     # <..., non-temporal, tables in device memory>
+        if nt:
+            streaming += 1
+            assert st_plain == 0 and st_nt > 0, f"{plain}: {st_plain} vector stores without the hint"
+            assert ld_plain <= (60 if ext else 8) and ld_nt >= (1 if ext else 4) * ld_plain, \
+                f"{plain}: {ld_plain} vector loads without the hint, {ld_nt} with"
+        else:
+            other += 1
+            assert st_nt == 0 and ld_nt == 0, f"{plain}: hints in a kernel built without them"
+    assert streaming > 150 and other > 150, (streaming, other)
+
     checked, bad = asm_checks.readlanes_of_loads_under_narrowed_exec(str(asm))
     assert checked > 1000, "no readlane of a loaded register found in the direct kernels"
     assert not bad, f"neighbour list loaded under a narrowed exec mask in {len(set(bad))} kernels, e.g. {bad[0]}"
