@@ -330,16 +330,26 @@ def test_literal_beta1_fold_selectable():
 # full-size configurations in the benchmark's launch configuration, sampled coordinates
 # ---------------------------------------------------------------------------------------------
 
-def sample_coordinates(layout, rng, n_random):
+def sample_coordinates(layout, rng, n_random, info):
+    """The coordinates the full-size tests check: the first and last 4096, 64 either side of every tensor
+    boundary, of the boundaries between the dies' shares of the tiles and of 1024 randomly chosen tile
+    boundaries of each kernel's grid, and n_random seeded uniform ones."""
     d = layout.d
     pick = [np.arange(0, min(4096, d)), np.arange(max(0, d - 4096), d)]
+    near = lambda edge: np.arange(max(0, edge - 64), min(d, edge + 64))
     for o, n in zip(layout.offsets, layout.numels):
         for edge in (int(o), int(o) + int(n)):
-            pick.append(np.arange(max(0, edge - 64), min(d, edge + 64)))
+            pick.append(near(edge))
+    for tile, n_tiles in ((int(info.tile_elems), int(info.n_tiles_tile)), (int(info.direct_elems), int(info.n_tiles_direct)),
+                          (int(info.mix_tile_elems), int(info.n_tiles_mix))):
+        if tile == 0 or n_tiles < 2:
+            continue
+        share = n_tiles // int(info.n_xcds)
+        for k in range(1, int(info.n_xcds)):
+            pick.append(near(k * share * tile))
+        for b in rng.integers(1, n_tiles, size=1024):
+            pick.append(near(int(b) * tile))
     pick.append(rng.integers(0, d, size=n_random))
-    # both sides of randomly chosen tile boundaries of the kernels (multiples of 256 elements)
-    tiles = rng.integers(1, max(2, d // 256), size=2048) * 256
-    pick.append(np.concatenate([tiles + k for k in (-2, -1, 0, 1)]).clip(0, d - 1))
     return np.unique(np.concatenate(pick))
 
 
@@ -355,7 +365,9 @@ def test_full_size_configs_sampled(cfg):
     sim = H.GpuSim(wl.n_rows, wl.n_cols, layout, hp, csrs, wl.param_dtype, wl.grad_dtype, inplace=(cfg == 3), pad_fill=None,
                    spread=True)     # the layout bench.py times
     rng = np.random.default_rng(cfg)
-    idx_np = sample_coordinates(layout, rng, 1 << (16 if wl.n_rows >= 16 else 18))
+    # 2^20 random coordinates per row (2^18 with 64 rows: the same 2^24 values a step, the oracle's minute)
+    idx_np = sample_coordinates(layout, rng, 1 << (18 if wl.n_rows > 16 else 20), B.dadam_get_plan_info(sim.h))
+    say("coordinates checked per row", len(idx_np))
     idx = torch.from_numpy(idx_np).to(dev)
     x0 = WL.normal_torch(WL.seed_for(cfg, 0), (layout.d,), wl.param_std, dev, H.TORCH_DT[wl.param_dtype])
     for c in range(wl.n_rows):
@@ -363,9 +375,11 @@ def test_full_size_configs_sampled(cfg):
         # replicas start equal (Algorithm 1 line 1); perturb so that mixing is visible at once
         sim.x_src[c].add_(WL.normal_torch(WL.seed_for(cfg, 500 + c), (layout.d,), 1e-3, dev, H.TORCH_DT[wl.param_dtype]))
     del x0
-    T = wl.s + 1
+    T = wl.steps                                   # the configuration's own number of iterations
     grads = [torch.empty(layout.d, dtype=H.TORCH_DT[wl.grad_dtype], device=dev) for _ in range(wl.n_rows)]
     gen = torch.Generator(device=dev)
+    import time
+    started = time.time()
     for t in range(1, T + 1):
         for c in range(wl.n_rows, wl.n_cols):
             sim.x_src[c].copy_(WL.normal_torch(WL.seed_for(cfg, 1) + 7 * t + c, (layout.d,), wl.param_std, dev, H.TORCH_DT[wl.param_dtype]))
@@ -385,7 +399,7 @@ def test_full_size_configs_sampled(cfg):
         csr = H.csr_oracle(csrs[slot])
         ref_x = O.dadam_step(ref_state, g64, csr, t, ohp, "O32m", wl.param_dtype)
         w = H.compare_step(prev, ref_x, ref_state, got, g64, csr, t, ohp, wl.param_dtype, None, f"{wl.name} t={t}")
-        say(f"t={t} worst error / tolerance: {w}")
+        say(f"t={t} ({time.time() - started:.0f} s) worst error / tolerance: {w}")
         H.assert_within(w, f"{wl.name} full size t={t}")
         sim.swap()
     # a property that holds at any size: with a doubly stochastic W the replica mean moves only
