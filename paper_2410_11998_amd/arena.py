@@ -4,24 +4,28 @@ On MI355X a streaming step that touches many arrays at once sustains about 0.65 
 bandwidth when those arrays all lie inside one third (96 GiB) of the device's physical memory -
 where a fresh process's consecutive allocations land - and 0.78-0.79 when half of them lie in one
 third and half in another (measured; which arrays does not matter as long as every group that is
-streamed together is split).  Nobody outside the driver sees physical addresses.  A large allocation
-is pieced together from whatever is free, emptiest third first: made first, its bytes [0, 96 GiB)
-lie in one third and [96, 192 GiB) in the next; made after 100 GiB of other allocations, the second
-boundary was seen at 160 GiB and, for a smaller arena, at 128 GiB.  What can be done is to MEASURE: a mixing pass over sixteen 64 MiB buffers runs at 0.79 of peak when half of them sit in
-one third and half in another, and at 0.65-0.73 when all sit in the same third (0.34 against
-0.37-0.41 ms, repeatable to 1 %), so timing that pass over pairs of 1 GiB chunks of an arena tells
-which chunks share a third.
+streamed together is split).  Nobody outside the driver sees physical addresses.  A large
+allocation is pieced together from whatever is free, emptiest third first: made first, its bytes
+[0, 96 GiB) lie in one third and [96, 192 GiB) in the next; made after 100 GiB of other
+allocations, the second boundary was seen at 160 GiB and, for a smaller arena, at 128 GiB.
 
-``SpreadArena`` makes ONE allocation (by default: free memory minus ``keep_free_bytes``), finds the
-thirds inside it that way (``calibrate=True``, a few hundred milliseconds, before anything is stored
-in the arena), and deals the buffers alternately over the two largest stretches that lie in
-different thirds (``dadam_deal_offsets``): buffers 0, 2, 4, ... in one, 1, 3, 5, ... in the other, so
+What can be done is to MEASURE.  A mixing pass over sixteen 64 MiB sources and outputs runs at
+0.78-0.80 of peak when half of its buffers sit in one third and half in another, and at 0.61-0.73
+when all sit in the same third, repeatable to 1 %: timing that pass over pairs of 1 GiB chunks of
+an arena tells which chunks share a third.
+
+``SpreadArena`` makes ONE allocation (by default: free memory minus ``keep_free_bytes``) and, before
+anything is stored in it (``calibrate=True``, about half a second): finds the stretches of it that
+lie in different thirds; deals the buffers over the two of them with the most room
+(``dadam_deal_offsets``: alternately, buffers 0, 2, 4, ... in one and 1, 3, 5, ... in the other, so
 that any run of consecutive buffers - all sources, all outputs, one kind of state - is split
-evenly.  The space between the buffers stays untouched and can be handed out as views for
-anything else.  This works whatever was allocated before, as long as the arena reaches into two
-thirds with room for half of the buffers in each; otherwise (or with ``calibrate=False``) the
-library's rule for an arena over the whole device applies (``dadam_place_offsets``), which falls
-back to equal distances over whatever arena there is; ``advice`` / ``policy`` say what was done.
+evenly; or every 3rd ... 8th buffer in a second stretch that is too small for half of them); and
+confirms the choice with one more pass across the two regions and one inside each.  ``policy``,
+``advice`` and ``describe()`` say what was done and what the probe measured.  If the probe finds
+nothing usable, or with ``calibrate=False``, the library's rule for an allocation that covers the
+device applies (``dadam_place_offsets``), which falls back to equal distances when the arena does
+not cover the device.  The space between the buffers stays untouched
+and can be handed out as views for anything else.
 Memory management only - nothing of the method is computed here.
 """
 
@@ -67,8 +71,14 @@ class ThirdsProbe:
     def rate(self, off_a: int, off_b: int, reps: int = 6) -> float:
         """Fraction of the HBM peak the pass sustains with half of its buffers at off_a and half at off_b."""
         nb, half = PROBE_ELEMS * 4, PROBE_ROWS // 2
-        xs = [self._view(off_a + k * nb) for k in range(half)] + [self._view(off_b + k * nb) for k in range(half)]
-        xd = [self._view(off_a + (half + k) * nb) for k in range(half)] + [self._view(off_b + (half + k) * nb) for k in range(half)]
+        return self.rate_of_layout([off_a + k * nb for k in range(half)] + [off_b + k * nb for k in range(half)] +
+                                   [off_a + (half + k) * nb for k in range(half)] + [off_b + (half + k) * nb for k in range(half)], reps)
+
+    def rate_of_layout(self, offsets: Sequence[int], reps: int = 6) -> float:
+        """The same for any placement of the pass's buffers: offsets of its 16 sources, then of its 16 outputs."""
+        xs = [self._view(o) for o in offsets[:PROBE_ROWS]]
+        xd = [self._view(o) for o in offsets[PROBE_ROWS:]]
+        nb = PROBE_ELEMS * 4
         B.dadam_bind(self.h, xs, xd, self.state[:PROBE_ROWS], self.state[PROBE_ROWS:], None)
         st = B.current_stream()
         for _ in range(2):
@@ -94,10 +104,10 @@ def stretches_in_different_thirds(span_bytes: int, rate, attempts: int = 2) -> L
     fraction of peak a streaming pass sustains over the chunks at those offsets.  Chunks every PROBE_STEP bytes
     are compared with a reference chunk; those that run fast with it (>= 0.95 of the fastest pairing, which
     itself must reach 0.75 of peak; measured: 0.78-0.80 across thirds, 0.61-0.73 inside one) lie in another
-    third.  A second reference taken from those separates the other two thirds.  An answer with more than
-    three stretches, or with two stretches of one third, is not believed: the timing is repeated, and an empty
-    list returned if that does not help.  Pure bookkeeping around the timings (tested on the CPU with a model
-    of the memory)."""
+    third.  A second reference taken from those separates the other two thirds.  The same third may come
+    back later in the arena (the driver pieces a large allocation together from what is free), but an answer
+    with more than six stretches is noise: the timing is repeated, and an empty list returned if that does
+    not help.  Pure bookkeeping around the timings (tested on the CPU with a model of the memory)."""
     offs = list(range(0, span_bytes - PROBE_CHUNK + 1, PROBE_STEP))
     if len(offs) < 3:
         return []
@@ -131,16 +141,17 @@ def stretches_in_different_thirds(span_bytes: int, rate, attempts: int = 2) -> L
             # that were classified alike on both sides
             runs.append((third[k], offs[k], offs[j] + PROBE_CHUNK))
             k = j + 1
-        if len(runs) <= 3 and len({t for t, _lo, _hi in runs}) == len(runs):
+        if len(runs) <= 6:
             return runs
     return []
 
 
-def two_regions_from_stretches(runs: Sequence[Tuple[int, int, int]], nbytes: Sequence[int]):
-    """The two regions to deal buffers over, and how: ((lo0, hi0), (lo1, hi1), every) for dadam_deal_offsets,
-    or None.  Alternate dealing (every = 2) over the two stretches of different thirds with the most room if
-    half of the buffers fit each; otherwise every 3rd, 4th, 6th or 8th buffer goes to the smaller stretch.  A
-    region is cut down to max(64 GiB, 1.2 x what it holds), at the end of its stretch nearest the other one."""
+def region_candidates(runs: Sequence[Tuple[int, int, int]], nbytes: Sequence[int]):
+    """Ways to deal the buffers over two stretches of different thirds: a list of ((lo0, hi0), (lo1, hi1), every)
+    for dadam_deal_offsets, at most one per `every` (2: alternately; 3, 4, 6, 8: every 3rd ... 8th buffer goes
+    to the smaller stretch), each over the two stretches with the most room that hold their shares.  A region
+    is cut down to max(64 GiB, 1.2 x what it holds), at the end of its stretch nearest the other one."""
+    out = []
     for every in (2, 3, 4, 6, 8):
         minor = sum(_round_up(n) for k, n in enumerate(nbytes) if k % every == every - 1)
         major = sum(_round_up(n) for n in nbytes) - minor
@@ -158,9 +169,16 @@ def two_regions_from_stretches(runs: Sequence[Tuple[int, int, int]], nbytes: Seq
         wa = min(a[2] - a[1], max(64 * GIB, _round_up(major * 6 // 5)))
         wb = min(b[2] - b[1], max(64 * GIB, _round_up(minor * 6 // 5)))
         if a[1] < b[1]:
-            return (a[2] - wa, a[2]), (b[1], b[1] + wb), every
-        return (a[1], a[1] + wa), (b[2] - wb, b[2]), every
-    return None
+            out.append(((a[2] - wa, a[2]), (b[1], b[1] + wb), every))
+        else:
+            out.append(((a[1], a[1] + wa), (b[2] - wb, b[2]), every))
+    return out
+
+
+def two_regions_from_stretches(runs: Sequence[Tuple[int, int, int]], nbytes: Sequence[int]):
+    """The first of region_candidates (the most even deal that fits), or None."""
+    found = region_candidates(runs, nbytes)
+    return found[0] if found else None
 
 
 class SpreadArena:
@@ -192,6 +210,8 @@ class SpreadArena:
         self.span_bytes = span_bytes
         self.advice = 0
         self.probe_launches = 0                   # mixing passes launched by the timing probe (profiles set them apart)
+        self.probe_note = ""                      # what the probe could not tell, if anything
+        self.probe_rates = ""                     # what its pass sustained under each candidate placement
         self.stretches: List[Tuple[int, int, int]] = []
         placed = None
         if offsets is not None:
@@ -204,24 +224,10 @@ class SpreadArena:
                 probe = None                      # no room for the probe's 2 GiB of state: fall through to the rule
             if probe is not None:
                 try:
-                    self.stretches = stretches_in_different_thirds(span_bytes // UNIT * UNIT, probe.rate)
-                    found = two_regions_from_stretches(self.stretches, self.nbytes)
-                    if found is not None:
-                        # believed only if a pass over the two regions' far ends runs at the two-thirds level and a
-                        # pass inside each region does not
-                        (lo0, hi0), (lo1, hi1), every = found
-                        ends = [(lo, max(lo, (hi - PROBE_CHUNK) // UNIT * UNIT)) for lo, hi in ((lo0, hi0), (lo1, hi1))]
-                        across = probe.rate(ends[0][0] if lo0 < lo1 else ends[0][1], ends[1][1] if lo0 < lo1 else ends[1][0])
-                        inside = [probe.rate(lo, hi) for lo, hi in ends if hi - lo >= PROBE_CHUNK]
-                        if across < 0.75 or any(r >= 0.95 * across for r in inside):
-                            found = None
+                    placed = self._place_by_timing(probe, span_bytes, total)
                 finally:
                     self.probe_launches = probe.launches
                     probe.close()
-                if found is not None:
-                    placed = B.dadam_deal_offsets(self.nbytes, found[0], found[1], every)
-                    self.regions_used, self.advice = [found[0], found[1]], B.DADAM_PLACE_TWO_REGIONS
-                    self.policy = "two regions found by timing" + ("" if every == 2 else f" (every {every}th buffer in the second)")
         if placed is None and two_regions:
             placed, self.regions_used, self.advice = B.dadam_place_offsets(self.nbytes, span_bytes, total)
             self.policy = {B.DADAM_PLACE_TWO_REGIONS: "two regions across the first boundary (whole-device rule)",
@@ -237,12 +243,47 @@ class SpreadArena:
             if k:
                 assert o >= taken[k - 1][0] + taken[k - 1][1], "buffers overlap"
 
+    def _place_by_timing(self, probe: "ThirdsProbe", span_bytes: int, total: int):
+        """Finds the stretches of the arena that lie in different thirds and deals the buffers over the two
+        with the most room, as evenly as they allow; the choice is kept only if one more pass across the two
+        regions runs at the two-thirds level and a pass inside each does not.  Returns the offsets, or None
+        (then ``probe_note`` says why and the caller falls back to the library's rule).
+
+        (Timing the probe's own pass with its buffers laid out like each candidate placement - dealt, by the
+        rule, at equal distances - and taking the fastest was tried and does not work: 32 buffers of one pass
+        are no model of 100 arrays streamed at once; it preferred equal distances at 0.80 on the probe where
+        the step then ran at 0.60-0.66.  Against equal distances an uneven deal won every matched comparison:
+        0.75 / 0.73 / 0.70 against 0.60 / 0.64 / 0.62 with 160 / 200 / 180 GiB allocated first.)"""
+        self.stretches = stretches_in_different_thirds(span_bytes // UNIT * UNIT, probe.rate)
+        if not self.stretches:
+            self.probe_note = "timing probe: no consistent picture of the thirds"
+            return None
+        found = two_regions_from_stretches(self.stretches, self.nbytes)
+        if found is None:
+            self.probe_note = "timing probe: no two stretches in different thirds hold the buffers"
+            return None
+        (lo0, hi0), (lo1, hi1), every = found
+        ends = [(lo, max(lo, (hi - PROBE_CHUNK) // UNIT * UNIT)) for lo, hi in ((lo0, hi0), (lo1, hi1))]
+        across = probe.rate(ends[0][0] if lo0 < lo1 else ends[0][1], ends[1][1] if lo0 < lo1 else ends[1][0])
+        inside = [probe.rate(lo, hi) for lo, hi in ends if hi - lo >= PROBE_CHUNK]
+        self.probe_rates = f"probe pass: {across:.3f} of peak across the regions, " + ", ".join(f"{r:.3f}" for r in inside) + " inside"
+        if across < 0.75 or any(r >= 0.95 * across for r in inside):
+            self.probe_note = "timing probe: regions not confirmed"
+            return None
+        self.regions_used, self.advice = [found[0], found[1]], B.DADAM_PLACE_TWO_REGIONS
+        self.policy = "two regions found by timing" + ("" if every == 2 else f" (every {every}th buffer in the second)")
+        return B.dadam_deal_offsets(self.nbytes, found[0], found[1], every)
+
     def describe(self) -> str:
         gib = lambda v: f"{v / GIB:.1f}"
         regs = " + ".join(f"[{gib(lo)}, {gib(hi)})" for lo, hi in self.regions_used)
         found = ""
         if self.stretches:
             found = "; thirds seen at " + ", ".join(f"[{gib(lo)}, {gib(hi)})" for _t, lo, hi in self.stretches)
+        if self.probe_note:
+            found += f"; {self.probe_note}"
+        if self.probe_rates:
+            found += f"; {self.probe_rates}"
         return (f"{self.policy}: {regs} GiB of a {gib(self.span_bytes)} GiB allocation made with "
                 f"{gib(self.in_use_before)} GiB in use{found}")
 

@@ -473,11 +473,12 @@ def test_arena_finds_stretches_in_different_thirds_by_timing():
         say("layout", ar.describe())
         H.record("arena_calibration", dict(first_gib=first_gib, stretches=[[t, lo >> 30, hi >> 30] for t, lo, hi in ar.stretches],
                                            regions=[[lo >> 30, hi >> 30] for lo, hi in ar.regions_used], policy=ar.policy))
-        assert len(ar.stretches) >= 2 and len({t for t, _lo, _hi in ar.stretches}) == len(ar.stretches)
-        assert ar.policy == "two regions found by timing" and ar.advice == B.DADAM_PLACE_TWO_REGIONS
-        owner = lambda off: next(t for t, lo, hi in ar.stretches if lo <= off < hi)
+        assert len(ar.stretches) >= 2 and len({t for t, _lo, _hi in ar.stretches}) >= 2
+        assert ar.policy.startswith("two regions found by timing") and ar.advice == B.DADAM_PLACE_TWO_REGIONS and ar.probe_rates
         (lo0, hi0), (lo1, hi1) = ar.regions_used
-        assert owner(lo0) == owner(hi0 - 1) != owner(lo1) == owner(hi1 - 1)
+        if ar.policy.startswith("two regions found by timing"):
+            owner = lambda off: next(t for t, lo, hi in ar.stretches if lo <= off < hi)
+            assert owner(lo0) == owner(hi0 - 1) != owner(lo1) == owner(hi1 - 1)
         for k, (o, n) in enumerate(zip(ar.offsets, sizes)):
             lo, hi = ar.regions_used[k % 2]
             assert lo <= o and o + n <= hi

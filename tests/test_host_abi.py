@@ -647,6 +647,8 @@ def test_thirds_are_found_from_timings_of_a_modelled_memory():
         firsts = {third_of(lo, base) for _t, lo, _hi in runs}
         assert len(runs) == len(firsts) == third_of(span - A.PROBE_CHUNK, base) - third_of(0, base) + 1, (base_gib, runs)
         assert len({t for t, _lo, _hi in runs}) == len(runs)
+        cands = A.region_candidates(runs, sizes)
+        assert [c[2] for c in cands] == sorted({c[2] for c in cands}) and (not cands or cands[0] == A.two_regions_from_stretches(runs, sizes))
         found = A.two_regions_from_stretches(runs, sizes)
         room = sorted(hi - lo for _t, lo, hi in runs)
         if len(runs) >= 2 and room[-1] >= sum(sizes) * 7 // 8 + (1 << 30) and room[-2] >= sum(sizes) // 8 + (1 << 30):
@@ -672,6 +674,12 @@ def test_thirds_are_found_from_timings_of_a_modelled_memory():
     # timings that make no sense (a fast pairing here and there): nothing is believed
     noisy = np.random.default_rng(1)
     assert A.stretches_in_different_thirds(200 * GIB, lambda a, b: 0.79 if noisy.uniform() < 0.5 else 0.65) == []
+    # a third that comes back later in the arena (an allocation pieced together from fragments) is accepted
+    def fragments(a, b):
+        piece = lambda off: 0 if off < 40 * GIB else 1 if off < 90 * GIB else 0
+        return 0.79 if piece(a) != piece(b) else 0.66
+    runs = A.stretches_in_different_thirds(130 * GIB, fragments)
+    assert [t for t, _lo, _hi in runs] == [0, 1, 0] and A.two_regions_from_stretches(runs, sizes) is not None
 
 
 def test_device_access_helpers_on_the_cpu_under_sanitizers(tmp_path):
