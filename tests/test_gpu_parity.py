@@ -918,15 +918,23 @@ def dyadic_case(rng, n, d):
     return u, x0, m_hat, v_hat, grads
 
 
+def dyadic_rows(n, offsets, weights):
+    """CSR rows i <- {(i + o) mod n} with the given (dyadic) weights."""
+    k = len(offsets)
+    col = np.array([(i + o) % n for i in range(n) for o in offsets], np.int32)
+    return np.arange(0, k * n + 1, k, dtype=np.int32), col, np.array(list(weights) * n, np.float32)
+
+
 @pytest.mark.parametrize("mode", ["tile", "direct"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_dyadic_inputs_give_the_oracles_bits(mode, dtype):
+@pytest.mark.parametrize("n", [4, 68])
+def test_dyadic_inputs_give_the_oracles_bits(mode, dtype, n):
     """Sums of two, three and four neighbours with weights 1/2 and 1/4, the moment and update arithmetic,
     accumulation, fold and the bfloat16 store (round to nearest even, ties included) on inputs where
     nothing is rounded before the final store: the device's bits must equal the oracle's, for every
     element of a ragged layout, over a whole accumulation loop that ends in a fold."""
-    say("case", mode, dtype)
-    n, s = 4, 4
+    say("case", mode, dtype, n)
+    s = 4
     layout = WL.pack(WL.odd_shapes() + [("big", (60001,))])
     d = layout.d
     rng = np.random.default_rng(99)
@@ -937,6 +945,9 @@ def test_dyadic_inputs_give_the_oracles_bits(mode, dtype):
     rows = (np.array([0, 3, 6, 9, 12], np.int32), np.array([0, 1, 2, 1, 2, 3, 2, 3, 0, 3, 0, 1], np.int32),
             np.array([half, quarter, quarter] * 4, np.float32))                       # 1/2 self, 1/4 to two neighbours
     csrs = [WL.one_peer_exponential(n, 0), WL.complete(n), rows, WL.one_peer_exponential(n, 1)]
+    if n != 4:      # the same degrees and weights for any number of replicas (68: the kernels of large handles)
+        csrs = [dyadic_rows(n, (0, 1), (half, half)), dyadic_rows(n, (0, 1, 2, 3), (quarter,) * 4),
+                dyadic_rows(n, (0, 1, 2), (half, quarter, quarter)), dyadic_rows(n, (0, 2), (half, half))]
     sim = H.GpuSim(n, n, layout, hp, csrs, dtype, dtype, pad_fill=None)
     dev = torch.device(DEV)
     for i in range(n):
