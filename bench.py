@@ -152,10 +152,13 @@ def host_cpu():
     return model, n
 
 
-def kernel_name(info, tile_mode: bool, wl, path: str) -> str:
-    """Name of the kernel shape a launch uses, as the profile summaries spell it."""
+def kernel_name(info, tile_mode: bool, wl, path: str, shared: bool = False) -> str:
+    """Name of the kernel shape a launch uses, as the profile summaries spell it (a direct kernel whose rows
+    share sources streams everything but the sources: "shared")."""
     dt = {"f32": "TF32", "bf16": "TBF16"}
     nt = "true" if info.streaming else "false"
+    if not tile_mode and shared and info.streaming:
+        nt = "shared"
     if path in ("mix", "mix_consensus"):
         return f"k_tile<{dt[wl.param_dtype]},{dt[wl.grad_dtype]},{info.mix_waves},{info.mix_vectors},{nt}>" if tile_mode else \
                f"k_direct<{dt[wl.param_dtype]},{dt[wl.grad_dtype]},{nt}>"
@@ -238,6 +241,8 @@ def measure(args, want_cpu_sample: bool):
     flags = B.DADAM_FUSE_ACCUM | {"auto": 0, "tile": B.DADAM_FORCE_TILE, "direct": B.DADAM_FORCE_DIRECT}[args.mode]
     tile_mode = (args.mode == "tile") or (args.mode == "auto" and B.dadam_slot_uses_tile_mode(h, 0))
     info = B.dadam_get_plan_info(h)
+    if args.path == "mix_consensus" and args.mode != "direct" and info.tile_mode_possible:
+        tile_mode = True                                  # the consensus error is a by-product of the staged tile
     tables = [B.grad_table(h, g) for g in pool]          # pointer tables marshalled once, as a training loop would
 
     # sample for the CPU baseline, taken before anything is updated
@@ -413,7 +418,8 @@ def measure(args, want_cpu_sample: bool):
         by_phase.setdefault(p, []).append(ms)
 
     # counter-measured HBM bytes, only for the kernel shape that was profiled
-    kname = kernel_name(info, tile_mode, wl, args.path)
+    import numpy as np
+    kname = kernel_name(info, tile_mode, wl, args.path, shared=bool(np.bincount(csrs[0][1], minlength=C).max() > 1))
     traffic, traffic_source = None, None
     table = measured_traffic().get((wl.name, kname))
     if table is not None and args.path == "fused" and all(p in table for p in phases):

@@ -34,7 +34,7 @@ DADAM_PLACE_TWO_REGIONS, DADAM_PLACE_ARENA_ELSEWHERE, DADAM_PLACE_TOO_LARGE = 1,
 EXPORTS = [
     "dadam_init", "dadam_set_topology", "dadam_bind", "dadam_swap_x", "dadam_gossip_step",
     "dadam_gossip_step_range", "dadam_accumulate", "dadam_mix", "dadam_mix_consensus", "dadam_mix_consensus_static", "dadam_set_lr", "dadam_get_plan_info",
-    "dadam_slot_uses_tile_mode", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_place_offsets", "dadam_deal_offsets",
+    "dadam_slot_uses_tile_mode", "dadam_get_row_order", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_place_offsets", "dadam_deal_offsets",
     "dadam_last_error",
     "dadam_destroy",
 ]
@@ -92,6 +92,7 @@ def _load() -> C.CDLL:
     lib.dadam_spread_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.POINTER(C.c_uint64)]
     lib.dadam_place_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64,
                                         C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
+    lib.dadam_get_row_order.argtypes = [H, C.c_uint32, C.POINTER(C.c_int32)]
     lib.dadam_deal_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64,
                                        C.c_uint32, C.POINTER(C.c_uint64)]
     lib.dadam_last_error.argtypes = [H]
@@ -186,6 +187,15 @@ def dadam_place_offsets(nbytes: Sequence[int], arena_bytes: int, device_total_by
         raise DadamError(rc, f"dadam_place_offsets: {n} buffers of {sum(int(x) for x in nbytes)} bytes do not fit in {arena_bytes}")
     regions = [(int(r[0]), int(r[1]))] + ([(int(r[2]), int(r[3]))] if r[3] else [])
     return [int(x) for x in o], regions, int(adv.value)
+
+
+def dadam_get_row_order(h, slot: int, n_rows: int):
+    """(order, in_use): the order in which direct mode takes the n_rows rows of a slot."""
+    out = (C.c_int32 * int(n_rows))()
+    rc = lib.dadam_get_row_order(h, slot, out)
+    if rc < 0:
+        _check(h, rc)
+    return [int(x) for x in out], bool(rc)
 
 
 def dadam_deal_offsets(nbytes: Sequence[int], region0, region1, every: int = 2):

@@ -646,7 +646,7 @@ __global__ __launch_bounds__(kWave* W) void k_tile(const StepArgs a) {
 constexpr int kUD = 2;  // 16-byte parameter vectors per thread (1 and 4 measured slower)
 
 // Neighbour sum with all loads of DEG sources issued before the first use.  DEG == 0: any degree.
-template <typename XT, int DEG, bool MASKED, bool NT, bool EXT>
+template <typename XT, int DEG, bool MASKED, bool NT, bool EXT>  // NT: hint on the source loads
 __device__ __forceinline__ void mix_direct(const StepArgs& a, RowList rl, int lane,
                                            const uint64_t (&e)[kUD], uint64_t lo, uint64_t hi,
                                            float (&mix)[kUD][XT::vec]) {
@@ -702,9 +702,12 @@ __device__ __forceinline__ void mix_direct(const StepArgs& a, RowList rl, int la
   }
 }
 
-template <typename XT, typename GT, int PHASE, bool MASKED, bool NT, bool EXT>
+// HINT: 0 no streaming hints, 1 on every vector access, 2 on all but the loads of sources (rows share
+// sources: the second reader must find them in the cache, while gradients, state and all stores still stream).
+template <typename XT, typename GT, int PHASE, bool MASKED, int HINT, bool EXT>
 __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t tbase, uint64_t lo,
                                             uint64_t hi, float wd, int lane) {
+  constexpr bool NT = HINT != 0, NTSRC = HINT == 1;
   constexpr int VEC = XT::vec;
   uint64_t e[kUD];
 #pragma unroll
@@ -737,12 +740,12 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
   }
   float mix[kUD][VEC];
   switch (rl.deg) {
-    case 1: mix_direct<XT, 1, MASKED, NT, EXT>(a, rl, lane, e, lo, hi, mix); break;
-    case 2: mix_direct<XT, 2, MASKED, NT, EXT>(a, rl, lane, e, lo, hi, mix); break;
-    case 3: mix_direct<XT, 3, MASKED, NT, EXT>(a, rl, lane, e, lo, hi, mix); break;
-    case 4: mix_direct<XT, 4, MASKED, NT, EXT>(a, rl, lane, e, lo, hi, mix); break;
-    case 5: mix_direct<XT, 5, MASKED, NT, EXT>(a, rl, lane, e, lo, hi, mix); break;
-    default: mix_direct<XT, 0, MASKED, NT, EXT>(a, rl, lane, e, lo, hi, mix); break;
+    case 1: mix_direct<XT, 1, MASKED, NTSRC, EXT>(a, rl, lane, e, lo, hi, mix); break;
+    case 2: mix_direct<XT, 2, MASKED, NTSRC, EXT>(a, rl, lane, e, lo, hi, mix); break;
+    case 3: mix_direct<XT, 3, MASKED, NTSRC, EXT>(a, rl, lane, e, lo, hi, mix); break;
+    case 4: mix_direct<XT, 4, MASKED, NTSRC, EXT>(a, rl, lane, e, lo, hi, mix); break;
+    case 5: mix_direct<XT, 5, MASKED, NTSRC, EXT>(a, rl, lane, e, lo, hi, mix); break;
+    default: mix_direct<XT, 0, MASKED, NTSRC, EXT>(a, rl, lane, e, lo, hi, mix); break;
   }
   // decoupled weight decay acts on the row's own previous parameters: source buffer `row` (the
   // load repeats one the mixing sum has just made, so it is served by the cache)
@@ -787,21 +790,35 @@ __device__ __forceinline__ void direct_body(const StepArgs& a, int row, uint64_t
 
 // Work items are numbered tile-major, row-minor, so that workgroups running at the same time work
 // on the same elements of different rows.
-template <typename XT, typename GT, int PHASE, bool NT, bool EXT>
+template <typename XT, typename GT, int PHASE, int HINT, bool EXT>
 __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
   constexpr int VEC = XT::vec;
   constexpr uint64_t TILE = (uint64_t)kDirectThreads * VEC * kUD;
   const int lane = threadIdx.x & (kWave - 1);
   const uint32_t n_rows = a.n_rows;
-  const uint32_t t = blockIdx.x / n_rows;
-  const int row = (int)(blockIdx.x - t * n_rows);
+  uint32_t t;
+  int row;
+  if (a.row_order != nullptr) {
+    // Rows share sources.  Consecutive workgroup ids go to the device's X dies in turn; die x takes the
+    // rows at positions [x G, (x + 1) G) of the sharing order, G = n_rows / X (the host passes the order
+    // only when that divides), tile after tile: the rows that read a source run on one die at about the
+    // same time, and the second reader finds the source in that die's L2.  (b mod X, b / X) -> (die, tile
+    // and position in the group) is a bijection of the launch's n_tiles * n_rows workgroups.
+    const uint32_t X = a.n_xcd, G = n_rows / X;
+    const uint32_t x = blockIdx.x % X, j = blockIdx.x / X;
+    t = j / G;
+    row = __builtin_amdgcn_readfirstlane(a.row_order[x * G + (j - t * G)]);
+  } else {
+    t = blockIdx.x / n_rows;
+    row = (int)(blockIdx.x - t * n_rows);
+  }
   uint64_t tile_index, lo, hi;
   float wd;
   locate(a, a.work_begin + t, tile_index, lo, hi, wd);
   const uint64_t tbase = tile_index * TILE;
   const bool full = tbase >= lo && tbase + TILE <= hi;
-  if (full) direct_body<XT, GT, PHASE, false, NT, EXT>(a, row, tbase, lo, hi, wd, lane);
-  else direct_body<XT, GT, PHASE, true, NT, EXT>(a, row, tbase, lo, hi, wd, lane);
+  if (full) direct_body<XT, GT, PHASE, false, HINT, EXT>(a, row, tbase, lo, hi, wd, lane);
+  else direct_body<XT, GT, PHASE, true, HINT, EXT>(a, row, tbase, lo, hi, wd, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -912,15 +929,15 @@ KernelFn tile_kernel_for_shape_nt(int phase, TileShape s) {
 #endif
   return nullptr;
 }
-template <typename XT, typename GT, bool NT, bool EXT>
+template <typename XT, typename GT, int HINT, bool EXT>
 KernelFn direct_kernel_for_phase(int phase) {
   switch (phase) {
-    case kMixOnly: return k_direct<XT, GT, kMixOnly, NT, EXT>;
-    case kUpdateOnly: return k_direct<XT, GT, kUpdateOnly, NT, EXT>;
-    case kPlain: return k_direct<XT, GT, kPlain, NT, EXT>;
-    case kLoopStart: return k_direct<XT, GT, kLoopStart, NT, EXT>;
-    case kFold: return k_direct<XT, GT, kFold, NT, EXT>;
-    case kAlg1: return k_direct<XT, GT, kAlg1, NT, EXT>;
+    case kMixOnly: return k_direct<XT, GT, kMixOnly, HINT, EXT>;
+    case kUpdateOnly: return k_direct<XT, GT, kUpdateOnly, HINT, EXT>;
+    case kPlain: return k_direct<XT, GT, kPlain, HINT, EXT>;
+    case kLoopStart: return k_direct<XT, GT, kLoopStart, HINT, EXT>;
+    case kFold: return k_direct<XT, GT, kFold, HINT, EXT>;
+    case kAlg1: return k_direct<XT, GT, kAlg1, HINT, EXT>;
   }
   return nullptr;
 }

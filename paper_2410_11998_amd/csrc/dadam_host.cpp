@@ -30,6 +30,9 @@ struct Slot {
   int32_t* d_row_ptr = nullptr;
   int32_t* d_col = nullptr;
   float* d_w = nullptr;
+  int32_t max_degree = 0;             // longest row
+  std::vector<int32_t> order;         // rows ordered so that neighbours share sources (empty: nothing is shared)
+  int32_t* d_order = nullptr;
   bool reuse = false;                 // some source is read by two or more rows
   std::vector<int32_t> sole_reader;   // per source: the only row reading it, -1 none, -2 several
 };
@@ -258,6 +261,8 @@ void fill_args(const dadam_handle* h, const Slot* slot, const void* const* grads
     a->row_ptr = slot->d_row_ptr;
     a->col = slot->d_col;
     a->w = slot->d_w;
+    // groups of the order go to the dies in turn: only when the rows divide evenly among them
+    if (slot->d_order && h->n_xcds > 1 && R % h->n_xcds == 0) a->row_order = slot->d_order;
   }
   a->seg = h->d_segs;
   a->n_seg = (uint32_t)h->segs.size();
@@ -313,7 +318,14 @@ int choose_mode(const dadam_handle* h, const Slot& slot, uint32_t flags, bool* t
       return fail(h, DADAM_EALIAS, "in-place update of a source that another row reads needs tile mode");
     *tile_mode = false;
   } else {
-    *tile_mode = h->tile_possible && (slot.reuse || !direct_legal);
+    // Shared sources normally mean tile mode.  The exception, measured on 64 replicas of a one-peer graph
+    // (mixing 0.77 against 0.75 of peak, the whole step 0.792 against 0.788): rows of at most two sources over
+    // more sources than the two-vector tile holds stream directly, the dies taking the rows in the sharing
+    // order so that the second reader of a source finds it in its die's L2.  With three sources a row (a
+    // ring) the tile is as fast or faster, so the exception stops at two.
+    const bool pairs_stream = slot.reuse && direct_legal && slot.max_degree <= 2 && h->cfg.n_cols > 16 &&
+                              h->n_xcds > 1 && h->cfg.n_rows % h->n_xcds == 0;
+    *tile_mode = h->tile_possible && ((slot.reuse && !pairs_stream) || !direct_legal);
     if (!*tile_mode && !direct_legal)
       return fail(h, DADAM_EALIAS, "in-place update of a shared source is impossible: tile does not fit in LDS");
   }
@@ -366,6 +378,8 @@ int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint6
         if (!h->acc[i]) return fail(h, DADAM_ESTATE, "accumulator of row %u is not bound", i);
   }
   bool tile_mode = false;
+  // the consensus error is computed from the staged tile: ask for tile mode unless the caller chose
+  if (consensus_out && !(flags & DADAM_FORCE_DIRECT) && h->tile_possible && slot.reuse) flags |= DADAM_FORCE_TILE;
   rc = choose_mode(h, slot, flags, &tile_mode);
   if (rc) return rc;
   if (consensus_out) {
@@ -407,17 +421,51 @@ int step_impl(dadam_handle* h, uint32_t slot_id, const void* const* grads, uint6
                             mix_only ? h->mix_lds_bytes : h->lds_bytes, stream)
               : launch_direct((int)h->cfg.param_dtype, (int)h->cfg.grad_dtype, phase,
                               // where rows share sources the re-reads must find them in the cache
-                              h->nontemporal && !slot.reuse, a, w1 - w0, stream);
+                              h->nontemporal, slot.reuse, a, w1 - w0, stream);
   if (e == (int)hipSuccess && consensus_out) e = launch_consensus_sum(partials, consensus_out, stream);
   if (e != (int)hipSuccess)
     return fail(h, DADAM_EHIP, "kernel launch failed: %s", hipGetErrorString((hipError_t)e));
   return DADAM_OK;
 }
 
+// Rows in an order in which consecutive rows share as many sources as possible (greedy: from the current row
+// to the unvisited row that shares most sources with it, the lowest-numbered on a tie; when nothing is shared
+// any more, on to the lowest unvisited row).  A one-peer graph with hop h comes out as its chains
+// 0, h, 2h, ..., a ring as 0, 1, 2, ...  The direct kernels hand contiguous groups of this order to the dies.
+std::vector<int32_t> sharing_order(uint32_t R, uint32_t C, const int32_t* row_ptr, const int32_t* col) {
+  std::vector<std::vector<int32_t>> readers(C);
+  for (uint32_t i = 0; i < R; ++i)
+    for (int32_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) readers[col[k]].push_back((int32_t)i);
+  std::vector<int32_t> order;
+  std::vector<char> visited(R, 0);
+  std::vector<int32_t> shared(R);
+  uint32_t lowest = 0;
+  int32_t cur = 0;
+  while (true) {
+    order.push_back(cur);
+    visited[cur] = 1;
+    if (order.size() == R) break;
+    std::fill(shared.begin(), shared.end(), 0);
+    for (int32_t k = row_ptr[cur]; k < row_ptr[cur + 1]; ++k)
+      for (int32_t j : readers[col[k]])
+        if (!visited[j]) ++shared[j];
+    int32_t best = -1;
+    for (uint32_t j = 0; j < R; ++j)
+      if (shared[j] > 0 && (best < 0 || shared[j] > shared[best])) best = (int32_t)j;
+    if (best < 0) {
+      while (visited[lowest]) ++lowest;
+      best = (int32_t)lowest;
+    }
+    cur = best;
+  }
+  return order;
+}
+
 void free_slot(Slot& s) {
   if (s.d_row_ptr) (void)hipFree(s.d_row_ptr);
   if (s.d_col) (void)hipFree(s.d_col);
   if (s.d_w) (void)hipFree(s.d_w);
+  if (s.d_order) (void)hipFree(s.d_order);
   s = Slot();
 }
 
@@ -606,6 +654,8 @@ int dadam_set_topology(dadam_handle* h, uint32_t slot_id, const int32_t* row_ptr
   fresh.w.assign(w, w + nnz);
   fresh.reuse = reuse;
   fresh.sole_reader = sole;
+  for (uint32_t i = 0; i < R; ++i) fresh.max_degree = std::max(fresh.max_degree, row_ptr[i + 1] - row_ptr[i]);
+  if (reuse) fresh.order = sharing_order(R, C, row_ptr, col_idx);
   if (h->cfg.device != DADAM_DEVICE_NONE) {
     DeviceGuard guard(h->cfg.device);
     hipError_t e = guard.err;
@@ -615,6 +665,10 @@ int dadam_set_topology(dadam_handle* h, uint32_t slot_id, const int32_t* row_ptr
     if (e == hipSuccess) e = hipMemcpy(fresh.d_row_ptr, row_ptr, (R + 1) * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(fresh.d_col, col_idx, (size_t)nnz * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(fresh.d_w, w, (size_t)nnz * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !fresh.order.empty()) {
+      e = hipMalloc((void**)&fresh.d_order, R * sizeof(int32_t));
+      if (e == hipSuccess) e = hipMemcpy(fresh.d_order, fresh.order.data(), R * sizeof(int32_t), hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
       free_slot(fresh);
       return fail(h, DADAM_EHIP, "uploading the neighbour list failed: %s", hipGetErrorString(e));
@@ -827,6 +881,16 @@ int dadam_slot_uses_tile_mode(const dadam_handle* h, uint32_t slot) {
   int rc = choose_mode(h, h->slots[slot], 0, &tile);
   if (rc) return rc;
   return tile ? 1 : 0;
+}
+
+int dadam_get_row_order(const dadam_handle* h, uint32_t slot, int32_t* order_out) {
+  if (!h || !order_out) return DADAM_EINVAL;
+  if (slot >= DADAM_MAX_SLOTS || !h->slots[slot].set) return fail(h, DADAM_ESTATE, "topology slot %u is not set", slot);
+  const Slot& s = h->slots[slot];
+  const uint32_t R = h->cfg.n_rows;
+  const bool used = !s.order.empty() && h->n_xcds > 1 && R % h->n_xcds == 0;
+  for (uint32_t i = 0; i < R; ++i) order_out[i] = used ? s.order[i] : (int32_t)i;
+  return used ? 1 : 0;
 }
 
 int dadam_pack_offsets(const uint64_t* numel, uint32_t n, uint32_t align_elems, uint64_t* offsets, uint64_t* d_out) {

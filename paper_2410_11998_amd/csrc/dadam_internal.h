@@ -78,6 +78,10 @@ struct StepArgs {
   const int32_t* row_ptr;  // device CSR of the slot
   const int32_t* col;
   const float* w;
+  // Direct kernels: the rows in an order in which neighbours share sources (device; null: rows as numbered).
+  // The device's dies take contiguous groups of this order, so that the rows which read a source run on the
+  // die whose L2 already holds it.
+  const int32_t* row_order;
   const Segment* seg;  // device
   uint32_t n_seg;
   uint32_t n_rows, n_cols;
@@ -88,6 +92,8 @@ struct StepArgs {
   double* partials;           // kConsensusPartials doubles (device), used by kMixConsensus only
   Scalars s;
 };
+
+static_assert(sizeof(StepArgs) <= 4096, "the argument block of a launch holds 4 KB");
 
 typedef void (*KernelFn)(const StepArgs);
 
@@ -101,7 +107,8 @@ struct TileShape {
 // xdt / gdt are DADAM_F32 | DADAM_BF16.  n_work is the number of tiles in this launch.
 int launch_tile(int xdt, int gdt, Phase phase, TileShape shape, const StepArgs& a, uint32_t n_work,
                 uint32_t lds_bytes, void* stream);
-int launch_direct(int xdt, int gdt, Phase phase, bool nontemporal, const StepArgs& a,
+// shared: rows share sources; a streaming launch then keeps the hint off the source loads.
+int launch_direct(int xdt, int gdt, Phase phase, bool nontemporal, bool shared, const StepArgs& a,
                   uint32_t n_work_tiles, void* stream);
 // vec = elements per direct-mode parameter vector of the handle (fixes the tile grid).
 int launch_accumulate(int gdt, Phase phase, bool nontemporal, const StepArgs& a, uint32_t n_work_tiles,

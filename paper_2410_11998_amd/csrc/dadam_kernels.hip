@@ -23,9 +23,9 @@ namespace dadam {
 // what the parts define
 #define DADAM_PART(name)                                       \
   KernelFn tile_kernel_##name(int phase, TileShape s);         \
-  KernelFn direct_kernel_##name(int phase);                    \
+  KernelFn direct_kernel_##name(int phase, bool shared);       \
   KernelFn tile_kernel_##name##_ext(int phase, TileShape s);   \
-  KernelFn direct_kernel_##name##_ext(int phase)
+  KernelFn direct_kernel_##name##_ext(int phase, bool shared)
 DADAM_PART(f32_f32_nt);
 DADAM_PART(f32_f32);
 DADAM_PART(bf16_bf16_nt);
@@ -162,11 +162,12 @@ int launch_tile(int xdt, int gdt, Phase phase, TileShape shape, const StepArgs& 
   return launch(fn, n_work, (uint32_t)(kWave * shape.waves), lds_bytes, a, stream);
 }
 
-int launch_direct(int xdt, int gdt, Phase phase, bool nt, const StepArgs& a, uint32_t n_work_tiles, void* stream) {
+int launch_direct(int xdt, int gdt, Phase phase, bool nt, bool shared, const StepArgs& a, uint32_t n_work_tiles,
+                  void* stream) {
   KernelFn fn = nullptr;
   const bool ext = a.ext != nullptr;
-#define DADAM_PICK(name) (ext ? (nt ? direct_kernel_##name##_nt_ext(phase) : direct_kernel_##name##_ext(phase)) \
-                              : (nt ? direct_kernel_##name##_nt(phase) : direct_kernel_##name(phase)))
+#define DADAM_PICK(name) (ext ? (nt ? direct_kernel_##name##_nt_ext(phase, shared) : direct_kernel_##name##_ext(phase, shared)) \
+                              : (nt ? direct_kernel_##name##_nt(phase, shared) : direct_kernel_##name(phase, shared)))
   if (xdt == DADAM_F32 && gdt == DADAM_F32) fn = DADAM_PICK(f32_f32);
   if (xdt == DADAM_BF16 && gdt == DADAM_BF16) fn = DADAM_PICK(bf16_bf16);
   if (xdt == DADAM_BF16 && gdt == DADAM_F32) fn = DADAM_PICK(bf16_f32);

@@ -18,8 +18,11 @@ KernelFn DADAM_JOIN(tile_kernel_, DADAM_PART_NAME)(int phase, TileShape s) {
   return tile_kernel_for_shape_nt<DADAM_PART_XT, DADAM_PART_GT, DADAM_PART_NT, DADAM_PART_EXT>(phase, s);
 }
 
-KernelFn DADAM_JOIN(direct_kernel_, DADAM_PART_NAME)(int phase) {
-  return direct_kernel_for_phase<DADAM_PART_XT, DADAM_PART_GT, DADAM_PART_NT, DADAM_PART_EXT>(phase);
+// shared: rows share sources (a streaming part then keeps the hint off the source loads)
+KernelFn DADAM_JOIN(direct_kernel_, DADAM_PART_NAME)(int phase, bool shared) {
+  if (!DADAM_PART_NT) return direct_kernel_for_phase<DADAM_PART_XT, DADAM_PART_GT, 0, DADAM_PART_EXT>(phase);
+  return shared ? direct_kernel_for_phase<DADAM_PART_XT, DADAM_PART_GT, DADAM_PART_NT ? 2 : 0, DADAM_PART_EXT>(phase)
+                : direct_kernel_for_phase<DADAM_PART_XT, DADAM_PART_GT, DADAM_PART_NT ? 1 : 0, DADAM_PART_EXT>(phase);
 }
 
 }  // namespace dadam

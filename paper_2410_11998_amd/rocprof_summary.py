@@ -48,8 +48,9 @@ def parse_kernel(name: str):
     try:
         if kind == "k_tile":          # <param type, grad type, phase, waves, vectors, non-temporal>
             return f"k_tile<{args[0]},{args[1]},{args[3]},{args[4]},{args[5]}>", PHASES[int(args[2])]
-        if kind == "k_direct":        # <param type, grad type, phase, non-temporal>
-            return f"k_direct<{args[0]},{args[1]},{args[3]}>", PHASES[int(args[2])]
+        if kind == "k_direct":        # <param type, grad type, phase, hints: 0 none, 1 all, 2 all but the sources'>
+            hint = {"0": "false", "1": "true", "2": "shared"}.get(args[3], args[3])
+            return f"k_direct<{args[0]},{args[1]},{hint}>", PHASES[int(args[2])]
         return f"k_acc<{args[0]},{args[1]},{args[3]}>", PHASES[int(args[2])]     # <grad type, elements per vector, phase, nt>
     except (IndexError, KeyError, ValueError):
         return None, None

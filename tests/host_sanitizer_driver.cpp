@@ -12,7 +12,7 @@
 #include <random>
 namespace dadam {
 int launch_tile(int, int, Phase, TileShape, const StepArgs&, uint32_t, uint32_t, void*) { return 0; }
-int launch_direct(int, int, Phase, bool, const StepArgs&, uint32_t, void*) { return 0; }
+int launch_direct(int, int, Phase, bool, bool, const StepArgs&, uint32_t, void*) { return 0; }
 int launch_accumulate(int, Phase, bool, const StepArgs&, uint32_t, void*, int) { return 0; }
 int launch_consensus_zero(double*, void*) { return 0; }
 int launch_consensus_sum(const double*, double*, void*) { return 0; }

@@ -1002,9 +1002,10 @@ def test_dyadic_inputs_give_the_oracles_bits(mode, dtype, n):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_64_sources_with_and_without_room_for_the_tile(lds_limit, dtype):
     """The planner works from the LDS size the device reports (160 KB per workgroup on an MI355X): 64
-    sources need a 64 KB tile.  A handle limited to 32 KB cannot stage them and falls back to the direct
-    kernel although sources are shared.  Mixing and the fused step in both, against the oracle, on a
-    one-peer exponential graph of 64 replicas."""
+    sources need a 64 KB tile, which fits; a handle limited to 32 KB cannot stage them.  Rows of two sources
+    stream directly by choice either way (the dies take them in the sharing order), and the tile is there on
+    request.  Mixing and the fused step in every mode there is, against the oracle, on a one-peer exponential
+    graph of 64 replicas."""
     say("case", lds_limit, dtype)
     n = 64
     layout = WL.pack([("a", (9001,)), ("b", (257,)), ("c", (1030,))])
@@ -1015,7 +1016,9 @@ def test_64_sources_with_and_without_room_for_the_tile(lds_limit, dtype):
     say("plan: lds limit", info.lds_limit_bytes, "dies", info.n_xcds, "tile LDS", info.lds_bytes_tile, "tile mode", info.tile_mode_possible)
     if lds_limit == 0:
         assert info.lds_limit_bytes >= 65536 and info.n_xcds >= 1 and info.tile_mode_possible == 1
-        assert B.dadam_slot_uses_tile_mode(sim.h, 0)
+        assert B.dadam_slot_uses_tile_mode(sim.h, 0) is (info.n_xcds < 2 or n % info.n_xcds != 0)
+        order, used = B.dadam_get_row_order(sim.h, 0, n)
+        assert sorted(order) == list(range(n)) and used is (info.n_xcds > 1 and n % info.n_xcds == 0)
     else:
         assert info.lds_limit_bytes == 32768 and info.tile_mode_possible == 0
         assert not B.dadam_slot_uses_tile_mode(sim.h, 0)
@@ -1024,8 +1027,9 @@ def test_64_sources_with_and_without_room_for_the_tile(lds_limit, dtype):
     for c in range(n):
         sim.x_src[c].copy_(H.to_device(WL.normal_np(4100 + c, d, 0.5), dtype, DEV))
     mask = H.valid_mask(layout)
-    for slot in range(3):
-        sim.mix(slot)
+    modes = [0, B.DADAM_FORCE_DIRECT] + ([B.DADAM_FORCE_TILE] if lds_limit == 0 else [])
+    for slot, mode in [(s_, m_) for m_ in modes for s_ in range(3)]:
+        sim.mix(slot, mode)
         torch.cuda.synchronize()
         xs = sim._get(sim.x_src, None)
         csr = H.csr_oracle(csrs[slot])
@@ -1033,11 +1037,13 @@ def test_64_sources_with_and_without_room_for_the_tile(lds_limit, dtype):
         got = sim._get(sim.x_dst, None)
         for i in range(n):
             scale = sum(abs(csr.w[k]) * np.abs(xs[csr.col[k]]) for k in range(csr.row_ptr[i], csr.row_ptr[i + 1]))
-            assert np.all(np.abs(got[i] - ref[i])[mask] <= (H.RTOL[dtype] * scale)[mask]), f"slot {slot} row {i}"
+            assert np.all(np.abs(got[i] - ref[i])[mask] <= (H.RTOL[dtype] * scale)[mask]), f"slot {slot} mode {mode} row {i}"
         sim.swap()
     sim.close()
-    w = H.run_parity(f"onepeer64-lds{lds_limit}-{dtype}", n, n, layout, H.HyperF32(s=2), csrs, lambda t: (t - 1) % 3, 3, seed=130,
-                     param_dtype=dtype, grad_dtype=dtype, flags=B.DADAM_FUSE_ACCUM, pad_fill=None, lds_limit_bytes=lds_limit)
+    for mode in modes:
+        w = H.run_parity(f"onepeer64-lds{lds_limit}-mode{mode}-{dtype}", n, n, layout, H.HyperF32(s=2), csrs, lambda t: (t - 1) % 3, 3,
+                         seed=130, param_dtype=dtype, grad_dtype=dtype, flags=B.DADAM_FUSE_ACCUM | mode, pad_fill=None,
+                         lds_limit_bytes=lds_limit)
     say("worst error / tolerance:", w)
 
 

@@ -144,6 +144,24 @@ def test_set_topology_validation():
     assert B.dadam_slot_uses_tile_mode(h, 1) is False         # nothing shared: stream directly
     expect(B.DADAM_EINVAL, B.dadam_set_topology, h, 16, rp, col, w)
     expect(B.DADAM_ESTATE, B.dadam_slot_uses_tile_mode, h, 5)
+    # rows of two sources over more than 16 sources stream directly (the dies take them in the sharing order);
+    # three sources a row, few sources, rows that do not divide among the dies, or an in-place row: the tile
+    for n, csr, want in ((64, WL.one_peer_exponential(64, 0), False), (64, WL.one_peer_exponential(64, 5), False),
+                         (16, WL.one_peer_exponential(16, 1), True), (64, WL.ring(64), True)):
+        hh, _ = host_handle(n, n)
+        B.dadam_set_topology(hh, 0, *csr)
+        assert B.dadam_slot_uses_tile_mode(hh, 0) is want, (n, want)
+        B.dadam_destroy(hh)
+    hh, _ = host_handle(24, 24)                                   # 24 rows of two sources, 8 dies: divides -> direct
+    pair24 = (np.arange(0, 49, 2, dtype=np.int32), np.array([(i + o) % 24 for i in range(24) for o in (0, 1)], np.int32), np.full(48, 0.5, np.float32))
+    B.dadam_set_topology(hh, 0, *pair24)
+    assert B.dadam_slot_uses_tile_mode(hh, 0) is False
+    B.dadam_destroy(hh)
+    hh, _ = host_handle(20, 20)                                   # 20 rows do not divide among 8 dies -> tile
+    pair20 = (np.arange(0, 41, 2, dtype=np.int32), np.array([(i + o) % 20 for i in range(20) for o in (0, 1)], np.int32), np.full(40, 0.5, np.float32))
+    B.dadam_set_topology(hh, 0, *pair20)
+    assert B.dadam_slot_uses_tile_mode(hh, 0) is True
+    B.dadam_destroy(hh)
     bad = rp.copy(); bad[0] = 1
     expect(B.DADAM_ETOPO, B.dadam_set_topology, h, 2, bad, col, w)
     bad = rp.copy(); bad[2] = bad[1]
@@ -413,7 +431,11 @@ def test_kernels_use_no_scratch_memory_and_load_neighbour_lists_with_all_lanes(t
         if not m:
             continue
         targs = [x.strip() for x in m.group(2).split(",")]
-        nt, ext = targs[-2] == "true", targs[-1] == "true"     # <..., non-temporal, tables in device memory>
+        nt, ext = targs[-2] in ("true", "1", "2"), targs[-1] == "true"     # <..., hints, tables in device memory>
+        if targs[-2] == "2":               # direct kernel for rows that share sources: source loads stay plain
+            streaming += 1
+            assert st_plain == 0 and st_nt > 0 and ld_plain > 0, f"{plain}: stores {st_nt}/{st_plain}, loads {ld_nt}/{ld_plain}"
+            continue
         if nt:
             streaming += 1
             assert st_plain == 0 and st_nt > 0, f"{plain}: {st_plain} vector stores without the hint"
@@ -586,6 +608,52 @@ def test_two_region_placement_policy():
     assert B.lib.dadam_place_offsets(None, 1, 100, 100, None, None, None) == B.DADAM_EINVAL
     with pytest.raises(B.DadamError):
         B.dadam_place_offsets([5 << 20, 5 << 20], 8 << 20, 288 * GIB)
+
+
+def test_rows_that_share_sources_are_neighbours_in_direct_modes_row_order():
+    """Direct mode hands contiguous groups of a row order to the device's dies; in that order rows that share a
+    source follow each other, so that one die's L2 serves the second reader.  The order is a permutation, used
+    only when rows share sources and divide evenly among the dies, and follows the chains of a one-peer graph."""
+    def order_of(n, csr, **kw):
+        L = WL.pack([("flat", (1000,))])
+        h = B.dadam_init(n, n, L.d, L.offsets, L.numels, device=B.DADAM_DEVICE_NONE, **kw)
+        B.dadam_set_topology(h, 0, *csr)
+        out = B.dadam_get_row_order(h, 0, n)
+        B.dadam_destroy(h)
+        return out
+    def shared(csr, i, j):
+        rp, col, _w = csr
+        return len(set(col[rp[i]:rp[i + 1]]) & set(col[rp[j]:rp[j + 1]]))
+    for k in range(6):                                               # hop 2^k on 64 replicas: chains 0, h, 2h, ...
+        csr = WL.one_peer_exponential(64, k)
+        order, used = order_of(64, csr)
+        assert used and sorted(order) == list(range(64))
+        hop = 1 << k
+        chain = 64 // hop
+        assert order[:chain] == [(j * hop) % 64 for j in range(chain)]
+        breaks = sum(1 for a, b in zip(order, order[1:]) if shared(csr, a, b) == 0)
+        assert breaks == hop - 1                                     # only where one chain ends and the next begins
+        # within every group of 8 (one die's share) at most the group's first row lacks a sharing predecessor
+        inside = sum(1 for g in range(8) for a, b in zip(order[8 * g:8 * g + 8], order[8 * g + 1:8 * g + 8]) if shared(csr, a, b))
+        assert inside >= 56 - max(0, hop - 8) - 7 * (hop >= 8) - 7 and inside >= 28
+    order, used = order_of(16, WL.ring(16))
+    assert used and sorted(order) == list(range(16)) and all(shared(WL.ring(16), a, b) >= 1 for a, b in zip(order, order[1:]))
+    assert order_of(16, WL.identity(16)) == (list(range(16)), False)     # nothing shared
+    assert order_of(12, WL.ring(12)) == (list(range(12)), False)         # 12 rows do not divide among 8 dies
+    order, used = order_of(12, WL.ring(12), n_xcds=4)                    # ... but among 4
+    assert used and sorted(order) == list(range(12))
+    rng = np.random.default_rng(3)
+    for n in (8, 40, 160):                                               # random rows: still a permutation
+        rp, col, w = [0], [], []
+        for i in range(n):
+            deg = int(rng.integers(1, 6))
+            cs = rng.choice(n, size=deg, replace=False)
+            col += [int(c) for c in cs]; w += [1.0 / deg] * deg; rp.append(len(col))
+        order, _used = order_of(n, (np.array(rp, np.int32), np.array(col, np.int32), np.array(w, np.float32)))
+        assert sorted(order) == list(range(n))
+    h, _ = host_handle(4, 4)
+    expect(B.DADAM_ESTATE, B.dadam_get_row_order, h, 3, 4)
+    B.dadam_destroy(h)
 
 
 def test_dealing_buffers_over_two_given_regions():
