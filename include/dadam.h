@@ -78,8 +78,9 @@ extern "C" {
 
 /* flags of dadam_gossip_step.  Without a FORCE flag the library chooses: tile mode when some source is read
  * by two or more rows and the tile fits in LDS (also when an in-place row needs it), direct mode otherwise -
- * and also for rows of at most two sources on more than 16 sources when n_rows is a multiple of the die count
- * (see dadam_get_row_order; measured faster there).  dadam_slot_uses_tile_mode reports the choice. */
+ * and also, where measured faster, for rows of at most two sources on more than 16 sources and for rows of at
+ * most eight sources when a CU would hold only one workgroup of the tile (see dadam_get_row_order).
+ * dadam_slot_uses_tile_mode reports the choice. */
 #define DADAM_FUSE_ACCUM 1u   /* also do lines 9-13 (accumulate and fold) in the same pass         */
 #define DADAM_FORCE_DIRECT 2u /* every row streams its sources from global memory                  */
 #define DADAM_FORCE_TILE 4u   /* stage each source tile once in LDS and update all rows from it    */
@@ -252,7 +253,7 @@ int dadam_get_plan_info(const dadam_handle* h, dadam_plan_info* out);
 int dadam_slot_uses_tile_mode(const dadam_handle* h, uint32_t slot);
 
 /* The order in which direct mode takes the rows of this slot (order_out: n_rows entries, a permutation of
- * 0 .. n_rows-1).  When rows share sources and n_rows is a multiple of the device's die count, rows that
+ * 0 .. n_rows-1).  When rows share sources (and the device has more than one die), rows that
  * share sources are neighbours in this order and each die works on one contiguous group of it, so that a
  * source two rows read comes from memory once and from that die's L2 the second time (one-peer graph on 64
  * replicas, mixing only: 0.54-0.61 of peak with rows as numbered when the two readers sit on different dies,

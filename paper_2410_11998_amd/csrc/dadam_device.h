@@ -798,16 +798,21 @@ __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
   const uint32_t n_rows = a.n_rows;
   uint32_t t;
   int row;
+  bool active = true;
   if (a.row_order != nullptr) {
     // Rows share sources.  Consecutive workgroup ids go to the device's X dies in turn; die x takes the
-    // rows at positions [x G, (x + 1) G) of the sharing order, G = n_rows / X (the host passes the order
-    // only when that divides), tile after tile: the rows that read a source run on one die at about the
-    // same time, and the second reader finds the source in that die's L2.  (b mod X, b / X) -> (die, tile
-    // and position in the group) is a bijection of the launch's n_tiles * n_rows workgroups.
-    const uint32_t X = a.n_xcd, G = n_rows / X;
+    // rows at positions [x R / X, (x + 1) R / X) of the sharing order (R = n_rows), tile after tile: the
+    // rows that read a source run on one die at about the same time, and the second reader finds the
+    // source in that die's L2.  Every die gets G = ceil(R / X) workgroups per tile; where R / X is not whole,
+    // the last workgroup of some dies has no row and does nothing (the whole workgroup, so no lane leaves
+    // a wavefront early).
+    const uint32_t X = a.n_xcd, G = a.order_group;
     const uint32_t x = blockIdx.x % X, j = blockIdx.x / X;
     t = j / G;
-    row = __builtin_amdgcn_readfirstlane(a.row_order[x * G + (j - t * G)]);
+    const uint32_t q = j - t * G;
+    const uint32_t first = x * n_rows / X, count = (x + 1) * n_rows / X - first;
+    active = q < count;
+    row = __builtin_amdgcn_readfirstlane(a.row_order[active ? first + q : 0]);
   } else {
     t = blockIdx.x / n_rows;
     row = (int)(blockIdx.x - t * n_rows);
@@ -817,8 +822,10 @@ __global__ __launch_bounds__(kDirectThreads) void k_direct(const StepArgs a) {
   locate(a, a.work_begin + t, tile_index, lo, hi, wd);
   const uint64_t tbase = tile_index * TILE;
   const bool full = tbase >= lo && tbase + TILE <= hi;
-  if (full) direct_body<XT, GT, PHASE, false, HINT, EXT>(a, row, tbase, lo, hi, wd, lane);
-  else direct_body<XT, GT, PHASE, true, HINT, EXT>(a, row, tbase, lo, hi, wd, lane);
+  if (active) {  // uniform over the workgroup
+    if (full) direct_body<XT, GT, PHASE, false, HINT, EXT>(a, row, tbase, lo, hi, wd, lane);
+    else direct_body<XT, GT, PHASE, true, HINT, EXT>(a, row, tbase, lo, hi, wd, lane);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -173,7 +173,7 @@ int plan(dadam_handle* h) {
   h->n_work_t = wt;
   h->n_work_d = wd;
   h->n_work_m = wm;
-  if (wt > 0x7fffffffull || wd * h->cfg.n_rows > 0x7fffffffull)
+  if (wt > 0x7fffffffull || wd * (h->cfg.n_rows + h->n_xcds) > 0x7fffffffull)  // direct mode pads rows up to the dies
     return fail(nullptr, DADAM_EINVAL, "layout too large: more than 2^31-1 work items");
   return DADAM_OK;
 }
@@ -261,8 +261,11 @@ void fill_args(const dadam_handle* h, const Slot* slot, const void* const* grads
     a->row_ptr = slot->d_row_ptr;
     a->col = slot->d_col;
     a->w = slot->d_w;
-    // groups of the order go to the dies in turn: only when the rows divide evenly among them
-    if (slot->d_order && h->n_xcds > 1 && R % h->n_xcds == 0) a->row_order = slot->d_order;
+    // the dies take contiguous groups of the sharing order in turn
+    if (slot->d_order && h->n_xcds > 1) {
+      a->row_order = slot->d_order;
+      a->order_group = (R + h->n_xcds - 1) / h->n_xcds;
+    }
   }
   a->seg = h->d_segs;
   a->n_seg = (uint32_t)h->segs.size();
@@ -318,14 +321,17 @@ int choose_mode(const dadam_handle* h, const Slot& slot, uint32_t flags, bool* t
       return fail(h, DADAM_EALIAS, "in-place update of a source that another row reads needs tile mode");
     *tile_mode = false;
   } else {
-    // Shared sources normally mean tile mode.  The exception, measured on 64 replicas of a one-peer graph
-    // (mixing 0.77 against 0.75 of peak, the whole step 0.792 against 0.788): rows of at most two sources over
-    // more sources than the two-vector tile holds stream directly, the dies taking the rows in the sharing
-    // order so that the second reader of a source finds it in its die's L2.  With three sources a row (a
-    // ring) the tile is as fast or faster, so the exception stops at two.
-    const bool pairs_stream = slot.reuse && direct_legal && slot.max_degree <= 2 && h->cfg.n_cols > 16 &&
-                              h->n_xcds > 1 && h->cfg.n_rows % h->n_xcds == 0;
-    *tile_mode = h->tile_possible && ((slot.reuse && !pairs_stream) || !direct_legal);
+    // Shared sources normally mean tile mode.  Two exceptions, where the rows stream directly and the dies
+    // take them in the sharing order, so that the second reader of a source finds it in its die's L2:
+    // (1) rows of at most two sources over more sources than the two-vector tile holds (64 replicas of a
+    // one-peer graph: mixing 0.77 against 0.75 of peak, the whole step 0.792 against 0.788; with three
+    // sources a row, a ring, the tile is as fast or faster);
+    // (2) a tile so large that a CU holds one workgroup of it (more than 80 sources on 160 KB), with rows of
+    // at most eight sources (128 replicas: the step 0.76-0.79 against 0.48-0.49, mixing 0.50-0.74 against 0.40).
+    const bool ordered = slot.reuse && direct_legal && h->n_xcds > 1;
+    const bool pairs_stream = ordered && slot.max_degree <= 2 && h->cfg.n_cols > 16;
+    const bool lone_tile = ordered && slot.max_degree <= 8 && 2 * (uint64_t)h->lds_bytes > h->lds_limit;
+    *tile_mode = h->tile_possible && ((slot.reuse && !pairs_stream && !lone_tile) || !direct_legal);
     if (!*tile_mode && !direct_legal)
       return fail(h, DADAM_EALIAS, "in-place update of a shared source is impossible: tile does not fit in LDS");
   }
@@ -888,7 +894,7 @@ int dadam_get_row_order(const dadam_handle* h, uint32_t slot, int32_t* order_out
   if (slot >= DADAM_MAX_SLOTS || !h->slots[slot].set) return fail(h, DADAM_ESTATE, "topology slot %u is not set", slot);
   const Slot& s = h->slots[slot];
   const uint32_t R = h->cfg.n_rows;
-  const bool used = !s.order.empty() && h->n_xcds > 1 && R % h->n_xcds == 0;
+  const bool used = !s.order.empty() && h->n_xcds > 1;
   for (uint32_t i = 0; i < R; ++i) order_out[i] = used ? s.order[i] : (int32_t)i;
   return used ? 1 : 0;
 }

@@ -82,6 +82,8 @@ struct StepArgs {
   // The device's dies take contiguous groups of this order, so that the rows which read a source run on the
   // die whose L2 already holds it.
   const int32_t* row_order;
+  uint32_t order_group;  // with row_order: rows per die, ceil(n_rows / n_xcd); the launch has n_xcd * order_group
+                         // workgroups per tile, of which those beyond a die's share of the rows have nothing to do
   const Segment* seg;  // device
   uint32_t n_seg;
   uint32_t n_rows, n_cols;

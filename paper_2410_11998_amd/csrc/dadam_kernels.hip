@@ -173,7 +173,9 @@ int launch_direct(int xdt, int gdt, Phase phase, bool nt, bool shared, const Ste
   if (xdt == DADAM_BF16 && gdt == DADAM_F32) fn = DADAM_PICK(bf16_f32);
   if (xdt == DADAM_F32 && gdt == DADAM_BF16) fn = DADAM_PICK(f32_bf16);
 #undef DADAM_PICK
-  return launch(fn, n_work_tiles * a.n_rows, kDirectThreads, 0, a, stream);
+  // with a sharing order every die gets the same number of workgroups per tile (see k_direct)
+  const uint32_t per_tile = a.row_order != nullptr ? a.n_xcd * a.order_group : a.n_rows;
+  return launch(fn, n_work_tiles * per_tile, kDirectThreads, 0, a, stream);
 }
 
 int launch_accumulate(int gdt, Phase phase, bool nt, const StepArgs& a, uint32_t n_work_tiles, void* stream,
@@ -188,7 +190,9 @@ int launch_accumulate(int gdt, Phase phase, bool nt, const StepArgs& a, uint32_t
   if (gdt == DADAM_BF16 && vec == 4) fn = DADAM_PICK(TBF16, 4);
   if (gdt == DADAM_BF16 && vec == 8) fn = DADAM_PICK(TBF16, 8);
 #undef DADAM_PICK
-  return launch(fn, n_work_tiles * a.n_rows, kDirectThreads, 0, a, stream);
+  // with a sharing order every die gets the same number of workgroups per tile (see k_direct)
+  const uint32_t per_tile = a.row_order != nullptr ? a.n_xcd * a.order_group : a.n_rows;
+  return launch(fn, n_work_tiles * per_tile, kDirectThreads, 0, a, stream);
 }
 
 }  // namespace dadam

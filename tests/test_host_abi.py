@@ -148,7 +148,7 @@ def test_set_topology_validation():
     # three sources a row, few sources, rows that do not divide among the dies, or an in-place row: the tile
     for n, csr, want in ((64, WL.one_peer_exponential(64, 0), False), (64, WL.one_peer_exponential(64, 5), False),
                          (16, WL.one_peer_exponential(16, 1), True), (64, WL.ring(64), True)):
-        hh, _ = host_handle(n, n)
+        hh, _ = host_handle(n, n, lds_limit_bytes=160 * 1024)        # the device's figure (a host-only handle assumes 64 KB)
         B.dadam_set_topology(hh, 0, *csr)
         assert B.dadam_slot_uses_tile_mode(hh, 0) is want, (n, want)
         B.dadam_destroy(hh)
@@ -157,11 +157,18 @@ def test_set_topology_validation():
     B.dadam_set_topology(hh, 0, *pair24)
     assert B.dadam_slot_uses_tile_mode(hh, 0) is False
     B.dadam_destroy(hh)
-    hh, _ = host_handle(20, 20)                                   # 20 rows do not divide among 8 dies -> tile
+    hh, _ = host_handle(20, 20)                                   # 20 rows over 8 dies (groups of 2 and 3): direct as well
     pair20 = (np.arange(0, 41, 2, dtype=np.int32), np.array([(i + o) % 20 for i in range(20) for o in (0, 1)], np.int32), np.full(40, 0.5, np.float32))
     B.dadam_set_topology(hh, 0, *pair20)
-    assert B.dadam_slot_uses_tile_mode(hh, 0) is True
+    assert B.dadam_slot_uses_tile_mode(hh, 0) is False
     B.dadam_destroy(hh)
+    # a tile of which a CU holds one workgroup (more than half of the LDS): rows of up to eight sources stream
+    for n, csr, lds, want in ((100, WL.ring(100), 160 * 1024, False), (80, WL.ring(80), 160 * 1024, True),
+                              (100, WL.complete(100), 160 * 1024, True), (40, WL.ring(40), 64 * 1024, False)):
+        hh, _ = host_handle(n, n, lds_limit_bytes=lds)
+        B.dadam_set_topology(hh, 0, *csr)
+        assert B.dadam_slot_uses_tile_mode(hh, 0) is want, (n, lds, want)
+        B.dadam_destroy(hh)
     bad = rp.copy(); bad[0] = 1
     expect(B.DADAM_ETOPO, B.dadam_set_topology, h, 2, bad, col, w)
     bad = rp.copy(); bad[2] = bad[1]
@@ -639,9 +646,9 @@ def test_rows_that_share_sources_are_neighbours_in_direct_modes_row_order():
     order, used = order_of(16, WL.ring(16))
     assert used and sorted(order) == list(range(16)) and all(shared(WL.ring(16), a, b) >= 1 for a, b in zip(order, order[1:]))
     assert order_of(16, WL.identity(16)) == (list(range(16)), False)     # nothing shared
-    assert order_of(12, WL.ring(12)) == (list(range(12)), False)         # 12 rows do not divide among 8 dies
-    order, used = order_of(12, WL.ring(12), n_xcds=4)                    # ... but among 4
+    order, used = order_of(12, WL.ring(12))                              # 12 rows over 8 dies: groups of 1 or 2
     assert used and sorted(order) == list(range(12))
+    assert order_of(12, WL.ring(12), n_xcds=1) == (list(range(12)), False)   # one die: nothing to deal
     rng = np.random.default_rng(3)
     for n in (8, 40, 160):                                               # random rows: still a permutation
         rp, col, w = [0], [], []
