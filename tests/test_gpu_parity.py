@@ -1052,7 +1052,7 @@ def test_64_sources_with_and_without_room_for_the_tile(lds_limit, dtype):
 # ---------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("case", ["aer96-tile", "aer96-direct", "complete96-tile", "complete96-direct", "ring160-tile-bf16",
-                                  "share-1x100-direct", "rect-70x130-tile"])
+                                  "share-1x100-direct", "rect-70x130-tile", "ring100-auto", "pairs100-auto-bf16"])
 def test_more_than_64_rows_or_sources(case):
     """Beyond 64 rows or sources the tables of the bound buffers live in device memory (one immutable copy
     per binding) and a row may list more neighbours than a wavefront has lanes.  An Alternating
@@ -1062,7 +1062,7 @@ def test_more_than_64_rows_or_sources(case):
     say("case", case)
     layout = WL.pack([("a", (3001,)), ("b", (7,)), ("c", (515,))])
     rng = np.random.default_rng(77)
-    dtype, mode, inplace, refresh = "f32", "tile" if "tile" in case else "direct", False, False
+    dtype, mode, inplace, refresh = "f32", "tile" if "tile" in case else "auto" if "auto" in case else "direct", False, False
     slot_of_t = lambda t: 0
     if case.startswith("aer96"):
         R = C = 96
@@ -1074,6 +1074,13 @@ def test_more_than_64_rows_or_sources(case):
     elif case.startswith("ring160"):
         R = C = 160
         csrs, dtype = [WL.ring(160)], "bf16"
+    elif case.startswith("ring100") or case.startswith("pairs100"):
+        # 100 rows over 8 dies: the planner streams them (a CU would hold one workgroup of the 100 KB tile), the
+        # dies take groups of 12 and 13 rows of the sharing order and four workgroups per tile stay idle
+        R = C = 100
+        csrs = [WL.ring(100)] if case.startswith("ring") else [dyadic_rows(100, (0, 1), (0.5, 0.5)), dyadic_rows(100, (0, 7), (0.5, 0.5))]
+        dtype = "bf16" if case.endswith("bf16") else "f32"
+        slot_of_t = lambda t: (t - 1) % len(csrs)
     elif case.startswith("share"):
         R, C = 1, 100
         csrs, inplace, refresh = [WL._uniform_rows([list(range(100))])], True, True
@@ -1088,6 +1095,12 @@ def test_more_than_64_rows_or_sources(case):
             col += list(cols); w += list(ww); row_ptr.append(len(col))
         csrs, refresh = [(np.array(row_ptr, np.int32), np.array(col, np.int32), np.array(w, np.float32))], True
     T = 5 if len(csrs) > 1 else 3
+    if mode == "auto":
+        hh = B.dadam_init(R, C, layout.d, layout.offsets, layout.numels, device=0)
+        B.dadam_set_topology(hh, 0, *csrs[0])
+        order, used = B.dadam_get_row_order(hh, 0, R)
+        assert B.dadam_slot_uses_tile_mode(hh, 0) is False and used and sorted(order) == list(range(R))
+        B.dadam_destroy(hh)
     w_ = H.run_parity(case, R, C, layout, H.HyperF32(lr=2e-3, s=2), csrs, slot_of_t, T, seed=140, param_dtype=dtype,
                       grad_dtype=dtype, grad_std=1e-2, flags=B.DADAM_FUSE_ACCUM | MODES[mode], inplace=inplace,
                       refresh_extra_sources=refresh, pad_fill=None)
