@@ -145,14 +145,14 @@ def test_set_topology_validation():
     expect(B.DADAM_EINVAL, B.dadam_set_topology, h, 16, rp, col, w)
     expect(B.DADAM_ESTATE, B.dadam_slot_uses_tile_mode, h, 5)
     # rows of two sources over more than 16 sources stream directly (the dies take them in the sharing order);
-    # three sources a row, few sources, rows that do not divide among the dies, or an in-place row: the tile
+    # three sources a row or few sources: the tile
     for n, csr, want in ((64, WL.one_peer_exponential(64, 0), False), (64, WL.one_peer_exponential(64, 5), False),
                          (16, WL.one_peer_exponential(16, 1), True), (64, WL.ring(64), True)):
         hh, _ = host_handle(n, n, lds_limit_bytes=160 * 1024)        # the device's figure (a host-only handle assumes 64 KB)
         B.dadam_set_topology(hh, 0, *csr)
         assert B.dadam_slot_uses_tile_mode(hh, 0) is want, (n, want)
         B.dadam_destroy(hh)
-    hh, _ = host_handle(24, 24)                                   # 24 rows of two sources, 8 dies: divides -> direct
+    hh, _ = host_handle(24, 24)                                   # 24 rows of two sources: direct
     pair24 = (np.arange(0, 49, 2, dtype=np.int32), np.array([(i + o) % 24 for i in range(24) for o in (0, 1)], np.int32), np.full(48, 0.5, np.float32))
     B.dadam_set_topology(hh, 0, *pair24)
     assert B.dadam_slot_uses_tile_mode(hh, 0) is False
@@ -620,7 +620,7 @@ def test_two_region_placement_policy():
 def test_rows_that_share_sources_are_neighbours_in_direct_modes_row_order():
     """Direct mode hands contiguous groups of a row order to the device's dies; in that order rows that share a
     source follow each other, so that one die's L2 serves the second reader.  The order is a permutation, used
-    only when rows share sources and divide evenly among the dies, and follows the chains of a one-peer graph."""
+    only when rows share sources and there is more than one die, and follows the chains of a one-peer graph."""
     def order_of(n, csr, **kw):
         L = WL.pack([("flat", (1000,))])
         h = B.dadam_init(n, n, L.d, L.offsets, L.numels, device=B.DADAM_DEVICE_NONE, **kw)
