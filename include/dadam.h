@@ -322,6 +322,72 @@ int dadam_place_offsets(const uint64_t* nbytes, uint32_t n, uint64_t arena_bytes
 int dadam_deal_offsets(const uint64_t* nbytes, uint32_t n, uint64_t lo0, uint64_t hi0, uint64_t lo1, uint64_t hi1,
                        uint32_t every, uint64_t* offsets);
 
+/* Layout advice for HBM, part 4: finding the thirds by measurement.
+ *
+ * Where the thirds of the physical memory begin inside a caller's allocation cannot be computed (a large
+ * allocation is pieced together from whatever is free: made first, its bytes [0, 96 GiB) lie in one third; made
+ * after 100 GiB of other allocations, the second boundary was seen at 160 GiB), but it can be measured: the
+ * library's mixing pass over sixteen 64 MiB sources and sixteen outputs runs at 0.78-0.80 of peak when half of
+ * its buffers sit in one third and half in another, and at 0.61-0.73 when all sit in one.
+ *
+ * dadam_find_stretches: the bookkeeping.  `rate(off_a, off_b, ctx)` is the fraction of peak a streaming pass
+ * sustains with half of its buffers in the DADAM_PROBE_CHUNK_BYTES at arena offset off_a and half in those at
+ * off_b (negative: failure, reported as DADAM_EHIP).  One chunk every DADAM_PROBE_STEP_BYTES is compared with a
+ * reference chunk; those that run fast with it (>= 0.95 of the fastest pairing, which must itself reach 0.75)
+ * lie in another third; a second reference among them tells the other two thirds apart.  out receives at most
+ * DADAM_MAX_STRETCHES stretches [lo, hi) with the id (0, 1, 2) of their third, in address order; the same third
+ * may come back later in the arena.  More stretches than that is noise: the timing is repeated once, then
+ * *n_out = 0.  An arena too small for three chunks also gives *n_out = 0.  Host only.
+ *
+ * dadam_regions_from_stretches: the two regions (regions_out[4] = lo0, hi0, lo1, hi1) to deal the buffers
+ * over with dadam_deal_offsets and its `every`: alternately (every = 2) over the two stretches of different
+ * thirds with the most room if half of the buffers fit each, otherwise every 3rd, 4th, 6th or 8th buffer in
+ * the smaller stretch (160 / 200 GiB allocated before the arena: 0.75 / 0.73 of peak against 0.60 / 0.64 at
+ * equal distances).  Returns 1 if found, 0 if no two stretches of different thirds hold the buffers.
+ *
+ * dadam_place_by_timing: the whole procedure on a device.  `arena` is DEVICE memory (2 MiB aligned,
+ * arena_bytes long, contents are overwritten: call it before anything is stored there).  The library times
+ * its own pass over the arena (about half a second, some hundreds of short launches on the null stream, 2 GiB
+ * of temporary device memory), finds the stretches, chooses the regions, confirms them with one more pass
+ * across the two regions and one inside each, and deals the buffers; if that yields nothing it falls back to
+ * dadam_place_offsets (device_total_bytes is passed on).  offsets[n] and *report say what was done.  Synchronous.
+ * Errors: DADAM_EINVAL, DADAM_EALIGN, DADAM_EHIP. */
+#define DADAM_PROBE_CHUNK_BYTES 1073741824ull
+#define DADAM_PROBE_STEP_BYTES 4294967296ull
+#define DADAM_MAX_STRETCHES 6u
+#define DADAM_POLICY_TIMED_REGIONS 1u  /* two regions found by timing, dealt with report.every             */
+#define DADAM_POLICY_RULE_REGIONS 2u   /* dadam_place_offsets' two regions (arena covers the device)        */
+#define DADAM_POLICY_EQUAL_DISTANCES 3u
+#define DADAM_NOTE_NO_PROBE 1u         /* arena too small for the probe, one buffer only, or no 2 GiB to spare */
+#define DADAM_NOTE_NO_PICTURE 2u       /* the timings gave no consistent picture of the thirds              */
+#define DADAM_NOTE_NO_ROOM 3u          /* no two stretches of different thirds hold the buffers             */
+#define DADAM_NOTE_NOT_CONFIRMED 4u    /* the confirming passes disagreed with the stretches                */
+typedef double (*dadam_pair_rate_fn)(uint64_t off_a, uint64_t off_b, void* ctx);
+typedef struct {
+  uint32_t third;    /* 0, 1, 2: stretches with the same id share a third */
+  uint32_t reserved; /* 0 */
+  uint64_t lo, hi;   /* arena offsets */
+} dadam_stretch;
+typedef struct {
+  uint32_t policy;         /* DADAM_POLICY_* */
+  uint32_t advice;         /* DADAM_PLACE_* as dadam_place_offsets reports it */
+  uint32_t every;          /* DADAM_POLICY_TIMED_REGIONS: every `every`-th buffer lies in the second region */
+  uint32_t note;           /* 0, or why the timing was not used: DADAM_NOTE_* */
+  uint32_t n_stretches;
+  uint32_t probe_launches; /* mixing passes the probe launched */
+  dadam_stretch stretches[DADAM_MAX_STRETCHES];
+  uint64_t regions[4];     /* lo0, hi0, lo1, hi1 (lo1 = hi1 = 0: one region) */
+  float rate_across;       /* fraction of peak of the confirming pass across the regions, 0 if none ran */
+  float rate_inside[2];    /* ... and inside each region */
+  uint32_t reserved;
+} dadam_placement;
+int dadam_find_stretches(uint64_t arena_bytes, dadam_pair_rate_fn rate, void* ctx, dadam_stretch* out,
+                         uint32_t* n_out);
+int dadam_regions_from_stretches(const dadam_stretch* stretches, uint32_t n_stretches, const uint64_t* nbytes,
+                                 uint32_t n, uint64_t* regions_out, uint32_t* every_out);
+int dadam_place_by_timing(void* arena, uint64_t arena_bytes, int32_t device, const uint64_t* nbytes, uint32_t n,
+                          uint64_t device_total_bytes, uint64_t* offsets, dadam_placement* report);
+
 /* Text of the last error recorded on this handle ("" if none).  With h == NULL: the text of the
  * last dadam_init failure of the calling thread.  The pointer stays valid until the next call on
  * the same handle (thread). */

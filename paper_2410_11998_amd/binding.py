@@ -34,7 +34,8 @@ DADAM_PLACE_TWO_REGIONS, DADAM_PLACE_ARENA_ELSEWHERE, DADAM_PLACE_TOO_LARGE = 1,
 EXPORTS = [
     "dadam_init", "dadam_set_topology", "dadam_bind", "dadam_swap_x", "dadam_gossip_step",
     "dadam_gossip_step_range", "dadam_accumulate", "dadam_mix", "dadam_mix_consensus", "dadam_mix_consensus_static", "dadam_set_lr", "dadam_get_plan_info",
-    "dadam_slot_uses_tile_mode", "dadam_get_row_order", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_place_offsets", "dadam_deal_offsets",
+    "dadam_slot_uses_tile_mode", "dadam_get_row_order", "dadam_pack_offsets", "dadam_spread_offsets", "dadam_place_offsets", "dadam_deal_offsets", "dadam_find_stretches", "dadam_regions_from_stretches",
+    "dadam_place_by_timing",
     "dadam_last_error",
     "dadam_destroy",
 ]
@@ -69,6 +70,22 @@ class dadam_plan_info(C.Structure):
                 ("mix_vectors", C.c_uint32), ("streaming", C.c_uint32)]
 
 
+PROBE_CHUNK_BYTES, PROBE_STEP_BYTES, MAX_STRETCHES = 1 << 30, 4 << 30, 6
+DADAM_POLICY_TIMED_REGIONS, DADAM_POLICY_RULE_REGIONS, DADAM_POLICY_EQUAL_DISTANCES = 1, 2, 3
+DADAM_NOTE_NO_PROBE, DADAM_NOTE_NO_PICTURE, DADAM_NOTE_NO_ROOM, DADAM_NOTE_NOT_CONFIRMED = 1, 2, 3, 4
+PAIR_RATE_FN = C.CFUNCTYPE(C.c_double, C.c_uint64, C.c_uint64, C.c_void_p)
+
+
+class dadam_stretch(C.Structure):
+    _fields_ = [("third", C.c_uint32), ("reserved", C.c_uint32), ("lo", C.c_uint64), ("hi", C.c_uint64)]
+
+
+class dadam_placement(C.Structure):
+    _fields_ = [("policy", C.c_uint32), ("advice", C.c_uint32), ("every", C.c_uint32), ("note", C.c_uint32),
+                ("n_stretches", C.c_uint32), ("probe_launches", C.c_uint32), ("stretches", dadam_stretch * MAX_STRETCHES),
+                ("regions", C.c_uint64 * 4), ("rate_across", C.c_float), ("rate_inside", C.c_float * 2), ("reserved", C.c_uint32)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2410_11998_amd.build); "
@@ -92,6 +109,11 @@ def _load() -> C.CDLL:
     lib.dadam_spread_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.POINTER(C.c_uint64)]
     lib.dadam_place_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64,
                                         C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
+    lib.dadam_find_stretches.argtypes = [C.c_uint64, PAIR_RATE_FN, C.c_void_p, C.POINTER(dadam_stretch), C.POINTER(C.c_uint32)]
+    lib.dadam_regions_from_stretches.argtypes = [C.POINTER(dadam_stretch), C.c_uint32, C.POINTER(C.c_uint64), C.c_uint32,
+                                                 C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]
+    lib.dadam_place_by_timing.argtypes = [C.c_void_p, C.c_uint64, C.c_int32, C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64,
+                                          C.POINTER(C.c_uint64), C.POINTER(dadam_placement)]
     lib.dadam_get_row_order.argtypes = [H, C.c_uint32, C.POINTER(C.c_int32)]
     lib.dadam_deal_offsets.argtypes = [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64,
                                        C.c_uint32, C.POINTER(C.c_uint64)]
@@ -187,6 +209,42 @@ def dadam_place_offsets(nbytes: Sequence[int], arena_bytes: int, device_total_by
         raise DadamError(rc, f"dadam_place_offsets: {n} buffers of {sum(int(x) for x in nbytes)} bytes do not fit in {arena_bytes}")
     regions = [(int(r[0]), int(r[1]))] + ([(int(r[2]), int(r[3]))] if r[3] else [])
     return [int(x) for x in o], regions, int(adv.value)
+
+
+def dadam_find_stretches(arena_bytes: int, rate):
+    """Stretches [(third id, lo, hi)] of an arena from pair timings; rate(off_a, off_b) -> fraction of peak."""
+    out = (dadam_stretch * MAX_STRETCHES)()
+    n = C.c_uint32(0)
+    cb = PAIR_RATE_FN(lambda a, b, _ctx: float(rate(int(a), int(b))))
+    rc = lib.dadam_find_stretches(int(arena_bytes), cb, None, out, C.byref(n))
+    if rc < 0:
+        raise DadamError(rc, "dadam_find_stretches failed")
+    return [(int(out[k].third), int(out[k].lo), int(out[k].hi)) for k in range(n.value)]
+
+
+def dadam_regions_from_stretches(stretches, nbytes: Sequence[int]):
+    """((lo0, hi0), (lo1, hi1), every) for dadam_deal_offsets, or None."""
+    st = (dadam_stretch * max(1, len(stretches)))()
+    for k, (t, lo, hi) in enumerate(stretches):
+        st[k].third, st[k].lo, st[k].hi = int(t), int(lo), int(hi)
+    a = (C.c_uint64 * len(nbytes))(*[int(x) for x in nbytes])
+    reg, every = (C.c_uint64 * 4)(), C.c_uint32(0)
+    rc = lib.dadam_regions_from_stretches(st, len(stretches), a, len(nbytes), reg, C.byref(every))
+    if rc < 0:
+        raise DadamError(rc, "dadam_regions_from_stretches failed")
+    return ((int(reg[0]), int(reg[1])), (int(reg[2]), int(reg[3])), int(every.value)) if rc == 1 else None
+
+
+def dadam_place_by_timing(arena_ptr: int, arena_bytes: int, device: int, nbytes: Sequence[int], device_total_bytes: int):
+    """(offsets, report): the buffers placed in a device arena by the library's timing probe (see include/dadam.h)."""
+    n = len(nbytes)
+    a = (C.c_uint64 * n)(*[int(x) for x in nbytes])
+    o = (C.c_uint64 * n)()
+    rep = dadam_placement()
+    rc = lib.dadam_place_by_timing(C.c_void_p(int(arena_ptr)), int(arena_bytes), int(device), a, n, int(device_total_bytes), o, C.byref(rep))
+    if rc < 0:
+        raise DadamError(rc, f"dadam_place_by_timing failed for {n} buffers in an arena of {arena_bytes} bytes")
+    return [int(x) for x in o], rep
 
 
 def dadam_get_row_order(h, slot: int, n_rows: int):

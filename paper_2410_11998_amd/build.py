@@ -26,7 +26,7 @@ LIB = os.path.join(HERE, "libdadam.so")
 
 TYPES = {"f32": "TF32", "bf16": "TBF16"}
 # (object name, source, extra definitions)
-UNITS = [("dadam_host", "dadam_host.cpp", []), ("dadam_kernels", "dadam_kernels.hip", [])]
+UNITS = [("dadam_host", "dadam_host.cpp", []), ("dadam_place", "dadam_place.cpp", []), ("dadam_kernels", "dadam_kernels.hip", [])]
 for _x in ("f32", "bf16"):
     for _g in ("f32", "bf16"):
         for _nt in (True, False):

@@ -120,6 +120,41 @@ int main() {
       if (o[k] < b[2 * r] || o[k] + sz[k] > b[2 * r + 1]) { printf("dealt out of its region\n"); return 1; }
     }
   }
+  // stretches from random pair timings (a model with thirds at a random base, noise, sometimes garbage), then
+  // regions from them: accepted regions lie inside stretches of different thirds and hold their shares
+  for (int it = 0; it < 200; ++it) {
+    struct Model { uint64_t base; int garbage; std::mt19937_64* rng; } m{(uint64_t)(rng() % 250) << 30, (int)(rng() % 6 == 0), &rng};
+    auto rate = [](uint64_t a, uint64_t b, void* ctx) -> double {
+      Model* mm = static_cast<Model*>(ctx);
+      if (mm->garbage) return ((*mm->rng)() % 100) / 100.0;
+      const uint64_t third = 96ull << 30;
+      const double r = ((a + mm->base) / third) % 3 != ((b + mm->base) / third) % 3 ? 0.79 : 0.66;
+      return r * (1.0 + 0.01 * ((int)((*mm->rng)() % 200) - 100) / 100.0);
+    };
+    const uint64_t span = (uint64_t)(rng() % 280) << 30;
+    dadam_stretch st[DADAM_MAX_STRETCHES];
+    uint32_t n_st = 99;
+    if (dadam_find_stretches(span, rate, &m, st, &n_st) != DADAM_OK || n_st > DADAM_MAX_STRETCHES) { printf("find_stretches failed\n"); return 1; }
+    for (uint32_t k = 0; k < n_st; ++k)
+      if (st[k].lo >= st[k].hi || st[k].hi > span || st[k].third > 2 || (k && st[k].lo < st[k - 1].hi)) { printf("bad stretch\n"); return 1; }
+    const uint32_t n = 1 + rng() % 120;
+    std::vector<uint64_t> sz(n), o(n);
+    for (auto& x : sz) x = 1 + rng() % (900u << 20);
+    uint64_t reg[4]; uint32_t every = 0;
+    const int found = dadam_regions_from_stretches(st, n_st, sz.data(), n, reg, &every);
+    if (found < 0) { printf("regions_from_stretches failed\n"); return 1; }
+    if (found == 1) {
+      ++n_ok;
+      if (dadam_deal_offsets(sz.data(), n, reg[0], reg[1], reg[2], reg[3], every, o.data()) != DADAM_OK) { printf("regions do not hold their shares\n"); return 1; }
+      int owner[2] = {-1, -1};
+      for (int r = 0; r < 2; ++r)
+        for (uint32_t k = 0; k < n_st; ++k)
+          if (reg[2 * r] >= st[k].lo && reg[2 * r + 1] <= st[k].hi) owner[r] = (int)st[k].third;
+      if (owner[0] < 0 || owner[1] < 0 || owner[0] == owner[1]) { printf("regions not inside stretches of different thirds\n"); return 1; }
+    } else {
+      ++n_err;
+    }
+  }
   printf("sanitizer driver finished: %d ok, %d rejected\n", n_ok, n_err);
   return 0;
 }

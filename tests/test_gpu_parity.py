@@ -474,7 +474,7 @@ def test_arena_finds_stretches_in_different_thirds_by_timing():
         H.record("arena_calibration", dict(first_gib=first_gib, stretches=[[t, lo >> 30, hi >> 30] for t, lo, hi in ar.stretches],
                                            regions=[[lo >> 30, hi >> 30] for lo, hi in ar.regions_used], policy=ar.policy))
         assert len(ar.stretches) >= 2 and len({t for t, _lo, _hi in ar.stretches}) >= 2
-        assert ar.policy.startswith("two regions found by timing") and ar.advice == B.DADAM_PLACE_TWO_REGIONS and ar.probe_rates
+        assert ar.policy.startswith("two regions found by timing") and ar.advice == B.DADAM_PLACE_TWO_REGIONS and ar.report.note == 0
         (lo0, hi0), (lo1, hi1) = ar.regions_used
         if ar.policy.startswith("two regions found by timing"):
             owner = lambda off: next(t for t, lo, hi in ar.stretches if lo <= off < hi)
@@ -485,15 +485,12 @@ def test_arena_finds_stretches_in_different_thirds_by_timing():
         # boundaries between thirds are 96 GiB apart wherever the arena starts
         cuts = [hi for _t, _lo, hi in ar.stretches[:-1]]
         if len(cuts) == 2:
-            assert abs((cuts[1] - cuts[0]) - (96 << 30)) <= 2 * A.PROBE_STEP
-        probe = A.ThirdsProbe(ar.storage, ar.base_offset)
-        across = probe.rate(lo0, hi1 - A.PROBE_CHUNK)
-        within = probe.rate(lo0, lo0 + (hi0 - lo0) // 2 // A.UNIT * A.UNIT)
-        probe.close()
+            assert abs((cuts[1] - cuts[0]) - (96 << 30)) <= 2 * B.PROBE_STEP_BYTES
+        across, within = float(ar.report.rate_across), [float(r) for r in ar.report.rate_inside]
         H.record("arena_calibration_rates", dict(first_gib=first_gib, across=across, within=within))
-        say("rates", f"across {across:.3f} within {within:.3f}")
-        assert across > within
-        del ar, probe, first
+        say("rates", f"across {across:.3f} within {within}")
+        assert across >= 0.75 and all(0 < r < 0.95 * across for r in within) and ar.probe_launches > 500
+        del ar, first
         import gc
         gc.collect()
         torch.cuda.empty_cache()

@@ -490,6 +490,7 @@ def test_host_code_under_address_and_ub_sanitizers(tmp_path):
            "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2410_11998_amd", "csrc"),
            "-I", "/opt/rocm/include", os.path.join(ROOT, "tests", "host_sanitizer_driver.cpp"),
            os.path.join(ROOT, "paper_2410_11998_amd", "csrc", "dadam_host.cpp"),
+           os.path.join(ROOT, "paper_2410_11998_amd", "csrc", "dadam_place.cpp"),
            "-L/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib", "-o", exe]
     r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stderr[-2000:]
@@ -690,17 +691,18 @@ def test_dealing_buffers_over_two_given_regions():
 
 
 def test_thirds_are_found_from_timings_of_a_modelled_memory():
-    """The arena's search for stretches in different thirds of the memory, run against a model of the device:
+    """The library's search for stretches in different thirds of the memory (dadam_find_stretches,
+    dadam_regions_from_stretches), run against a model of the device in place of its timing probe:
     physical position = arena offset + a base, a pass over two chunks sustains 0.79 of peak across thirds and
     0.73 or 0.65 (alternating 8 GiB bands) inside one, with 1 % noise.  Whatever the base, the stretches found
     are those of the model, and the two regions chosen lie in different thirds with room for the buffers."""
-    from paper_2410_11998_amd import arena as A
+    CHUNK = B.PROBE_CHUNK_BYTES
     GIB = 1 << 30
     rng = np.random.default_rng(5)
 
     def model(base):
         def third(off):
-            return ((off + base) // (96 * GIB)) % 3, (off + base) % (96 * GIB) + A.PROBE_CHUNK > 96 * GIB
+            return ((off + base) // (96 * GIB)) % 3, (off + base) % (96 * GIB) + CHUNK > 96 * GIB
         def rate(a, b):
             (ta, sa), (tb, sb) = third(a), third(b)
             r = 0.79 if ta != tb else (0.73 if ((a + base) // (8 * GIB) + (b + base) // (8 * GIB)) % 2 == 0 else 0.65)
@@ -715,23 +717,21 @@ def test_thirds_are_found_from_timings_of_a_modelled_memory():
     seen_every = set()
     for base_gib, span_gib in ((0, 275), (40, 235), (70, 200), (100, 170), (190, 90), (3, 60), (50, 100), (75, 60), (20, 90)):
         base, span = base_gib * GIB, span_gib * GIB
-        runs = A.stretches_in_different_thirds(span, model(base))
+        runs = B.dadam_find_stretches(span, model(base))
         assert runs and runs[0][1] == 0
         for t, lo, hi in runs:                                       # each stretch lies in one third (up to one chunk of overlap)
-            assert third_of(lo, base) == third_of(hi - 1 - A.PROBE_CHUNK, base), (base_gib, runs)
+            assert third_of(lo, base) == third_of(hi - 1 - CHUNK, base), (base_gib, runs)
         firsts = {third_of(lo, base) for _t, lo, _hi in runs}
-        assert len(runs) == len(firsts) == third_of(span - A.PROBE_CHUNK, base) - third_of(0, base) + 1, (base_gib, runs)
+        assert len(runs) == len(firsts) == third_of(span - CHUNK, base) - third_of(0, base) + 1, (base_gib, runs)
         assert len({t for t, _lo, _hi in runs}) == len(runs)
-        cands = A.region_candidates(runs, sizes)
-        assert [c[2] for c in cands] == sorted({c[2] for c in cands}) and (not cands or cands[0] == A.two_regions_from_stretches(runs, sizes))
-        found = A.two_regions_from_stretches(runs, sizes)
+        found = B.dadam_regions_from_stretches(runs, sizes)
         room = sorted(hi - lo for _t, lo, hi in runs)
         if len(runs) >= 2 and room[-1] >= sum(sizes) * 7 // 8 + (1 << 30) and room[-2] >= sum(sizes) // 8 + (1 << 30):
             (lo0, hi0), (lo1, hi1), every = found
             seen_every.add(every)
             off = B.dadam_deal_offsets(sizes, (lo0, hi0), (lo1, hi1), every)      # fits
-            assert third_of(lo0, base) == third_of(hi0 - 1 - A.PROBE_CHUNK, base) if lo0 < lo1 else third_of(lo0 + A.PROBE_CHUNK, base) == third_of(hi0 - 1, base)
-            assert third_of(lo1 + A.PROBE_CHUNK, base) == third_of(hi1 - 1, base) if lo0 < lo1 else third_of(lo1, base) == third_of(hi1 - 1 - A.PROBE_CHUNK, base)
+            assert third_of(lo0, base) == third_of(hi0 - 1 - CHUNK, base) if lo0 < lo1 else third_of(lo0 + CHUNK, base) == third_of(hi0 - 1, base)
+            assert third_of(lo1 + CHUNK, base) == third_of(hi1 - 1, base) if lo0 < lo1 else third_of(lo1, base) == third_of(hi1 - 1 - CHUNK, base)
             assert third_of((lo0 + hi0) // 2, base) != third_of((lo1 + hi1) // 2, base)
             assert hi0 - lo0 <= 64 * GIB and hi1 - lo1 <= 64 * GIB
             assert min(hi0, hi1) <= max(lo0, lo1)
@@ -743,18 +743,18 @@ def test_thirds_are_found_from_timings_of_a_modelled_memory():
             assert found is None
     assert seen_every >= {2} and len(seen_every) >= 2, seen_every
     # a memory with no fast pairing at all: one stretch, no regions
-    runs = A.stretches_in_different_thirds(100 * GIB, lambda a, b: 0.66)
-    assert len(runs) == 1 and A.two_regions_from_stretches(runs, sizes) is None
-    assert A.stretches_in_different_thirds(5 * GIB, lambda a, b: 0.79) == []
+    runs = B.dadam_find_stretches(100 * GIB, lambda a, b: 0.66)
+    assert len(runs) == 1 and B.dadam_regions_from_stretches(runs, sizes) is None
+    assert B.dadam_find_stretches(5 * GIB, lambda a, b: 0.79) == []
     # timings that make no sense (a fast pairing here and there): nothing is believed
     noisy = np.random.default_rng(1)
-    assert A.stretches_in_different_thirds(200 * GIB, lambda a, b: 0.79 if noisy.uniform() < 0.5 else 0.65) == []
+    assert B.dadam_find_stretches(200 * GIB, lambda a, b: 0.79 if noisy.uniform() < 0.5 else 0.65) == []
     # a third that comes back later in the arena (an allocation pieced together from fragments) is accepted
     def fragments(a, b):
         piece = lambda off: 0 if off < 40 * GIB else 1 if off < 90 * GIB else 0
         return 0.79 if piece(a) != piece(b) else 0.66
-    runs = A.stretches_in_different_thirds(130 * GIB, fragments)
-    assert [t for t, _lo, _hi in runs] == [0, 1, 0] and A.two_regions_from_stretches(runs, sizes) is not None
+    runs = B.dadam_find_stretches(130 * GIB, fragments)
+    assert [t for t, _lo, _hi in runs] == [0, 1, 0] and B.dadam_regions_from_stretches(runs, sizes) is not None
 
 
 def test_device_access_helpers_on_the_cpu_under_sanitizers(tmp_path):
