@@ -32,7 +32,9 @@
  *   - "host" / "device" says where a pointer must point.  Large buffers (parameters, gradients,
  *     moments, accumulator) are DEVICE memory owned by the caller; the library never allocates,
  *     frees or copies them and never synchronises a stream.  The library owns only small metadata
- *     (segment table, CSR slots) on host and device.
+ *     (segment table, CSR slots) on host and device.  (One set-up call is the exception and says so:
+ *     dadam_place_by_timing overwrites the empty arena it is given, holds 2 GiB of its own while it runs
+ *     and returns when its measurements are done.)
  *   - Launching entry points enqueue work on the given HIP stream (a hipStream_t passed as
  *     void*; NULL = the default stream) and return at once.  The caller keeps every buffer alive
  *     and unmodified until that work has finished.
