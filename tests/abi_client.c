@@ -6,8 +6,20 @@
 
 #include "dadam.h"
 
+/* pair timings of a memory whose thirds begin at arena offsets 40 and 136 GiB */
+static double model_rate(uint64_t a, uint64_t b, void* ctx) {
+  const uint64_t gib = 1024ull * 1024ull * 1024ull;
+  const int ta = a < 40 * gib ? 0 : a < 136 * gib ? 1 : 2, tb = b < 40 * gib ? 0 : b < 136 * gib ? 1 : 2;
+  (void)ctx;
+  return ta != tb ? 0.79 : 0.66;
+}
+
 int main(void) {
   dadam_tensor_desc tensors[3];
+  dadam_stretch stretches[DADAM_MAX_STRETCHES];
+  uint32_t n_stretches = 0u, every = 0u;
+  uint64_t sizes[8], regions[4], placed[8];
+  int32_t order[4];
   uint64_t numel[3] = {1000, 24, 5001};
   uint64_t offsets[3];
   uint64_t d = 0;
@@ -68,6 +80,23 @@ int main(void) {
   printf("n_tiles_tile %llu\n", (unsigned long long)info.n_tiles_tile);
   printf("n_tiles_direct %llu\n", (unsigned long long)info.n_tiles_direct);
   printf("lds_bytes_tile %u\n", info.lds_bytes_tile);
+
+  rc = dadam_get_row_order(h, 0u, order);
+  printf("row_order_rc %d\n", rc);
+  printf("row_order %d%d%d%d\n", (int)order[0], (int)order[1], (int)order[2], (int)order[3]);
+
+  /* placement bookkeeping with a model in place of the device's timings */
+  rc = dadam_find_stretches(200ull << 30, model_rate, NULL, stretches, &n_stretches);
+  printf("stretches_rc %d\n", rc);
+  printf("n_stretches %u\n", n_stretches);
+  for (i = 0; i < 8; ++i) sizes[i] = 3ull << 30;
+  rc = dadam_regions_from_stretches(stretches, n_stretches, sizes, 8u, regions, &every);
+  printf("regions_found %d\n", rc);
+  printf("every %u\n", every);
+  rc = dadam_deal_offsets(sizes, 8u, regions[0], regions[1], regions[2], regions[3], every, placed);
+  printf("deal_rc %d\n", rc);
+  printf("first_in_region0 %d\n", placed[0] >= regions[0] && placed[0] + sizes[0] <= regions[1]);
+  printf("second_in_region1 %d\n", placed[1] >= regions[2] && placed[1] + sizes[1] <= regions[3]);
 
   /* a host-only handle cannot launch: an error code, not a crash */
   rc = dadam_mix(h, 0u, 0u, NULL);

@@ -569,6 +569,10 @@ def test_c99_client_compiles_links_and_agrees_with_the_binding(tmp_path):
     assert int(got["plan_rc"]) == 0
     for key in ("n_segments", "tile_elems", "n_tiles_tile", "n_tiles_direct", "lds_bytes_tile"):
         assert int(got[key]) == int(getattr(info, key)), key
+    assert int(got["row_order_rc"]) == 1 and sorted(got["row_order"]) == list("0123")
+    assert int(got["stretches_rc"]) == 0 and int(got["n_stretches"]) == 3 and int(got["regions_found"]) == 1
+    assert int(got["every"]) == 2 and int(got["deal_rc"]) == 0
+    assert int(got["first_in_region0"]) == 1 and int(got["second_in_region1"]) == 1
     assert int(got["mix_on_host_only_handle_rc"]) == B.DADAM_ESTATE
     assert int(got["set_lr_rc"]) == 0 and int(got["done"]) == 1
 
