@@ -737,11 +737,13 @@ def test_free_running_distance_from_the_unrounded_iteration(dtype):
     sim.close()
 
 
-def test_step_sequence_can_be_captured_in_a_graph_and_replayed():
+@pytest.mark.parametrize("consensus", ["handle", "static"])
+def test_step_sequence_can_be_captured_in_a_graph_and_replayed(consensus):
     """Callers that capture their loop: the library's calls are kernel launches only (no allocation, no
     synchronisation, no memset), so an accumulation loop and a mixing pass with the consensus error
     can be recorded once and replayed.  Every replay (with eager work and synchronisations between
-    them) must reproduce the eager results bit for bit."""
+    them) must reproduce the eager results bit for bit.  The consensus pass once with the handle's own
+    partial sums and once through the entry point that keeps them in the library's device image."""
     n, s = 8, 2
     layout = WL.pack(WL.odd_shapes())
     d = layout.d
@@ -765,7 +767,10 @@ def test_step_sequence_can_be_captured_in_a_graph_and_replayed():
         for t in range(1, s + 1):
             sim.step(grads[t - 1], t)
             sim.swap()
-        sim.mix_consensus(cons)          # reads the loop's result, writes the other buffer set
+        if consensus == "handle":        # reads the loop's result, writes the other buffer set
+            sim.mix_consensus(cons)
+        else:
+            B.dadam_mix_consensus_static(sim.h, 0, cons, 0, sim.stream())
         # an even number of exchanges: the handle's tables are back where they were
 
     def results():
