@@ -272,6 +272,7 @@ void fill_args(const dadam_handle* h, const Slot* slot, const void* const* grads
   a->n_rows = R;
   a->n_cols = C;
   a->n_xcd = h->n_xcds;
+  a->xcd_block = (uint32_t)env_int("DADAM_XCD_BLOCK", (int)kDieBlockTiles);
 }
 
 // Scalars of iteration t (Algorithm 3 lines 4 and 8), computed in double and rounded once.

@@ -90,12 +90,15 @@ struct StepArgs {
   uint32_t grid;        // Grid: which tile numbering work items refer to
   uint32_t work_begin;  // first work item (in tiles) of this launch
   uint32_t n_xcd;       // dies that consecutive workgroup ids are dealt over (tile order)
+  uint32_t xcd_block;   // tile mode: tiles per block; blocks go to the dies in turn (0: one contiguous share each)
   uint64_t clip_lo, clip_hi;  // element range of this launch (whole layout or a tensor range)
   double* partials;           // kConsensusPartials doubles (device), used by kMixConsensus only
   Scalars s;
 };
 
 static_assert(sizeof(StepArgs) <= 4096, "the argument block of a launch holds 4 KB");
+
+constexpr uint32_t kDieBlockTiles = 32;  // measured, see k_tile
 
 typedef void (*KernelFn)(const StepArgs);
 

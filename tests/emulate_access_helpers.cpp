@@ -87,7 +87,41 @@ void sweep(const char* name) {
   printf("%-44s %s\n", name, fails == before ? "ok" : "FAILED"); fflush(stdout);
 }
 
+// The maps from workgroup id to work item: every item exactly once, whatever the sizes.
+static void work_orders() {
+  int bad = 0;
+  for (uint32_t X : {1u, 4u, 8u})
+    for (uint32_t n : {1u, 7u, 8u, 9u, 63u, 64u, 257u, 1000u, 4099u})
+      for (uint32_t B : {0u, 1u, 3u, 32u, 100u, 5000u}) {
+        std::vector<int> seen(n, 0);
+        for (uint32_t b = 0; b < n; ++b) {
+          const uint32_t t = die_block_order(b, n, X, B);
+          if (t >= n) { ++bad; continue; }
+          ++seen[t];
+        }
+        for (uint32_t t = 0; t < n; ++t) bad += seen[t] != 1;
+      }
+  for (uint32_t X : {2u, 8u})
+    for (uint32_t R : {1u, 3u, 8u, 12u, 64u, 100u, 160u})
+      for (uint32_t T : {1u, 5u}) {
+        const uint32_t G = (R + X - 1) / X;
+        std::vector<int> seen(T * R, 0);
+        for (uint32_t b = 0; b < T * X * G; ++b) {
+          uint32_t tile = 0, pos = 0;
+          const bool active = die_group_order(b, R, X, G, tile, pos);
+          if (tile >= T || pos >= R) { ++bad; continue; }
+          if (active) ++seen[tile * R + pos];
+          // a die's rows are a contiguous group of the order
+          if (active && (pos < (b % X) * R / X || pos >= (b % X + 1) * R / X)) ++bad;
+        }
+        for (int c : seen) bad += c != 1;
+      }
+  printf("work orders %s\n", bad ? "FAIL" : "ok");
+  fails += bad;
+}
+
 int main() {
+  work_orders();
   sweep<TF32, TF32, kWave, kHalfWave, 1>("tile  x f32  state f32  UT1");
   sweep<TF32, TF32, kWave, kHalfWave, 2>("tile  x f32  state f32  UT2");
   sweep<TF32, TBF16, kWave, kHalfWave, 1>("tile  x f32  grad bf16 UT1");

@@ -763,8 +763,9 @@ def test_thirds_are_found_from_timings_of_a_modelled_memory():
 
 def test_device_access_helpers_on_the_cpu_under_sanitizers(tmp_path):
     """The kernels' vector load / store helpers (the lane-to-element layout, clipping at segment
-    edges, the two-group layout of 8-element lanes) compiled for the host from the kernel source's
-    own text and run on exact-size buffers under ASan + UBSan."""
+    edges, the two-group layout of 8-element lanes) and the maps from workgroup id to work item,
+    compiled for the host from the kernel source's own text and run on exact-size buffers under
+    ASan + UBSan."""
     import shutil
     import subprocess
     from paper_2410_11998_amd import build as bld
@@ -784,4 +785,4 @@ def test_device_access_helpers_on_the_cpu_under_sanitizers(tmp_path):
     env["ASAN_OPTIONS"] = "detect_leaks=0"
     r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=600)
     assert r.returncode == 0 and "fails 0" in r.stdout, (r.stdout[-1500:], r.stderr[-1500:])
-    assert r.stdout.count(" ok") == 10
+    assert r.stdout.count(" ok") == 11 and "work orders ok" in r.stdout
